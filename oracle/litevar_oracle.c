@@ -1,0 +1,359 @@
+/*
+ * litevar_oracle.c -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.
+ *
+ * Plain, slow, fp64 CPU statement of LiteVAR's multi-diagonal windowed
+ * attention (MDWA) with the optional CFG shared-output step (ASC).  Only the
+ * test-suite, the smoke check and the benchmark's cpu_baseline leg may call
+ * it.  It shares no code, header, table or helper with the HIP library.
+ *
+ * Everything here is written as the definition: a predicate allowed(q, t)
+ * evaluated for every key t, a max-subtracted softmax over the allowed keys,
+ * and a weighted sum of V rows.  No window tables, no tiling, no fusion.
+ *
+ * What the paper fixes (Section 2, "Multi-Diagonal Window Attention"):
+ *   - K scales, scale k holds s_k^2 tokens; a query of scale k sees the
+ *     tokens of scales 1..k (block-causal; same-scale tokens are mutually
+ *     visible).  Worked shape: k = 2 gives a [4, 5] attention map.
+ *   - the map is cut into per-key-scale parts and a local window of some
+ *     width is kept inside each part; a threshold of 1 means full attention.
+ *   - Section 2, "MDWA implementation details": the leading parts stay dense
+ *     (attention sinks) -> parameter n_sink.
+ *   - Section 3 (ASC): the unconditional branch reuses the conditional
+ *     branch's attention output.
+ * What the paper leaves open and the reading taken here:
+ *   - window geometry: a square (Chebyshev) window of radius r_j around the
+ *     query's position mapped into key scale j's s_j x s_j grid;
+ *   - position map: centre = floor((2c+1) s_j / (2 s_k)) per axis (integer);
+ *   - tokens of a scale are stored row-major (y major, x minor);
+ *   - masking happens before the softmax, so kept weights renormalise to 1;
+ *   - CFG layout: batch rows [0, B/2) conditional, b + B/2 the partner.
+ *
+ * Parity pins live in tests/ (golden worked example, closed-form pair
+ * counts, brute force in numpy, reduction to dense scaled-dot-product
+ * attention, softmax invariants).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define LVO_OK 0
+#define LVO_BAD_ARG (-1)
+#define LVO_NO_MEM (-2)
+#define LVO_CAP (-3)
+
+enum { LVO_F64 = 0, LVO_F32 = 1, LVO_BF16 = 2 };
+
+/* ---- geometry (Section 2: scale k has s_k^2 tokens) -------------------- */
+
+int64_t lvo_seq_len(int32_t K, const int32_t* scales) {
+  int64_t L = 0;
+  for (int32_t k = 0; k < K; ++k) L += (int64_t)scales[k] * scales[k];
+  return L;
+}
+
+/* first token of scale k in the flattened sequence */
+int64_t lvo_scale_offset(int32_t K, const int32_t* scales, int32_t k) {
+  int64_t o = 0;
+  for (int32_t i = 0; i < k && i < K; ++i) o += (int64_t)scales[i] * scales[i];
+  return o;
+}
+
+/* token t -> (scale, row, col); row-major inside the scale */
+int lvo_token_coords(int32_t K, const int32_t* scales, int64_t t,
+                     int32_t* k_out, int32_t* y_out, int32_t* x_out) {
+  if (t < 0) return LVO_BAD_ARG;
+  int64_t o = 0;
+  for (int32_t k = 0; k < K; ++k) {
+    int64_t n = (int64_t)scales[k] * scales[k];
+    if (t < o + n) {
+      int64_t local = t - o;
+      *k_out = k;
+      *y_out = (int32_t)(local / scales[k]);
+      *x_out = (int32_t)(local % scales[k]);
+      return LVO_OK;
+    }
+    o += n;
+  }
+  return LVO_BAD_ARG;
+}
+
+/* The predicate, on coordinates.  radii[j] < 0 means "no window in part j". */
+static int allowed_coords(const int32_t* scales, const int32_t* radii,
+                          int32_t n_sink, int32_t qk, int32_t qy, int32_t qx,
+                          int32_t kj, int32_t ky, int32_t kx) {
+  if (kj > qk) return 0;                 /* block-causal across scales */
+  if (kj < n_sink) return 1;             /* leading parts kept dense */
+  int32_t r = radii[kj];
+  if (r < 0) return 1;                   /* dense part */
+  int64_t sj = scales[kj], sk = scales[qk];
+  int64_t cy = ((2 * (int64_t)qy + 1) * sj) / (2 * sk);
+  int64_t cx = ((2 * (int64_t)qx + 1) * sj) / (2 * sk);
+  int64_t dy = (int64_t)ky - cy, dx = (int64_t)kx - cx;
+  if (dy < 0) dy = -dy;
+  if (dx < 0) dx = -dx;
+  return dy <= r && dx <= r;
+}
+
+/* allowed(q, t) on flattened token indices of the full sequence */
+int lvo_allowed(int32_t K, const int32_t* scales, const int32_t* radii,
+                int32_t n_sink, int64_t tq, int64_t tk) {
+  int32_t qk, qy, qx, kj, ky, kx;
+  if (lvo_token_coords(K, scales, tq, &qk, &qy, &qx) != LVO_OK) return LVO_BAD_ARG;
+  if (lvo_token_coords(K, scales, tk, &kj, &ky, &kx) != LVO_OK) return LVO_BAD_ARG;
+  return allowed_coords(scales, radii, n_sink, qk, qy, qx, kj, ky, kx);
+}
+
+typedef struct { int32_t k, y, x; } coord_t;
+
+static coord_t* coord_table(int32_t K, const int32_t* scales, int64_t L) {
+  coord_t* c = (coord_t*)malloc((size_t)(L > 0 ? L : 1) * sizeof(coord_t));
+  if (!c) return NULL;
+  for (int64_t t = 0; t < L; ++t)
+    lvo_token_coords(K, scales, t, &c[t].k, &c[t].y, &c[t].x);
+  return c;
+}
+
+static int check_desc(int32_t K, const int32_t* scales, const int32_t* radii,
+                      int32_t n_sink, int32_t qb, int32_t qe) {
+  if (K < 1 || !scales || !radii) return LVO_BAD_ARG;
+  for (int32_t k = 0; k < K; ++k) if (scales[k] < 1) return LVO_BAD_ARG;
+  if (n_sink < 0 || qb < 0 || qe > K || qb >= qe) return LVO_BAD_ARG;
+  return LVO_OK;
+}
+
+/* ---- masks and index sets --------------------------------------------- */
+
+/* dense byte mask [Lq][L]; rows are the queries of scales [qb, qe) */
+int lvo_mask_dense(int32_t K, const int32_t* scales, const int32_t* radii,
+                   int32_t n_sink, int32_t qb, int32_t qe, uint8_t* mask) {
+  if (check_desc(K, scales, radii, n_sink, qb, qe) || !mask) return LVO_BAD_ARG;
+  int64_t L = lvo_seq_len(K, scales);
+  int64_t q0 = lvo_scale_offset(K, scales, qb), q1 = lvo_scale_offset(K, scales, qe);
+  coord_t* c = coord_table(K, scales, L);
+  if (!c) return LVO_NO_MEM;
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t q = q0; q < q1; ++q)
+    for (int64_t t = 0; t < L; ++t)
+      mask[(q - q0) * L + t] = (uint8_t)allowed_coords(
+          scales, radii, n_sink, c[q].k, c[q].y, c[q].x, c[t].k, c[t].y, c[t].x);
+  free(c);
+  return LVO_OK;
+}
+
+/* per-query count of allowed keys: counts[Lq] */
+int lvo_row_counts(int32_t K, const int32_t* scales, const int32_t* radii,
+                   int32_t n_sink, int32_t qb, int32_t qe, int64_t* counts) {
+  if (check_desc(K, scales, radii, n_sink, qb, qe) || !counts) return LVO_BAD_ARG;
+  int64_t L = lvo_seq_len(K, scales);
+  int64_t q0 = lvo_scale_offset(K, scales, qb), q1 = lvo_scale_offset(K, scales, qe);
+  coord_t* c = coord_table(K, scales, L);
+  if (!c) return LVO_NO_MEM;
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t q = q0; q < q1; ++q) {
+    int64_t n = 0;
+    for (int64_t t = 0; t < L; ++t)
+      n += allowed_coords(scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
+                          c[t].k, c[t].y, c[t].x);
+    counts[q - q0] = n;
+  }
+  free(c);
+  return LVO_OK;
+}
+
+/* ascending index sets in CSR form: rowptr[Lq+1] (caller-filled from
+ * lvo_row_counts by prefix sum), cols[rowptr[Lq]] */
+int lvo_index_sets(int32_t K, const int32_t* scales, const int32_t* radii,
+                   int32_t n_sink, int32_t qb, int32_t qe,
+                   const int64_t* rowptr, int32_t* cols, int64_t cols_cap) {
+  if (check_desc(K, scales, radii, n_sink, qb, qe) || !rowptr || !cols) return LVO_BAD_ARG;
+  int64_t L = lvo_seq_len(K, scales);
+  int64_t q0 = lvo_scale_offset(K, scales, qb), q1 = lvo_scale_offset(K, scales, qe);
+  if (rowptr[q1 - q0] > cols_cap) return LVO_CAP;
+  coord_t* c = coord_table(K, scales, L);
+  if (!c) return LVO_NO_MEM;
+  int bad = 0;
+#pragma omp parallel for schedule(dynamic, 16)
+  for (int64_t q = q0; q < q1; ++q) {
+    int64_t w = rowptr[q - q0];
+    for (int64_t t = 0; t < L; ++t)
+      if (allowed_coords(scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
+                         c[t].k, c[t].y, c[t].x)) {
+        if (w < rowptr[q - q0 + 1]) cols[w] = (int32_t)t;
+        ++w;
+      }
+    if (w != rowptr[q - q0 + 1]) {
+#pragma omp atomic write
+      bad = 1;
+    }
+  }
+  free(c);
+  return bad ? LVO_BAD_ARG : LVO_OK;
+}
+
+/* ---- attention --------------------------------------------------------- */
+
+static double load_elem(const void* p, int32_t dtype, int64_t i) {
+  if (dtype == LVO_F64) return ((const double*)p)[i];
+  if (dtype == LVO_F32) return (double)((const float*)p)[i];
+  /* bf16: the upper half of an IEEE binary32 */
+  uint32_t bits = (uint32_t)((const uint16_t*)p)[i] << 16;
+  float f;
+  memcpy(&f, &bits, sizeof f);
+  return (double)f;
+}
+
+/*
+ * One softmax row, the textbook way: scores over allowed keys, subtract the
+ * maximum, exponentiate, normalise, weight V.  probs (optional, length L)
+ * receives the normalised weights, 0 for masked keys.
+ */
+static int attn_row(const int32_t* scales, const int32_t* radii, int32_t n_sink,
+                    const coord_t* c, int64_t L, int64_t tq,
+                    const double* qrow, const double* Kd, const double* Vd,
+                    int32_t D, double sm_scale, double* z, double* out, double* probs) {
+  double m = -INFINITY;
+  for (int64_t t = 0; t < L; ++t) {
+    if (!allowed_coords(scales, radii, n_sink, c[tq].k, c[tq].y, c[tq].x,
+                        c[t].k, c[t].y, c[t].x)) { z[t] = NAN; continue; }
+    double s = 0.0;
+    for (int32_t d = 0; d < D; ++d) s += qrow[d] * Kd[t * D + d];
+    z[t] = sm_scale * s;
+    if (z[t] > m) m = z[t];
+  }
+  double denom = 0.0;
+  for (int64_t t = 0; t < L; ++t)
+    if (!isnan(z[t])) { z[t] = exp(z[t] - m); denom += z[t]; }
+  for (int32_t d = 0; d < D; ++d) out[d] = 0.0;
+  for (int64_t t = 0; t < L; ++t) {
+    double p = isnan(z[t]) ? 0.0 : z[t] / denom;
+    if (probs) probs[t] = p;
+    if (p != 0.0)
+      for (int32_t d = 0; d < D; ++d) out[d] += p * Vd[t * D + d];
+  }
+  return LVO_OK;
+}
+
+/*
+ * q: [B,H,Lq,D], k,v: [B,H,L,D] packed, element type `dtype`;
+ * rows: optional list of n_rows query indices local to [0, Lq) (NULL = all);
+ * out: [B,H,n_rows,D] fp64.  bh_begin/bh_end restrict the (b*H+h) range
+ * (used to time or check a sample); rows outside it are left untouched.
+ */
+int lvo_attn(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
+             int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
+             int32_t dtype, int32_t B, int32_t H, int32_t D, double sm_scale,
+             int64_t n_rows, const int64_t* rows, int64_t bh_begin, int64_t bh_end,
+             double* out) {
+  if (check_desc(K, scales, radii, n_sink, qb, qe)) return LVO_BAD_ARG;
+  if (!q || !k || !v || !out || B < 1 || H < 1 || D < 1) return LVO_BAD_ARG;
+  if (dtype != LVO_F64 && dtype != LVO_F32 && dtype != LVO_BF16) return LVO_BAD_ARG;
+  int64_t L = lvo_seq_len(K, scales);
+  int64_t q0 = lvo_scale_offset(K, scales, qb), q1 = lvo_scale_offset(K, scales, qe);
+  int64_t Lq = q1 - q0;
+  if (!rows) n_rows = Lq;
+  if (n_rows < 0) return LVO_BAD_ARG;
+  if (rows) for (int64_t i = 0; i < n_rows; ++i)
+    if (rows[i] < 0 || rows[i] >= Lq) return LVO_BAD_ARG;
+  if (bh_begin < 0 || bh_end > (int64_t)B * H || bh_begin > bh_end) return LVO_BAD_ARG;
+  coord_t* c = coord_table(K, scales, L);
+  if (!c) return LVO_NO_MEM;
+  int err = 0;
+#pragma omp parallel
+  {
+    double* Kd = (double*)malloc((size_t)L * D * sizeof(double));
+    double* Vd = (double*)malloc((size_t)L * D * sizeof(double));
+    double* z = (double*)malloc((size_t)L * sizeof(double));
+    double* qrow = (double*)malloc((size_t)D * sizeof(double));
+    if (!Kd || !Vd || !z || !qrow) {
+#pragma omp atomic write
+      err = 1;
+    }
+#pragma omp barrier
+    if (!err) {
+#pragma omp for schedule(dynamic, 1)
+      for (int64_t bh = bh_begin; bh < bh_end; ++bh) {
+        for (int64_t i = 0; i < L * D; ++i) {
+          Kd[i] = load_elem(k, dtype, bh * L * D + i);
+          Vd[i] = load_elem(v, dtype, bh * L * D + i);
+        }
+        for (int64_t r = 0; r < n_rows; ++r) {
+          int64_t ql = rows ? rows[r] : r;
+          for (int32_t d = 0; d < D; ++d)
+            qrow[d] = load_elem(q, dtype, (bh * Lq + ql) * D + d);
+          attn_row(scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
+                   z, out + (bh * n_rows + r) * D, NULL);
+        }
+      }
+    }
+    free(Kd); free(Vd); free(z); free(qrow);
+  }
+  free(c);
+  return err ? LVO_NO_MEM : LVO_OK;
+}
+
+/* normalised weights of one (b,h,query) over all L keys: probs[L] fp64 */
+int lvo_attn_probs(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
+                   int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
+                   int32_t dtype, int32_t B, int32_t H, int32_t D, double sm_scale,
+                   int64_t bh, int64_t ql, double* probs, double* out_row) {
+  if (check_desc(K, scales, radii, n_sink, qb, qe)) return LVO_BAD_ARG;
+  if (!q || !k || !v || !probs || !out_row) return LVO_BAD_ARG;
+  int64_t L = lvo_seq_len(K, scales);
+  int64_t q0 = lvo_scale_offset(K, scales, qb), q1 = lvo_scale_offset(K, scales, qe);
+  int64_t Lq = q1 - q0;
+  if (bh < 0 || bh >= (int64_t)B * H || ql < 0 || ql >= Lq) return LVO_BAD_ARG;
+  coord_t* c = coord_table(K, scales, L);
+  double* Kd = (double*)malloc((size_t)L * D * sizeof(double));
+  double* Vd = (double*)malloc((size_t)L * D * sizeof(double));
+  double* z = (double*)malloc((size_t)L * sizeof(double));
+  double* qrow = (double*)malloc((size_t)D * sizeof(double));
+  int rc = LVO_NO_MEM;
+  if (c && Kd && Vd && z && qrow) {
+    for (int64_t i = 0; i < L * D; ++i) {
+      Kd[i] = load_elem(k, dtype, bh * L * D + i);
+      Vd[i] = load_elem(v, dtype, bh * L * D + i);
+    }
+    for (int32_t d = 0; d < D; ++d) qrow[d] = load_elem(q, dtype, (bh * Lq + ql) * D + d);
+    rc = attn_row(scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
+                  z, out_row, probs);
+  }
+  free(c); free(Kd); free(Vd); free(z); free(qrow);
+  return rc;
+}
+
+/*
+ * ASC (Section 3): for every (head h, query scale k) with share[h*K + k] != 0
+ * the unconditional row b + B/2 takes the conditional row b's output.
+ * o: [B,H,Lq,D] fp64, modified in place; Lq spans query scales [qb, qe).
+ */
+int lvo_cfg_share(int32_t K, const int32_t* scales, int32_t qb, int32_t qe,
+                  const uint8_t* share, int32_t B, int32_t H, int32_t D, double* o) {
+  if (K < 1 || !scales || qb < 0 || qe > K || qb >= qe || !share || !o) return LVO_BAD_ARG;
+  if (B < 2 || (B & 1)) return LVO_BAD_ARG;
+  int64_t q0 = lvo_scale_offset(K, scales, qb), q1 = lvo_scale_offset(K, scales, qe);
+  int64_t Lq = q1 - q0;
+  int32_t half = B / 2;
+  for (int32_t b = 0; b < half; ++b)
+    for (int32_t h = 0; h < H; ++h)
+      for (int32_t kq = qb; kq < qe; ++kq) {
+        if (!share[(int64_t)h * K + kq]) continue;
+        int64_t a = lvo_scale_offset(K, scales, kq) - q0;
+        int64_t n = (int64_t)scales[kq] * scales[kq];
+        double* src = o + (((int64_t)b * H + h) * Lq + a) * D;
+        double* dst = o + (((int64_t)(b + half) * H + h) * Lq + a) * D;
+        memcpy(dst, src, (size_t)(n * D) * sizeof(double));
+      }
+  return LVO_OK;
+}
+
+int lvo_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

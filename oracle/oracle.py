@@ -1,0 +1,193 @@
+"""ctypes front-end of oracle/litevar_oracle.c (test infrastructure only).
+
+Argument marshalling only; all arithmetic is in the C file.  Inputs may be
+float64 / float32 numpy arrays or uint16 arrays holding bf16 bit patterns.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        _lib = C.CDLL(path)
+        _lib.lvo_seq_len.restype = C.c_int64
+        _lib.lvo_scale_offset.restype = C.c_int64
+    return _lib
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def expand_radii(scales, radius, radius_per_key_scale=None):
+    """One radius per key scale; a negative radius means a dense part."""
+    K = len(scales)
+    if radius_per_key_scale is not None:
+        r = [int(x) for x in radius_per_key_scale]
+        assert len(r) == K
+        return r
+    return [int(radius)] * K
+
+
+def seq_len(scales):
+    s = _i32(scales)
+    return int(_L().lvo_seq_len(C.c_int32(len(s)), _p(s)))
+
+
+def scale_offsets(scales):
+    s = _i32(scales)
+    return [int(_L().lvo_scale_offset(C.c_int32(len(s)), _p(s), C.c_int32(k)))
+            for k in range(len(s) + 1)]
+
+
+def token_coords(scales, t):
+    s = _i32(scales)
+    k, y, x = C.c_int32(), C.c_int32(), C.c_int32()
+    rc = _L().lvo_token_coords(C.c_int32(len(s)), _p(s), C.c_int64(t),
+                               C.byref(k), C.byref(y), C.byref(x))
+    if rc:
+        raise ValueError("token out of range")
+    return k.value, y.value, x.value
+
+
+def allowed(scales, radii, n_sink, tq, tk):
+    s, r = _i32(scales), _i32(radii)
+    rc = _L().lvo_allowed(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                          C.c_int64(tq), C.c_int64(tk))
+    if rc < 0:
+        raise ValueError("token out of range")
+    return bool(rc)
+
+
+def _qrange(scales, q_scales):
+    K = len(scales)
+    qb, qe = (0, K) if q_scales is None else q_scales
+    off = scale_offsets(scales)
+    return qb, qe, off[qe] - off[qb]
+
+
+def mask_dense(scales, radii, n_sink=0, q_scales=None):
+    s, r = _i32(scales), _i32(radii)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    m = np.empty((Lq, seq_len(scales)), dtype=np.uint8)
+    rc = _L().lvo_mask_dense(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                             C.c_int32(qb), C.c_int32(qe), _p(m))
+    if rc:
+        raise ValueError(f"lvo_mask_dense failed: {rc}")
+    return m
+
+
+def row_counts(scales, radii, n_sink=0, q_scales=None):
+    s, r = _i32(scales), _i32(radii)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    cnt = np.empty(Lq, dtype=np.int64)
+    rc = _L().lvo_row_counts(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                             C.c_int32(qb), C.c_int32(qe), _p(cnt))
+    if rc:
+        raise ValueError(f"lvo_row_counts failed: {rc}")
+    return cnt
+
+
+def index_sets(scales, radii, n_sink=0, q_scales=None):
+    """(rowptr[Lq+1] int64, cols int32): ascending allowed keys of every query."""
+    s, r = _i32(scales), _i32(radii)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    cnt = row_counts(scales, radii, n_sink, q_scales)
+    rowptr = np.zeros(Lq + 1, dtype=np.int64)
+    np.cumsum(cnt, out=rowptr[1:])
+    cols = np.empty(int(rowptr[-1]), dtype=np.int32)
+    rc = _L().lvo_index_sets(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                             C.c_int32(qb), C.c_int32(qe), _p(rowptr), _p(cols),
+                             C.c_int64(cols.size))
+    if rc:
+        raise ValueError(f"lvo_index_sets failed: {rc}")
+    return rowptr, cols
+
+
+def _dtype_code(a):
+    if a.dtype == np.float64:
+        return 0
+    if a.dtype == np.float32:
+        return 1
+    if a.dtype == np.uint16:
+        return 2
+    raise TypeError("inputs must be float64, float32 or uint16 (bf16 bits)")
+
+
+def attn(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, rows=None,
+         bh_range=None):
+    """fp64 windowed attention.  q [B,H,Lq,D]; k,v [B,H,L,D]; returns [B,H,n_rows,D]."""
+    s, r = _i32(scales), _i32(radii)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    code = _dtype_code(q)
+    assert _dtype_code(k) == code and _dtype_code(v) == code
+    B, H, lq, D = q.shape
+    assert lq == Lq and k.shape == (B, H, seq_len(scales), D) and v.shape == k.shape
+    if rows is not None:
+        rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+        n_rows = rows.size
+    else:
+        n_rows = Lq
+    b0, b1 = (0, B * H) if bh_range is None else bh_range
+    out = np.zeros((B, H, n_rows, D), dtype=np.float64)
+    rc = _L().lvo_attn(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                       C.c_int32(qb), C.c_int32(qe), _p(q), _p(k), _p(v),
+                       C.c_int32(code), C.c_int32(B), C.c_int32(H), C.c_int32(D),
+                       C.c_double(sm_scale), C.c_int64(n_rows),
+                       _p(rows) if rows is not None else None,
+                       C.c_int64(b0), C.c_int64(b1), _p(out))
+    if rc:
+        raise ValueError(f"lvo_attn failed: {rc}")
+    return out
+
+
+def attn_probs(scales, radii, q, k, v, sm_scale, bh, ql, n_sink=0, q_scales=None):
+    """(probs[L], out[D]) of one (b*H+h, local query) pair, fp64."""
+    s, r = _i32(scales), _i32(radii)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    code = _dtype_code(q)
+    B, H, lq, D = q.shape
+    probs = np.zeros(seq_len(scales), dtype=np.float64)
+    out = np.zeros(D, dtype=np.float64)
+    rc = _L().lvo_attn_probs(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                             C.c_int32(qb), C.c_int32(qe), _p(q), _p(k), _p(v),
+                             C.c_int32(code), C.c_int32(B), C.c_int32(H), C.c_int32(D),
+                             C.c_double(sm_scale), C.c_int64(bh), C.c_int64(ql),
+                             _p(probs), _p(out))
+    if rc:
+        raise ValueError(f"lvo_attn_probs failed: {rc}")
+    return probs, out
+
+
+def cfg_share(scales, o, share, q_scales=None):
+    """In-place cond -> uncond copy of o [B,H,Lq,D] fp64 for share[H,K] != 0."""
+    s = _i32(scales)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    assert o.dtype == np.float64 and o.flags.c_contiguous
+    B, H, lq, D = o.shape
+    assert lq == Lq
+    share = np.ascontiguousarray(np.asarray(share, dtype=np.uint8))
+    assert share.shape == (H, len(s))
+    rc = _L().lvo_cfg_share(C.c_int32(len(s)), _p(s), C.c_int32(qb), C.c_int32(qe),
+                            _p(share), C.c_int32(B), C.c_int32(H), C.c_int32(D), _p(o))
+    if rc:
+        raise ValueError(f"lvo_cfg_share failed: {rc}")
+    return o
+
+
+def num_threads():
+    return int(_L().lvo_num_threads())

@@ -1,0 +1,52 @@
+"""Independent brute-force statement of the method in Python/numpy loops.
+
+Used only to pin the C oracle on small inputs.  Written from the definition
+(Section 2 of the paper plus the readings listed in the design notes), with
+its own token decoding, its own predicate and a dense masked softmax.
+"""
+import numpy as np
+
+
+def decode_tokens(scales):
+    """list of (scale index, row, col) for every token, row-major per scale."""
+    out = []
+    for k, s in enumerate(scales):
+        for y in range(s):
+            for x in range(s):
+                out.append((k, y, x))
+    return out
+
+
+def centre(c, s_from, s_to):
+    # centre-aligned nearest cell: pixel centre (c + 1/2) / s_from mapped to s_to cells
+    from fractions import Fraction
+    pos = (Fraction(c) + Fraction(1, 2)) / s_from * s_to
+    return int(pos // 1)
+
+
+def dense_mask(scales, radii, n_sink=0, q_scales=None):
+    toks = decode_tokens(scales)
+    qb, qe = (0, len(scales)) if q_scales is None else q_scales
+    qs = [i for i, (k, _, _) in enumerate(toks) if qb <= k < qe]
+    m = np.zeros((len(qs), len(toks)), dtype=bool)
+    for r, qi in enumerate(qs):
+        k, y, x = toks[qi]
+        for t, (j, yy, xx) in enumerate(toks):
+            if j > k:
+                continue
+            if j < n_sink or radii[j] < 0:
+                m[r, t] = True
+                continue
+            cy, cx = centre(y, scales[k], scales[j]), centre(x, scales[k], scales[j])
+            m[r, t] = max(abs(yy - cy), abs(xx - cx)) <= radii[j]
+    return m
+
+
+def masked_attention(q, k, v, mask, sm_scale):
+    """q [Lq,D], k,v [L,D] float64, mask [Lq,L] bool -> (out [Lq,D], probs [Lq,L])."""
+    z = sm_scale * (q @ k.T)
+    z = np.where(mask, z, -np.inf)
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    p = e / e.sum(axis=1, keepdims=True)
+    return p @ v, p

@@ -1,0 +1,324 @@
+"""Pins of the fp64 CPU oracle against things other than itself (CPU only).
+
+Each test is chosen so that a plausible slip in oracle/litevar_oracle.c -- a
+dropped clause of the predicate, a wrong centre map, a transposed row/column,
+softmax before masking, a wrong CFG partner -- fails at least one of them.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+from hypothesis import given, settings, strategies as st
+
+import oracle
+import workloads
+from _bruteforce import decode_tokens, dense_mask, masked_attention
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+VAR256 = workloads.CONFIGS["var_d16"].scales
+
+
+def _read_golden_rows():
+    rows, sums, totals = {}, None, {}
+    with open(os.path.join(GOLDEN, "tiny_r1_rows.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#") or line == "rows:":
+                continue
+            if line.startswith("row_sums:"):
+                sums = [int(x) for x in line.split(":")[1].split()]
+            elif ":" in line:
+                key, val = line.split(":")
+                totals[key.strip()] = int(val)
+            else:
+                idx, pat = line.split()
+                rows[int(idx)] = [c == "1" for c in pat.replace("|", "")]
+    return rows, sums, totals
+
+
+def _read_pair_counts():
+    totals, lists = {}, {}
+    with open(os.path.join(GOLDEN, "pair_counts.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if ":" in line:
+                key, val = line.split(":")
+                lists[key.strip()] = [int(x) for x in val.split()]
+            else:
+                name, kept, dense = line.split()
+                totals[name] = (int(kept), int(dense))
+    return totals, lists
+
+
+# ---- what the paper prints -------------------------------------------------
+
+def test_paper_shapes():
+    # Section 2: ten scales (1,2,3,4,5,6,8,10,13,16); sum of squares = 680 tokens
+    assert oracle.seq_len(VAR256) == 680
+    # Section 2: for k = 2 the attention map is [4, 5]
+    m = oracle.mask_dense(VAR256, [-1] * 10, 0, q_scales=(1, 2))
+    assert m.shape == (4, 680)
+    assert m[:, :5].all() and not m[:, 5:].any()
+    # Section 2, step (2): the first part spans the first three scales = 14 columns
+    assert oracle.scale_offsets(VAR256)[3] == 14
+
+
+def test_token_coords_row_major():
+    toks = decode_tokens((1, 2, 3, 4))
+    for t, kyx in enumerate(toks):
+        assert oracle.token_coords((1, 2, 3, 4), t) == kyx
+    with pytest.raises(ValueError):
+        oracle.token_coords((1, 2, 3, 4), 30)
+
+
+# ---- worked example ----------------------------------------------------------
+
+def test_golden_worked_example():
+    rows, sums, totals = _read_golden_rows()
+    scales = (1, 2, 3, 4)
+    m = oracle.mask_dense(scales, [1] * 4, 0)
+    assert m.shape == (30, 30)
+    for qi, pat in rows.items():
+        assert m[qi].astype(bool).tolist() == pat, f"row {qi}"
+    assert m.sum(axis=1).tolist() == sums
+    assert int(m.sum()) == totals["total"] == 395
+    assert int(oracle.mask_dense(scales, [1] * 4, 3).sum()) == totals["total_n_sink_3"]
+    assert int(oracle.mask_dense(scales, [-1] * 4, 0).sum()) == totals["dense_block_causal_total"]
+    assert oracle.row_counts(scales, [1] * 4, 0).tolist() == sums
+
+
+def test_index_sets_match_dense_mask():
+    scales = (1, 2, 3, 4, 6)
+    radii = [1, 0, 2, 1, 1]
+    m = oracle.mask_dense(scales, radii, 1)
+    rowptr, cols = oracle.index_sets(scales, radii, 1)
+    for qi in range(m.shape[0]):
+        assert cols[rowptr[qi]:rowptr[qi + 1]].tolist() == np.nonzero(m[qi])[0].tolist()
+    for qi in (0, 7, 29, 65):
+        for t in range(m.shape[1]):
+            assert oracle.allowed(scales, radii, 1, qi, t) == bool(m[qi, t])
+
+
+# ---- closed-form pair counts ---------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny_f32", "var_d16", "var_d30_kvstep", "var_d36_512"])
+def test_pair_counts(name):
+    totals, lists = _read_pair_counts()
+    w = workloads.get(name)
+    radii = oracle.expand_radii(w.scales, w.radius)
+    cnt = oracle.row_counts(w.scales, radii, w.n_sink, w.q_scales)
+    assert int(cnt.sum()) == totals[name][0]
+    dense = oracle.row_counts(w.scales, [-1] * len(w.scales), 0, w.q_scales)
+    assert int(dense.sum()) == totals[name][1]
+    off = oracle.scale_offsets(w.scales)
+    if name == "var_d16":
+        per_q = [int(cnt[off[k]:off[k + 1]].sum()) for k in range(len(w.scales))]
+        assert per_q == lists["var_d16_per_query_scale"]
+        saving = 1.0 - cnt.sum() / dense.sum()
+        # Table 1 of the paper: savings between 70.34 % and 81.39 % for its thresholds
+        assert 0.7034 <= saving <= 0.8139
+        assert abs(saving - 0.7469) < 5e-5
+    if name == "var_d36_512":
+        per_q = [int(cnt[off[k]:off[k + 1]].sum()) for k in range(len(w.scales))]
+        assert per_q == lists["var_2k_cfg_per_query_scale"][:10]
+    if name == "var_d30_kvstep":
+        m = oracle.mask_dense(w.scales, radii, 0, w.q_scales)
+        per_j = [int(m[:, off[j]:off[j + 1]].sum()) for j in range(10)]
+        assert per_j == lists["var_d30_kvstep_per_key_scale"]
+
+
+def test_pair_counts_2k_sampled_scales():
+    # the 34 240-token case: whole-scale totals for a few query scales (the full
+    # count is 1.17e9 predicate evaluations; three scales keep this test short)
+    totals, lists = _read_pair_counts()
+    w = workloads.get("var_2k_cfg")
+    radii = oracle.expand_radii(w.scales, w.radius)
+    for k in (9, 10, 11):
+        cnt = oracle.row_counts(w.scales, radii, 0, (k, k + 1))
+        assert int(cnt.sum()) == lists["var_2k_cfg_per_query_scale"][k]
+    assert sum(lists["var_2k_cfg_per_query_scale"]) == totals["var_2k_cfg"][0]
+
+
+# ---- brute force on small inputs -------------------------------------------------
+
+def test_bruteforce_tiny_config():
+    w = workloads.get("tiny_f32")
+    q, k, v = workloads.make_workload_qkv(w)
+    for n_sink in (0, 3):
+        radii = [1] * 4
+        mask = dense_mask(w.scales, radii, n_sink)
+        assert (oracle.mask_dense(w.scales, radii, n_sink).astype(bool) == mask).all()
+        ref, _ = masked_attention(q[0, 0].double().numpy(), k[0, 0].double().numpy(),
+                                  v[0, 0].double().numpy(), mask, w.sm_scale)
+        got = oracle.attn(w.scales, radii, q.numpy(), k.numpy(), v.numpy(), w.sm_scale, n_sink)
+        np.testing.assert_allclose(got[0, 0], ref, rtol=0, atol=1e-12)
+
+
+@settings(max_examples=40, deadline=None)
+@given(scales=st.lists(st.integers(1, 7), min_size=1, max_size=5),
+       radius=st.integers(-1, 4), n_sink=st.integers(0, 3),
+       D=st.sampled_from([1, 4, 64]), seed=st.integers(0, 2 ** 16),
+       kv_step=st.booleans())
+def test_bruteforce_random_scale_lists(scales, radius, n_sink, D, seed, kv_step):
+    K = len(scales)
+    rng = np.random.default_rng(seed)
+    radii = [int(x) for x in rng.integers(-1, 5, size=K)] if seed % 3 == 0 else [radius] * K
+    q_scales = (K - 1, K) if kv_step else None
+    mask = dense_mask(scales, radii, n_sink, q_scales)
+    assert (oracle.mask_dense(scales, radii, n_sink, q_scales).astype(bool) == mask).all()
+    L, Lq = mask.shape[1], mask.shape[0]
+    q = rng.standard_normal((2, 1, Lq, D))
+    k = rng.standard_normal((2, 1, L, D))
+    v = rng.standard_normal((2, 1, L, D))
+    got = oracle.attn(scales, radii, q, k, v, 0.37, n_sink, q_scales)
+    for b in range(2):
+        ref, _ = masked_attention(q[b, 0], k[b, 0], v[b, 0], mask, 0.37)
+        np.testing.assert_allclose(got[b, 0], ref, rtol=0, atol=1e-11)
+
+
+# ---- invariants -------------------------------------------------------------------
+
+def _small_case(seed=7, scales=(1, 2, 3, 4, 6), B=2, H=3, D=16):
+    rng = np.random.default_rng(seed)
+    L = workloads.seq_len(scales)
+    q = rng.standard_normal((B, H, L, D))
+    k = rng.standard_normal((B, H, L, D))
+    v = rng.standard_normal((B, H, L, D))
+    return scales, q, k, v
+
+
+def test_softmax_rows_sum_to_one_and_respect_mask():
+    scales, q, k, v = _small_case()
+    radii = [1] * len(scales)
+    mask = oracle.mask_dense(scales, radii, 0).astype(bool)
+    for bh, ql in [(0, 0), (1, 5), (3, 29), (5, 65)]:
+        p, o = oracle.attn_probs(scales, radii, q, k, v, 0.25, bh, ql)
+        assert abs(p.sum() - 1.0) < 1e-14
+        assert (p[~mask[ql]] == 0).all() and (p[mask[ql]] > 0).all()
+        np.testing.assert_allclose(o, p @ v.reshape(-1, *v.shape[2:])[bh], atol=1e-13)
+
+
+def test_full_window_reduces_to_dense_sdpa():
+    # a window covering every scale (or radius -1) is dense block-causal attention,
+    # which torch's scaled_dot_product_attention computes from a boolean mask
+    scales, q, k, v = _small_case(D=8)
+    toks = decode_tokens(scales)
+    sid = torch.tensor([t[0] for t in toks])
+    bc = sid[None, :] <= sid[:, None]
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q), torch.from_numpy(k), torch.from_numpy(v), attn_mask=bc, scale=0.3)
+    for radii in ([-1] * len(scales), [max(scales) - 1] * len(scales)):
+        got = oracle.attn(scales, radii, q, k, v, 0.3)
+        np.testing.assert_allclose(got, ref.numpy(), rtol=0, atol=1e-12)
+    # and a windowed mask, same library routine
+    radii = [2, 1, 0, 1, 2]
+    m = torch.from_numpy(oracle.mask_dense(scales, radii, 1).astype(bool))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q), torch.from_numpy(k), torch.from_numpy(v), attn_mask=m, scale=0.3)
+    got = oracle.attn(scales, radii, q, k, v, 0.3, n_sink=1)
+    np.testing.assert_allclose(got, ref.numpy(), rtol=0, atol=1e-12)
+
+
+def test_single_token_scale_is_exact():
+    rng = np.random.default_rng(3)
+    q, k, v = (rng.standard_normal((2, 2, 1, 64)) for _ in range(3))
+    got = oracle.attn((1,), [0], q, k, v, 0.125)
+    assert (got == v).all()
+    # the first token of any sequence sees only itself
+    scales, q, k, v = _small_case()
+    got = oracle.attn(scales, [1] * len(scales), q, k, v, 0.125, rows=[0])
+    assert (got[:, :, 0] == v[:, :, 0]).all()
+
+
+def test_zero_queries_average_the_index_set():
+    scales, q, k, v = _small_case()
+    radii = [1, 2, 0, 1, 2]
+    rowptr, cols = oracle.index_sets(scales, radii, 0)
+    got = oracle.attn(scales, radii, np.zeros_like(q), k, v, 0.125)
+    for ql in (0, 3, 14, 40, 65):
+        idx = cols[rowptr[ql]:rowptr[ql + 1]]
+        np.testing.assert_allclose(got[:, :, ql], v[:, :, idx].mean(axis=2), atol=1e-13)
+
+
+def test_sinks_are_redundant_for_radius_two():
+    w = workloads.get("var_d16")
+    a = oracle.mask_dense(w.scales, [2] * 10, 0)
+    b = oracle.mask_dense(w.scales, [2] * 10, 3)
+    assert (a == b).all()
+    assert (oracle.mask_dense(w.scales, [1] * 10, 0) != oracle.mask_dense(w.scales, [1] * 10, 3)).any()
+
+
+def test_kv_cache_step_equals_tail_of_full_call():
+    scales, q, k, v = _small_case()
+    radii = [1] * len(scales)
+    full = oracle.attn(scales, radii, q, k, v, 0.2)
+    off = oracle.scale_offsets(scales)
+    K = len(scales)
+    step = oracle.attn(scales, radii, q[:, :, off[K - 1]:], k, v, 0.2, q_scales=(K - 1, K))
+    assert (step == full[:, :, off[K - 1]:]).all()
+    mid = oracle.attn(scales, radii, q[:, :, off[2]:off[4]], k, v, 0.2, q_scales=(2, 4))
+    assert (mid == full[:, :, off[2]:off[4]]).all()
+
+
+def test_key_shift_invariance():
+    # adding one vector to every key shifts each query's scores by a constant
+    scales, q, k, v = _small_case()
+    radii = [1] * len(scales)
+    c = np.random.default_rng(1).standard_normal(k.shape[-1])
+    a = oracle.attn(scales, radii, q, k, v, 0.2)
+    b = oracle.attn(scales, radii, q, k + c, v, 0.2)
+    np.testing.assert_allclose(a, b, atol=1e-11)
+
+
+def test_rows_subset_and_bh_range():
+    scales, q, k, v = _small_case()
+    radii = [1] * len(scales)
+    full = oracle.attn(scales, radii, q, k, v, 0.2)
+    rows = [65, 0, 17]
+    sub = oracle.attn(scales, radii, q, k, v, 0.2, rows=rows)
+    assert (sub == full[:, :, rows]).all()
+    part = oracle.attn(scales, radii, q, k, v, 0.2, bh_range=(2, 4))
+    flat, pf = full.reshape(6, *full.shape[2:]), part.reshape(6, *part.shape[2:])
+    assert (pf[2:4] == flat[2:4]).all() and (pf[:2] == 0).all() and (pf[4:] == 0).all()
+
+
+def test_input_dtypes_upcast_exactly():
+    w = workloads.get("var_d16")
+    q, k, v = workloads.make_qkv((1, 2, 3), 2, 2, 64, "bf16", 5)
+    bits = [workloads.to_oracle_array(t) for t in (q, k, v)]
+    f64 = [t.double().numpy() for t in (q, k, v)]
+    f32 = [t.float().numpy() for t in (q, k, v)]
+    a = oracle.attn((1, 2, 3), [1] * 3, *bits, w.sm_scale)
+    b = oracle.attn((1, 2, 3), [1] * 3, *f64, w.sm_scale)
+    c = oracle.attn((1, 2, 3), [1] * 3, *f32, w.sm_scale)
+    assert (a == b).all() and (a == c).all()
+
+
+def test_cfg_share_copies_cond_to_uncond():
+    scales = (1, 2, 3, 4)
+    rng = np.random.default_rng(0)
+    B, H, D = 4, 3, 8
+    L = 30
+    o = rng.standard_normal((B, H, L, D))
+    share = workloads.make_cfg_share(H, len(scales), seed=9).numpy()
+    assert share.any() and not share.all()
+    ref = o.copy()
+    off = oracle.scale_offsets(scales)
+    out = oracle.cfg_share(scales, o.copy(), share)
+    for b in range(B):
+        for h in range(H):
+            for kq in range(4):
+                sl = slice(off[kq], off[kq + 1])
+                if b >= B // 2 and share[h, kq]:
+                    assert (out[b, h, sl] == ref[b - B // 2, h, sl]).all()
+                else:
+                    assert (out[b, h, sl] == ref[b, h, sl]).all()
+    # KV-cache step: only the selected query scales are present in o
+    o2 = rng.standard_normal((B, H, 16, D))
+    out2 = oracle.cfg_share(scales, o2.copy(), share, q_scales=(3, 4))
+    for h in range(H):
+        exp = o2[:2, h] if share[h, 3] else o2[2:, h]
+        assert (out2[2:, h] == exp).all()

@@ -1,0 +1,59 @@
+"""Seeded tensor generators (torch CPU).  No attention arithmetic lives here."""
+import numpy as np
+import torch
+
+
+def seq_len(scales):
+    return int(sum(int(s) * int(s) for s in scales))
+
+
+def _lq(scales, q_scales):
+    if q_scales is None:
+        return seq_len(scales)
+    return int(sum(int(s) * int(s) for s in scales[q_scales[0]:q_scales[1]]))
+
+
+def make_qkv(scales, batch, heads, head_dim, dtype, seed, input_scale=1.0, q_scales=None,
+             bh_limit=None):
+    """Q [B,H,Lq,D], K, V [B,H,L,D] as CPU torch tensors of `dtype` ("f32"|"bf16").
+
+    Draws fp32 N(0,1) in the order Q, K, V from torch.Generator(seed), multiplies
+    by input_scale, casts once.  bh_limit is unused for generation order; callers
+    slice afterwards.
+    """
+    g = torch.Generator(device="cpu").manual_seed(int(seed))
+    L, Lq = seq_len(scales), _lq(scales, q_scales)
+    q = torch.randn(batch, heads, Lq, head_dim, generator=g, dtype=torch.float32)
+    k = torch.randn(batch, heads, L, head_dim, generator=g, dtype=torch.float32)
+    v = torch.randn(batch, heads, L, head_dim, generator=g, dtype=torch.float32)
+    if input_scale != 1.0:
+        q, k, v = q * input_scale, k * input_scale, v * input_scale
+    if dtype == "bf16":
+        q, k, v = q.to(torch.bfloat16), k.to(torch.bfloat16), v.to(torch.bfloat16)
+    elif dtype != "f32":
+        raise ValueError(dtype)
+    return q, k, v
+
+
+def make_workload_qkv(w):
+    return make_qkv(w.scales, w.batch, w.heads, w.head_dim, w.dtype, w.seed, w.input_scale,
+                    w.q_scales)
+
+
+def make_cfg_share(heads, n_scales, seed, p=0.5):
+    """uint8 [H, K] table: 1 where the uncond rows reuse the cond output."""
+    g = torch.Generator(device="cpu").manual_seed(int(seed) + 100)
+    return (torch.rand(heads, n_scales, generator=g) < p).to(torch.uint8)
+
+
+def bf16_bits(t):
+    """numpy uint16 view of a CPU bf16 tensor's bit patterns (no copy of values)."""
+    assert t.dtype == torch.bfloat16 and t.device.type == "cpu"
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def to_oracle_array(t):
+    """What the oracle consumes for tensor t: f32 array or bf16 bit patterns."""
+    if t.dtype == torch.bfloat16:
+        return bf16_bits(t)
+    return t.contiguous().numpy()
