@@ -1,0 +1,205 @@
+/*
+ * litevar.h -- C ABI of the MI355X (gfx950) multi-diagonal windowed attention library.
+ *
+ * The operation is the attention of LiteVAR (arXiv 2411.17178) over VAR's
+ * coarse-to-fine token sequence:
+ *   - Section 2 ("Multi-Diagonal Window Attention"): K scales, scale k holds
+ *     s_k^2 tokens, a query of scale k sees the tokens of scales 1..k, and inside
+ *     each per-key-scale part of the attention map only a local window is kept;
+ *   - Section 2, "MDWA implementation details": the leading parts may stay dense;
+ *   - Section 3 ("Attention Sharing across CFG"): the unconditional rows may reuse
+ *     the conditional rows' attention output.
+ * Window geometry (the paper's figure is its only definition): query (k, y, x)
+ * keeps key (j, y', x') of scale j <= k iff j < n_sink_scales, or
+ * |y' - cy| <= r_j and |x' - cx| <= r_j with cy = floor((2y+1) s_j / (2 s_k)),
+ * cx likewise.  Tokens of a scale are stored row-major.  Masking precedes the
+ * softmax, so the kept weights sum to 1.
+ *
+ * Conventions
+ *   - Every pointer argument says HOST or DEVICE.  The library allocates no
+ *     device memory and keeps no global state besides a thread-local error string.
+ *   - All GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and never synchronised, unless stated otherwise.
+ *   - Arguments are validated on the host before any HIP call; a failed
+ *     validation launches nothing.
+ *   - Every function returns a litevar_status; details of the last failure on the
+ *     calling thread are available from litevar_last_error().
+ */
+#ifndef LITEVAR_H_
+#define LITEVAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t litevar_status;
+enum {
+  LITEVAR_OK = 0,
+  LITEVAR_E_INVALID_ARG = -1,    /* null pointer, out-of-range value, inconsistent sizes */
+  LITEVAR_E_UNSUPPORTED = -2,    /* valid but not implemented (e.g. head_dim != 64) */
+  LITEVAR_E_PLAN_TOO_SMALL = -3, /* plan buffer smaller than litevar_mask_plan_bytes() */
+  LITEVAR_E_HIP = -4,            /* a HIP runtime call failed; see litevar_last_error() */
+  LITEVAR_E_PLAN_CORRUPT = -5    /* plan handle or device blob failed its self-check */
+};
+
+#define LITEVAR_MAX_SCALES 32
+#define LITEVAR_MAX_SIDE 1024        /* largest s_k */
+#define LITEVAR_RADIUS_DENSE (-1)    /* no window: dense block-causal part */
+
+/* Static strings; never freed. */
+const char* litevar_status_string(litevar_status s);
+const char* litevar_last_error(void); /* thread-local */
+int32_t litevar_version(void);
+
+/*
+ * Problem statement of one mask (Section 2).  All pointers are HOST pointers read
+ * during the call only.
+ */
+typedef struct litevar_mask_desc {
+  int32_t n_scales;                    /* K, 1..LITEVAR_MAX_SCALES */
+  const int32_t* scales;               /* [K] side lengths s_k, 1..LITEVAR_MAX_SIDE, any order */
+  int32_t radius;                      /* r >= 0 (window width 2r+1), or LITEVAR_RADIUS_DENSE */
+  const int32_t* radius_per_key_scale; /* optional [K]; overrides `radius` when non-NULL */
+  int32_t n_sink_scales;               /* leading key scales kept dense, 0..K (paper: 3) */
+  int32_t q_scale_begin, q_scale_end;  /* query scales [begin, end): whole sequence = [0, K),
+                                          last KV-cache step = [K-1, K) */
+} litevar_mask_desc;
+
+/*
+ * Host-side handle of a built plan.  Plain data, owned by the caller, may be
+ * copied.  The device blob it points to is owned by the caller too and must stay
+ * alive and unmodified while the handle is used.  Fields are filled by
+ * litevar_mask_build(); callers may read them, never write them.
+ */
+typedef struct litevar_plan {
+  uint64_t magic;
+  void* d_blob;             /* DEVICE */
+  uint64_t blob_bytes;
+  int32_t n_scales;
+  int32_t q_scale_begin, q_scale_end;
+  int32_t kv_len;           /* L  = sum of s_k^2 over all scales */
+  int32_t q_len;            /* Lq = tokens of the query scales */
+  int32_t q_token_begin;    /* index in the full sequence of query row 0 */
+  int32_t side_max;         /* largest s_k */
+  int32_t waves_per_group;  /* 4x4 query patches handled by one workgroup */
+  int32_t chunk_keys;       /* keys staged into LDS per phase */
+  int32_t ring_chunks;      /* LDS ring depth in chunks */
+  int32_t n_groups;         /* workgroup tiles per (batch, head) */
+  int32_t n_patches;        /* 4x4 query patches per (batch, head) */
+  int64_t n_steps;          /* 32-key MFMA steps per (batch, head) */
+  int64_t n_union_keys;     /* keys staged through LDS per (batch, head), padded */
+  int64_t retained_pairs;   /* allowed (query, key) pairs per (batch, head) */
+  int64_t computed_pairs;   /* 16 * 32 * n_steps: pairs the MFMA tiles cover */
+  uint64_t off[12];         /* byte offsets of the blob's sections (private) */
+  int32_t scales[LITEVAR_MAX_SCALES];
+  int32_t radii[LITEVAR_MAX_SCALES];
+  int32_t n_sink_scales;
+  int32_t reserved;
+} litevar_plan;
+
+/* Tuning knobs of the plan; zero-initialise for the defaults. */
+typedef struct litevar_plan_opts {
+  int32_t waves_per_group;  /* 0 = choose; else 4, 8 or 16 */
+  int32_t reserved[7];
+} litevar_plan_opts;
+
+/*
+ * Size in bytes of the device blob a plan for `desc` needs.  Host-only, no HIP
+ * call.  opts may be NULL.  out_bytes: HOST.
+ */
+litevar_status litevar_mask_plan_bytes(const litevar_mask_desc* desc,
+                                       const litevar_plan_opts* opts, size_t* out_bytes);
+
+/*
+ * Host-only dry run of litevar_mask_build(): fills `stats` with the sizes and
+ * counts the plan would have (kv_len, q_len, n_groups, n_steps, retained_pairs,
+ * computed_pairs, blob_bytes ...) but with magic = 0 and d_blob = NULL, so the
+ * result cannot be passed to the device entry points.  No HIP call.
+ */
+litevar_status litevar_mask_plan_stats(const litevar_mask_desc* desc,
+                                       const litevar_plan_opts* opts, litevar_plan* stats);
+
+/*
+ * Build the plan on the device (Section 2: per-key-scale parts and their windows):
+ * per-(query scale, key scale) window tables, then the work-list (query patches,
+ * the key list each workgroup stages through LDS, and per-wave 32-key steps with
+ * their mask bits).  d_blob: DEVICE, blob_bytes >= litevar_mask_plan_bytes(), 256-byte
+ * aligned.  plan: HOST, filled on success.  The kernels are enqueued on `stream`;
+ * the plan may be used by later calls on the same stream without synchronising.
+ */
+litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
+                                  void* d_blob, size_t blob_bytes, void* stream,
+                                  litevar_plan* plan);
+
+/*
+ * Synchronises `stream`, reads the blob's header back and checks it against the
+ * handle (magic, sizes, the builder's overflow flag).  For tests and debugging.
+ */
+litevar_status litevar_plan_check(const litevar_plan* plan, void* stream);
+
+/*
+ * Window table as built on the device, for parity checks: d_out is DEVICE
+ * int16 [K][K][side_max][2]; entry (k, j, c) holds the inclusive [lo, hi] key
+ * coordinates of scale j that query coordinate c of scale k keeps along one axis
+ * (the 2-D window is the product of the row and column intervals); (-1, -1) where
+ * j > k or c >= s_k.
+ */
+litevar_status litevar_window_table_export(const litevar_plan* plan, int16_t* d_out,
+                                           size_t out_bytes, void* stream);
+
+/*
+ * What the work-list encodes, as a dense byte mask: d_mask is DEVICE uint8
+ * [q_len][kv_len], 1 = kept pair.  Written from the per-wave steps the attention
+ * kernel consumes (not from the window table).  d_pair_count: optional DEVICE
+ * uint64[1], receives the number of (query, key) entries in the work-list, which
+ * equals the mask's popcount iff no pair is listed twice.
+ */
+litevar_status litevar_mask_export_dense(const litevar_plan* plan, uint8_t* d_mask,
+                                         size_t mask_bytes, uint64_t* d_pair_count,
+                                         void* stream);
+
+/*
+ * Same content in CSR form: d_rowptr DEVICE int64 [q_len + 1]; d_cols DEVICE
+ * int32 [cols_cap], each row's kept keys in the order the work-list visits them
+ * (ascending token index).  cols_cap >= plan->retained_pairs.
+ */
+litevar_status litevar_mask_export_csr(const litevar_plan* plan, int64_t* d_rowptr,
+                                       int32_t* d_cols, size_t cols_cap, void* stream);
+
+typedef enum { LITEVAR_BF16 = 0, LITEVAR_F32 = 1 } litevar_dtype;
+enum { LITEVAR_FLAG_CFG_SHARE = 1u }; /* batch rows [0, B/2) conditional, b + B/2 its partner */
+
+/*
+ * O = softmax(sm_scale * Q K^T restricted to the plan's kept pairs) V   (Section 2),
+ * optionally followed by the cond -> uncond output reuse of Section 3.
+ *
+ *   d_q            DEVICE [B, H, q_len, D]; d_k, d_v DEVICE [B, H, kv_len, D];
+ *   d_o            DEVICE [B, H, q_len, D], written; must not alias the inputs.
+ *   D              head dimension, must be 64.
+ *   dt             element type of q, k, v, o.  BF16: bf16 MFMA with fp32 accumulation,
+ *                  probabilities rounded to bf16 before P V.  F32: fp32 throughout.
+ *   q_strides, kv_strides, o_strides
+ *                  HOST, element strides of the (B, H, token) axes; the D axis is
+ *                  contiguous.  NULL = packed.  Rows must be 16-byte aligned.
+ *   sm_scale       softmax scale (1/sqrt(D) in VAR), finite, > 0.
+ *   d_cfg_share    DEVICE uint8 [H][K], indexed by (head, query scale); read only
+ *                  when LITEVAR_FLAG_CFG_SHARE is set (then B must be even): where
+ *                  non-zero the conditional workgroup stores its output to both rows
+ *                  and the unconditional one does no work.
+ * Inputs must be finite.  Asynchronous on `stream`.
+ */
+litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d_q,
+                                         const void* d_k, const void* d_v, void* d_o,
+                                         int32_t B, int32_t H, int32_t D, litevar_dtype dt,
+                                         const int64_t* q_strides, const int64_t* kv_strides,
+                                         const int64_t* o_strides, float sm_scale,
+                                         const uint8_t* d_cfg_share, uint32_t flags,
+                                         void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LITEVAR_H_ */

@@ -1,0 +1,11 @@
+"""MI355X-native multi-diagonal windowed attention (LiteVAR, arXiv 2411.17178).
+
+Thin Python binding over the C-ABI library built from csrc/ (see include/litevar.h).
+PyTorch is used for device memory and streams only; every step of the path runs in
+the library's HIP kernels.  There is no CPU fallback: a missing library raises.
+"""
+from .binding import (  # noqa: F401
+    LitevarError, Plan, lib_path, litevar_mask_build, litevar_mask_export_csr,
+    litevar_mask_export_dense, litevar_mask_plan_bytes, litevar_mask_plan_stats, litevar_plan_check,
+    litevar_window_table_export, litevar_windowed_attn_fwd, load_library,
+)

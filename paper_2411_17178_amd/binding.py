@@ -1,0 +1,220 @@
+"""ctypes binding of liblitevar.so: argument marshalling only.
+
+Function names match include/litevar.h.  Tensors are torch CUDA(HIP) tensors; the
+binding passes their data pointers and the current stream handle to the library.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblitevar.so")
+_lib = None
+
+MAX_SCALES = 32
+FLAG_CFG_SHARE = 1
+DT_BF16, DT_F32 = 0, 1
+
+
+class LitevarError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"litevar status {status}: {message}")
+        self.status = status
+
+
+class _MaskDesc(C.Structure):
+    _fields_ = [("n_scales", C.c_int32), ("scales", C.POINTER(C.c_int32)),
+                ("radius", C.c_int32), ("radius_per_key_scale", C.POINTER(C.c_int32)),
+                ("n_sink_scales", C.c_int32), ("q_scale_begin", C.c_int32),
+                ("q_scale_end", C.c_int32)]
+
+
+class _PlanOpts(C.Structure):
+    _fields_ = [("waves_per_group", C.c_int32), ("reserved", C.c_int32 * 7)]
+
+
+class _Plan(C.Structure):
+    _fields_ = [("magic", C.c_uint64), ("d_blob", C.c_void_p), ("blob_bytes", C.c_uint64),
+                ("n_scales", C.c_int32), ("q_scale_begin", C.c_int32), ("q_scale_end", C.c_int32),
+                ("kv_len", C.c_int32), ("q_len", C.c_int32), ("q_token_begin", C.c_int32),
+                ("side_max", C.c_int32), ("waves_per_group", C.c_int32),
+                ("chunk_keys", C.c_int32), ("ring_chunks", C.c_int32),
+                ("n_groups", C.c_int32), ("n_patches", C.c_int32),
+                ("n_steps", C.c_int64), ("n_union_keys", C.c_int64),
+                ("retained_pairs", C.c_int64), ("computed_pairs", C.c_int64),
+                ("off", C.c_uint64 * 12), ("scales", C.c_int32 * MAX_SCALES),
+                ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load liblitevar.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2411_17178_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no CPU fallback")
+    lib = C.CDLL(_LIB_PATH)
+    lib.litevar_status_string.restype = C.c_char_p
+    lib.litevar_last_error.restype = C.c_char_p
+    lib.litevar_version.restype = C.c_int32
+    for name in ("litevar_mask_plan_bytes", "litevar_mask_plan_stats", "litevar_mask_build", "litevar_plan_check",
+                 "litevar_window_table_export", "litevar_mask_export_dense",
+                 "litevar_mask_export_csr", "litevar_windowed_attn_fwd"):
+        getattr(lib, name).restype = C.c_int32
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise LitevarError(rc, load_library().litevar_last_error().decode())
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
+    K = len(scales)
+    sc = (C.c_int32 * K)(*[int(s) for s in scales])
+    rp = None
+    if radius_per_key_scale is not None:
+        rp = (C.c_int32 * len(radius_per_key_scale))(*[int(r) for r in radius_per_key_scale])
+    qb, qe = (0, K) if q_scales is None else q_scales
+    d = _MaskDesc(K, sc, int(radius), rp, int(n_sink_scales), int(qb), int(qe))
+    d._keep = (sc, rp)
+    return d
+
+
+def _make_opts(waves_per_group):
+    o = _PlanOpts()
+    o.waves_per_group = int(waves_per_group)
+    return o
+
+
+class Plan:
+    """A built plan: the host handle plus the torch tensor that owns the device blob."""
+
+    def __init__(self, handle, blob):
+        self.handle = handle
+        self.blob = blob
+
+    def __getattr__(self, name):
+        return getattr(self.handle, name)
+
+    @property
+    def scales(self):
+        return [self.handle.scales[i] for i in range(self.handle.n_scales)]
+
+
+def litevar_mask_plan_bytes(scales, radius, radius_per_key_scale=None, n_sink_scales=0,
+                            q_scales=None, waves_per_group=0):
+    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
+    o = _make_opts(waves_per_group)
+    n = C.c_size_t(0)
+    _check(load_library().litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
+    return int(n.value)
+
+
+def litevar_mask_plan_stats(scales, radius, radius_per_key_scale=None, n_sink_scales=0,
+                            q_scales=None, waves_per_group=0):
+    """Host-only dry run: a Plan without a device blob (sizes and pair counts only)."""
+    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
+    o = _make_opts(waves_per_group)
+    handle = _Plan()
+    _check(load_library().litevar_mask_plan_stats(C.byref(d), C.byref(o), C.byref(handle)))
+    return Plan(handle, None)
+
+
+def litevar_mask_build(scales, radius, radius_per_key_scale=None, n_sink_scales=0, q_scales=None,
+                       waves_per_group=0, device="cuda", stream=None):
+    lib = load_library()
+    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
+    o = _make_opts(waves_per_group)
+    n = C.c_size_t(0)
+    _check(lib.litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
+    blob = torch.empty(n.value, dtype=torch.uint8, device=device)
+    handle = _Plan()
+    _check(lib.litevar_mask_build(C.byref(d), C.byref(o), C.c_void_p(blob.data_ptr()),
+                                  C.c_size_t(n.value), _stream_handle(stream), C.byref(handle)))
+    return Plan(handle, blob)
+
+
+def litevar_plan_check(plan, stream=None):
+    _check(load_library().litevar_plan_check(C.byref(plan.handle), _stream_handle(stream)))
+
+
+def litevar_window_table_export(plan, stream=None):
+    K, smax = plan.n_scales, plan.side_max
+    out = torch.empty((K, K, smax, 2), dtype=torch.int16, device=plan.blob.device)
+    _check(load_library().litevar_window_table_export(
+        C.byref(plan.handle), C.c_void_p(out.data_ptr()), C.c_size_t(out.numel() * 2),
+        _stream_handle(stream)))
+    return out
+
+
+def litevar_mask_export_dense(plan, stream=None):
+    """(uint8 [q_len, kv_len] mask, number of work-list entries)."""
+    mask = torch.empty((plan.q_len, plan.kv_len), dtype=torch.uint8, device=plan.blob.device)
+    count = torch.empty(1, dtype=torch.int64, device=plan.blob.device)
+    _check(load_library().litevar_mask_export_dense(
+        C.byref(plan.handle), C.c_void_p(mask.data_ptr()), C.c_size_t(mask.numel()),
+        C.c_void_p(count.data_ptr()), _stream_handle(stream)))
+    return mask, count
+
+
+def litevar_mask_export_csr(plan, stream=None):
+    rowptr = torch.empty(plan.q_len + 1, dtype=torch.int64, device=plan.blob.device)
+    cols = torch.empty(max(1, plan.retained_pairs), dtype=torch.int32, device=plan.blob.device)
+    _check(load_library().litevar_mask_export_csr(
+        C.byref(plan.handle), C.c_void_p(rowptr.data_ptr()), C.c_void_p(cols.data_ptr()),
+        C.c_size_t(cols.numel()), _stream_handle(stream)))
+    return rowptr, cols[:plan.retained_pairs]
+
+
+def _strides(t):
+    assert t.dim() == 4 and t.stride(3) == 1, "expected [B, H, tokens, D] with contiguous D"
+    return (C.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+def litevar_windowed_attn_fwd(plan, q, k, v, sm_scale, out=None, cfg_share=None, stream=None):
+    """out[B,H,q_len,D] = windowed attention of q against k, v under `plan`.
+
+    cfg_share: optional uint8 CUDA tensor [H, K]; when given, the CFG shared-output
+    flag is set and rows b + B/2 reuse rows b where the table is non-zero.
+    """
+    lib = load_library()
+    assert q.is_cuda and k.is_cuda and v.is_cuda
+    assert q.dtype == k.dtype == v.dtype
+    if q.dtype == torch.bfloat16:
+        dt = DT_BF16
+    elif q.dtype == torch.float32:
+        dt = DT_F32
+    else:
+        raise TypeError(f"unsupported dtype {q.dtype}")
+    B, H, Lq, D = q.shape
+    assert Lq == plan.q_len and k.shape == (B, H, plan.kv_len, D) and v.shape == k.shape
+    if out is None:
+        out = torch.empty_like(q)
+    assert out.shape == q.shape and out.dtype == q.dtype and out.is_cuda
+    flags, share_ptr = 0, None
+    if cfg_share is not None:
+        assert cfg_share.is_cuda and cfg_share.dtype == torch.uint8 and cfg_share.is_contiguous()
+        assert cfg_share.shape == (H, plan.n_scales)
+        flags, share_ptr = FLAG_CFG_SHARE, C.c_void_p(cfg_share.data_ptr())
+    assert k.stride() == v.stride(), "k and v must share strides"
+    _check(lib.litevar_windowed_attn_fwd(
+        C.byref(plan.handle), C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+        C.c_void_p(v.data_ptr()), C.c_void_p(out.data_ptr()), C.c_int32(B), C.c_int32(H),
+        C.c_int32(D), C.c_int32(dt), _strides(q), _strides(k), _strides(out),
+        C.c_float(sm_scale), share_ptr, C.c_uint32(flags), _stream_handle(stream)))
+    return out

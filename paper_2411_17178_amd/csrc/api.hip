@@ -1,0 +1,225 @@
+// C ABI of the library: argument validation, error strings, dispatch.
+#include "internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace lv {
+
+static thread_local char g_err[512] = "";
+
+litevar_status fail(litevar_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+litevar_status hip_check(hipError_t e, const char* what) {
+  if (e == hipSuccess) return LITEVAR_OK;
+  return fail(LITEVAR_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static litevar_status check_plan(const litevar_plan* pl) {
+  if (!pl) return fail(LITEVAR_E_INVALID_ARG, "plan is NULL");
+  if (pl->magic != kMagic) return fail(LITEVAR_E_PLAN_CORRUPT, "plan handle has a bad magic");
+  if (!pl->d_blob || pl->off[kSecEnd] != pl->blob_bytes)
+    return fail(LITEVAR_E_PLAN_CORRUPT, "plan handle is inconsistent");
+  return LITEVAR_OK;
+}
+
+}  // namespace lv
+
+using namespace lv;
+
+extern "C" {
+
+const char* litevar_status_string(litevar_status s) {
+  switch (s) {
+    case LITEVAR_OK: return "ok";
+    case LITEVAR_E_INVALID_ARG: return "invalid argument";
+    case LITEVAR_E_UNSUPPORTED: return "unsupported";
+    case LITEVAR_E_PLAN_TOO_SMALL: return "plan buffer too small";
+    case LITEVAR_E_HIP: return "HIP runtime error";
+    case LITEVAR_E_PLAN_CORRUPT: return "plan corrupt";
+    default: return "unknown status";
+  }
+}
+
+const char* litevar_last_error(void) { return g_err; }
+
+int32_t litevar_version(void) { return 100; }
+
+litevar_status litevar_mask_plan_bytes(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
+                                       size_t* out_bytes) {
+  if (!out_bytes) return fail(LITEVAR_E_INVALID_ARG, "out_bytes is NULL");
+  Geom g;
+  litevar_status rc = make_geom(desc, opts, g);
+  if (rc) return rc;
+  PlanSizes z;
+  rc = size_plan(g, z);
+  if (rc) return rc;
+  *out_bytes = (size_t)z.bytes;
+  return LITEVAR_OK;
+}
+
+static void fill_handle(const Geom& g, const PlanSizes& z, litevar_plan* plan) {
+  memset(plan, 0, sizeof *plan);
+  plan->blob_bytes = z.bytes;
+  plan->n_scales = g.K;
+  plan->q_scale_begin = g.qb; plan->q_scale_end = g.qe;
+  plan->kv_len = g.L; plan->q_len = g.Lq; plan->q_token_begin = g.q0;
+  plan->side_max = g.smax;
+  plan->waves_per_group = g.NW; plan->chunk_keys = g.C; plan->ring_chunks = g.NR;
+  plan->n_groups = g.n_groups; plan->n_patches = g.n_patches;
+  plan->n_steps = z.n_steps; plan->n_union_keys = z.n_union;
+  plan->retained_pairs = z.retained_pairs;
+  plan->computed_pairs = z.n_steps * 16 * kStepKeys;
+  for (int i = 0; i < kNumSections; ++i) plan->off[i] = z.off[i];
+  for (int k = 0; k < g.K; ++k) { plan->scales[k] = g.s[k]; plan->radii[k] = g.rad[k]; }
+  plan->n_sink_scales = g.n_sink;
+}
+
+litevar_status litevar_mask_plan_stats(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
+                                       litevar_plan* stats) {
+  if (!stats) return fail(LITEVAR_E_INVALID_ARG, "stats is NULL");
+  Geom g;
+  litevar_status rc = make_geom(desc, opts, g);
+  if (rc) return rc;
+  PlanSizes z;
+  rc = size_plan(g, z);
+  if (rc) return rc;
+  fill_handle(g, z, stats);
+  return LITEVAR_OK;
+}
+
+litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
+                                  void* d_blob, size_t blob_bytes, void* stream,
+                                  litevar_plan* plan) {
+  if (!plan) return fail(LITEVAR_E_INVALID_ARG, "plan is NULL");
+  Geom g;
+  litevar_status rc = make_geom(desc, opts, g);
+  if (rc) return rc;
+  PlanSizes z;
+  rc = size_plan(g, z);
+  if (rc) return rc;
+  if (!d_blob) return fail(LITEVAR_E_INVALID_ARG, "d_blob is NULL");
+  if ((uintptr_t)d_blob & 255) return fail(LITEVAR_E_INVALID_ARG, "d_blob must be 256-byte aligned");
+  if (blob_bytes < z.bytes)
+    return fail(LITEVAR_E_PLAN_TOO_SMALL, "plan needs %llu bytes, buffer has %llu",
+                (unsigned long long)z.bytes, (unsigned long long)blob_bytes);
+  rc = build_plan(g, z, d_blob, (hipStream_t)stream);
+  if (rc) return rc;
+  fill_handle(g, z, plan);
+  plan->magic = kMagic;
+  plan->d_blob = d_blob;
+  return LITEVAR_OK;
+}
+
+litevar_status litevar_plan_check(const litevar_plan* plan, void* stream) {
+  litevar_status rc = check_plan(plan);
+  if (rc) return rc;
+  Header h;
+  rc = read_header(plan, (hipStream_t)stream, h);
+  if (rc) return rc;
+  if (h.magic != kMagic) return fail(LITEVAR_E_PLAN_CORRUPT, "device blob has a bad magic");
+  if (h.error) return fail(LITEVAR_E_PLAN_CORRUPT, "device builder disagrees with the host sizing");
+  if (h.blob_bytes != plan->blob_bytes || h.n_groups != plan->n_groups ||
+      h.n_steps != plan->n_steps || h.n_union != plan->n_union_keys ||
+      h.retained_pairs != plan->retained_pairs)
+    return fail(LITEVAR_E_PLAN_CORRUPT, "device blob does not match the handle");
+  return LITEVAR_OK;
+}
+
+litevar_status litevar_window_table_export(const litevar_plan* plan, int16_t* d_out,
+                                           size_t out_bytes, void* stream) {
+  litevar_status rc = check_plan(plan);
+  if (rc) return rc;
+  if (!d_out) return fail(LITEVAR_E_INVALID_ARG, "d_out is NULL");
+  const size_t need = (size_t)plan->n_scales * plan->n_scales * plan->side_max * 2 * sizeof(int16_t);
+  if (out_bytes < need)
+    return fail(LITEVAR_E_INVALID_ARG, "window table needs %zu bytes, buffer has %zu", need, out_bytes);
+  return export_window_table(plan, d_out, (hipStream_t)stream);
+}
+
+litevar_status litevar_mask_export_dense(const litevar_plan* plan, uint8_t* d_mask, size_t mask_bytes,
+                                         uint64_t* d_pair_count, void* stream) {
+  litevar_status rc = check_plan(plan);
+  if (rc) return rc;
+  if (!d_mask) return fail(LITEVAR_E_INVALID_ARG, "d_mask is NULL");
+  const size_t need = (size_t)plan->q_len * plan->kv_len;
+  if (mask_bytes < need)
+    return fail(LITEVAR_E_INVALID_ARG, "dense mask needs %zu bytes, buffer has %zu", need, mask_bytes);
+  return export_dense(plan, d_mask, d_pair_count, (hipStream_t)stream);
+}
+
+litevar_status litevar_mask_export_csr(const litevar_plan* plan, int64_t* d_rowptr, int32_t* d_cols,
+                                       size_t cols_cap, void* stream) {
+  litevar_status rc = check_plan(plan);
+  if (rc) return rc;
+  if (!d_rowptr || !d_cols) return fail(LITEVAR_E_INVALID_ARG, "d_rowptr or d_cols is NULL");
+  if ((int64_t)cols_cap < plan->retained_pairs)
+    return fail(LITEVAR_E_INVALID_ARG, "cols_cap %zu below the %lld kept pairs", cols_cap,
+                (long long)plan->retained_pairs);
+  return export_csr(plan, d_rowptr, d_cols, cols_cap, (hipStream_t)stream);
+}
+
+static bool strides_ok(const int64_t* s, int B, int H, int64_t len, int D, int64_t out[3]) {
+  if (!s) { out[2] = D; out[1] = len * D; out[0] = (int64_t)H * len * D; return true; }
+  for (int i = 0; i < 3; ++i) out[i] = s[i];
+  if (s[2] < D || s[2] % 8) return false;          // rows 16-byte aligned for bf16, 32 for fp32
+  if (s[1] < 0 || s[0] < 0 || s[1] % 8 || s[0] % 8) return false;
+  (void)B;
+  return true;
+}
+
+litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d_q, const void* d_k,
+                                         const void* d_v, void* d_o, int32_t B, int32_t H, int32_t D,
+                                         litevar_dtype dt, const int64_t* q_strides,
+                                         const int64_t* kv_strides, const int64_t* o_strides,
+                                         float sm_scale, const uint8_t* d_cfg_share, uint32_t flags,
+                                         void* stream) {
+  litevar_status rc = check_plan(plan);
+  if (rc) return rc;
+  if (!d_q || !d_k || !d_v || !d_o) return fail(LITEVAR_E_INVALID_ARG, "q, k, v or o is NULL");
+  if (B < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "B and H must be positive (got %d, %d)", B, H);
+  if ((int64_t)B * H > (1 << 24)) return fail(LITEVAR_E_UNSUPPORTED, "B*H above 2^24");
+  if (D != 64) return fail(LITEVAR_E_UNSUPPORTED, "head dimension %d is not supported (only 64)", D);
+  if (dt != LITEVAR_BF16 && dt != LITEVAR_F32) return fail(LITEVAR_E_UNSUPPORTED, "unknown dtype %d", (int)dt);
+  if (!(sm_scale > 0.f) || !std::isfinite(sm_scale) || sm_scale > 1.0e4f)
+    return fail(LITEVAR_E_INVALID_ARG, "sm_scale must be finite, positive and at most 1e4");
+  if (flags & ~(uint32_t)LITEVAR_FLAG_CFG_SHARE) return fail(LITEVAR_E_INVALID_ARG, "unknown flag bits 0x%x", flags);
+  if (flags & LITEVAR_FLAG_CFG_SHARE) {
+    if (B & 1) return fail(LITEVAR_E_INVALID_ARG, "CFG sharing needs an even batch (got %d)", B);
+    if (!d_cfg_share) return fail(LITEVAR_E_INVALID_ARG, "CFG sharing flag set but d_cfg_share is NULL");
+  }
+  if (d_o == d_q || d_o == d_k || d_o == d_v) return fail(LITEVAR_E_INVALID_ARG, "o aliases an input");
+  const uintptr_t align = (uintptr_t)d_q | (uintptr_t)d_k | (uintptr_t)d_v | (uintptr_t)d_o;
+  if (align & 15) return fail(LITEVAR_E_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
+
+  AttnArgs a;
+  memset(&a, 0, sizeof a);
+  if (!strides_ok(q_strides, B, H, plan->q_len, D, a.qs) ||
+      !strides_ok(kv_strides, B, H, plan->kv_len, D, a.ks) ||
+      !strides_ok(o_strides, B, H, plan->q_len, D, a.os))
+    return fail(LITEVAR_E_INVALID_ARG, "strides must be non-negative multiples of 8 with token stride >= D");
+  a.q = d_q; a.k = d_k; a.v = d_v; a.o = d_o;
+  a.B = B; a.H = H; a.sm_scale = sm_scale;
+  a.cfg_share = (flags & LITEVAR_FLAG_CFG_SHARE) ? d_cfg_share : nullptr;
+  a.n_scales = plan->n_scales;
+  const char* blob = (const char*)plan->d_blob;
+  a.groups = (const GroupDesc*)(blob + plan->off[kSecGroups]);
+  a.waves = (const WaveDesc*)(blob + plan->off[kSecWaves]);
+  a.phase_end = (const uint16_t*)(blob + plan->off[kSecPhaseEnd]);
+  a.union_tok = (const int32_t*)(blob + plan->off[kSecUnion]);
+  a.step_words = (const uint32_t*)(blob + plan->off[kSecStepWords]);
+  a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
+  a.n_groups = plan->n_groups;
+  if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);
+  return launch_attn_bf16(plan, a, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "../../include/litevar.h"
+#include "plan.h"
+
+namespace lv {
+
+// records a printf-style message in the thread-local error string, returns `code`
+litevar_status fail(litevar_status code, const char* fmt, ...);
+litevar_status hip_check(hipError_t e, const char* what);
+
+struct PlanSizes {
+  int64_t n_steps, n_union, n_phase_entries, retained_pairs;
+  uint64_t off[kNumSections];
+  uint64_t bytes;
+};
+
+litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* opts, Geom& g);
+litevar_status size_plan(const Geom& g, PlanSizes& z);
+litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipStream_t st);
+litevar_status read_header(const litevar_plan* pl, hipStream_t st, Header& h);
+
+litevar_status export_window_table(const litevar_plan* pl, int16_t* d_out, hipStream_t st);
+litevar_status export_dense(const litevar_plan* pl, uint8_t* d_mask, uint64_t* d_count, hipStream_t st);
+litevar_status export_csr(const litevar_plan* pl, int64_t* d_rowptr, int32_t* d_cols, size_t cap,
+                          hipStream_t st);
+
+struct AttnArgs {
+  const void* q; const void* k; const void* v; void* o;
+  int64_t qs[3], ks[3], os[3];   // element strides of (B, H, token)
+  int B, H;
+  float sm_scale;
+  const uint8_t* cfg_share;      // [H][K] or nullptr
+  int n_scales;
+  // plan sections
+  const GroupDesc* groups; const WaveDesc* waves; const uint16_t* phase_end;
+  const int32_t* union_tok; const uint32_t* step_words; const int32_t* step_tok;
+  int n_groups;
+};
+
+litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
+litevar_status launch_attn_bf16(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
+
+}  // namespace lv

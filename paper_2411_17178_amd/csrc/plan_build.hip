@@ -1,0 +1,400 @@
+// Plan construction: host-side validation and sizing, device-side builder kernels
+// (window table, work-list count -> scan -> fill) and the parity exports.
+#include "internal.h"
+
+#include <cmath>
+#include <cstring>
+
+namespace lv {
+
+// ---- host: descriptor -> geometry ------------------------------------------
+
+static void choose_tiling(Geom& g, int waves) {
+  g.NW = waves;
+  if (waves == 16) { g.RH = 4; g.RW = 4; g.C = 128; g.NR = 3; }
+  else if (waves == 8) { g.RH = 2; g.RW = 4; g.C = 64; g.NR = 3; }
+  else { g.RH = 2; g.RW = 2; g.C = 64; g.NR = 3; }
+  g.A = g.NR - 2;
+}
+
+litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* opts, Geom& g) {
+  if (!d) return fail(LITEVAR_E_INVALID_ARG, "desc is NULL");
+  if (d->n_scales < 1 || d->n_scales > kMaxScales)
+    return fail(LITEVAR_E_INVALID_ARG, "n_scales must be in 1..%d (got %d)", kMaxScales, d->n_scales);
+  if (!d->scales) return fail(LITEVAR_E_INVALID_ARG, "scales is NULL");
+  memset(&g, 0, sizeof g);
+  g.K = d->n_scales;
+  int64_t L = 0;
+  for (int k = 0; k < g.K; ++k) {
+    const int s = d->scales[k];
+    if (s < 1 || s > kMaxSide)
+      return fail(LITEVAR_E_INVALID_ARG, "scales[%d] = %d outside 1..%d", k, s, kMaxSide);
+    g.s[k] = s; g.off[k] = (int)L; L += (int64_t)s * s;
+    if (L > (int64_t)1 << 30) return fail(LITEVAR_E_UNSUPPORTED, "sequence longer than 2^30 tokens");
+    if (s > g.smax) g.smax = s;
+  }
+  g.off[g.K] = (int)L; g.L = (int)L;
+  for (int k = 0; k < g.K; ++k) {
+    const int r = d->radius_per_key_scale ? d->radius_per_key_scale[k] : d->radius;
+    if (r < LITEVAR_RADIUS_DENSE)
+      return fail(LITEVAR_E_INVALID_ARG, "radius %d of key scale %d is below -1", r, k);
+    g.rad[k] = r > kMaxSide ? kMaxSide : r;
+  }
+  if (d->n_sink_scales < 0 || d->n_sink_scales > g.K)
+    return fail(LITEVAR_E_INVALID_ARG, "n_sink_scales %d outside 0..%d", d->n_sink_scales, g.K);
+  g.n_sink = d->n_sink_scales;
+  if (d->q_scale_begin < 0 || d->q_scale_end > g.K || d->q_scale_begin >= d->q_scale_end)
+    return fail(LITEVAR_E_INVALID_ARG, "query scale range [%d, %d) is empty or outside [0, %d)",
+                d->q_scale_begin, d->q_scale_end, g.K);
+  g.qb = d->q_scale_begin; g.qe = d->q_scale_end;
+  g.q0 = g.off[g.qb]; g.Lq = g.off[g.qe] - g.q0;
+
+  int waves = opts ? opts->waves_per_group : 0;
+  if (waves == 0) {
+    int sq = 0;
+    for (int k = g.qb; k < g.qe; ++k) if (g.s[k] > sq) sq = g.s[k];
+    waves = sq >= 12 ? 16 : (sq >= 8 ? 8 : 4);
+  }
+  if (waves != 4 && waves != 8 && waves != 16)
+    return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4, 8 or 16 (got %d)", waves);
+  choose_tiling(g, waves);
+
+  int64_t ng = 0, np = 0;
+  for (int i = 0; i < g.qe - g.qb; ++i) {
+    const int k = g.qe - 1 - i;
+    g.grp_off[i] = (int)ng;
+    ng += (int64_t)groups_y(g, k) * groups_x(g, k);
+    np += (int64_t)patches_per_side(g, k) * patches_per_side(g, k);
+  }
+  g.grp_off[g.qe - g.qb] = (int)ng;
+  g.n_groups = (int)ng; g.n_patches = (int)np;
+  return LITEVAR_OK;
+}
+
+static uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
+
+litevar_status size_plan(const Geom& g, PlanSizes& z) {
+  memset(&z, 0, sizeof z);
+  for (int grp = 0; grp < g.n_groups; ++grp) {
+    int k, gy, gx;
+    group_coords(g, grp, k, gy, gx);
+    const GroupExtent e = group_extent(g, k, gy, gx);
+    const int nu = group_union_keys(g, e);
+    const int nph = (nu + g.C - 1) / g.C;
+    z.n_union += (int64_t)nph * g.C;
+    z.n_phase_entries += (int64_t)nph * g.NW;
+    for (int w = 0; w < g.NW; ++w) {
+      CountSink sink;
+      const int ns = walk_patch(g, e, patch_extent(g, k, gy, gx, w), sink);
+      if (ns > 65535) return fail(LITEVAR_E_UNSUPPORTED, "a query patch needs more than 65535 steps");
+      z.n_steps += ns;
+      z.retained_pairs += sink.pairs;
+    }
+  }
+  if (z.n_steps > (int64_t)1 << 26 || z.n_union > (int64_t)1 << 30)
+    return fail(LITEVAR_E_UNSUPPORTED, "work-list too large (%lld steps)", (long long)z.n_steps);
+  uint64_t o = 0;
+  z.off[kSecHeader] = o; o += sizeof(Header);
+  z.off[kSecWin] = o; o = align256(o + (uint64_t)g.K * g.K * g.smax * 2 * sizeof(int16_t));
+  z.off[kSecGroups] = o; o = align256(o + (uint64_t)g.n_groups * sizeof(GroupDesc));
+  z.off[kSecWaves] = o; o = align256(o + (uint64_t)g.n_groups * g.NW * sizeof(WaveDesc));
+  z.off[kSecPhaseEnd] = o; o = align256(o + (uint64_t)z.n_phase_entries * sizeof(uint16_t));
+  z.off[kSecUnion] = o; o = align256(o + (uint64_t)z.n_union * sizeof(int32_t));
+  z.off[kSecStepWords] = o; o = align256(o + (uint64_t)z.n_steps * 64 * sizeof(uint32_t));
+  z.off[kSecStepTok] = o; o = align256(o + (uint64_t)z.n_steps * kStepKeys * sizeof(int32_t));
+  z.off[kSecEnd] = o;
+  z.bytes = o;
+  return LITEVAR_OK;
+}
+
+// ---- device: builder kernels -------------------------------------------------
+
+struct BlobPtrs {
+  Header* hdr; int16_t* win; GroupDesc* groups; WaveDesc* waves; uint16_t* phase_end;
+  int32_t* union_tok; uint32_t* step_words; int32_t* step_tok;
+};
+
+static BlobPtrs blob_ptrs(void* blob, const uint64_t* off) {
+  char* b = (char*)blob;
+  BlobPtrs p;
+  p.hdr = (Header*)(b + off[kSecHeader]); p.win = (int16_t*)(b + off[kSecWin]);
+  p.groups = (GroupDesc*)(b + off[kSecGroups]); p.waves = (WaveDesc*)(b + off[kSecWaves]);
+  p.phase_end = (uint16_t*)(b + off[kSecPhaseEnd]); p.union_tok = (int32_t*)(b + off[kSecUnion]);
+  p.step_words = (uint32_t*)(b + off[kSecStepWords]); p.step_tok = (int32_t*)(b + off[kSecStepTok]);
+  return p;
+}
+
+struct Caps { int64_t n_steps, n_union, n_phase_entries, retained_pairs; uint64_t bytes; };
+
+// K1: win[k][j][c] = inclusive [lo, hi]; (-1,-1) where undefined
+__global__ void k_window_table(Geom g, int16_t* win) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  const int total = g.K * g.K * g.smax;
+  if (idx >= total) return;
+  const int c = idx % g.smax, j = (idx / g.smax) % g.K, k = idx / (g.smax * g.K);
+  Interval iv = {-1, -1};
+  if (j <= k && c < g.s[k]) iv = win_interval(g, k, j, c);
+  win[2 * idx] = (int16_t)iv.lo; win[2 * idx + 1] = (int16_t)iv.hi;
+}
+
+// K2a: one thread per (group, wave): number of steps and kept pairs; wave 0 also
+// sizes the group's union list
+__global__ void k_count(Geom g, BlobPtrs p) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= g.n_groups * g.NW) return;
+  const int grp = idx / g.NW, w = idx % g.NW;
+  int k, gy, gx;
+  group_coords(g, grp, k, gy, gx);
+  const GroupExtent e = group_extent(g, k, gy, gx);
+  const PatchExtent pe = patch_extent(g, k, gy, gx, w);
+  CountSink sink;
+  const int ns = walk_patch(g, e, pe, sink);
+  WaveDesc wd;
+  wd.step_begin = 0; wd.n_steps = ns;
+  wd.q_base = g.off[k] - g.q0 + pe.y0 * g.s[k] + pe.x0;
+  wd.sk = (int16_t)g.s[k]; wd.ny = (int16_t)pe.ny; wd.nx = (int16_t)pe.nx; wd.kq = (int16_t)k;
+  wd.pairs = (int32_t)sink.pairs; wd.pad[0] = wd.pad[1] = 0;
+  p.waves[idx] = wd;
+  if (w == 0) {
+    GroupDesc gd;
+    gd.union_base = 0; gd.n_union = group_union_keys(g, e);
+    gd.n_phases = (gd.n_union + g.C - 1) / g.C;
+    gd.k = k; gd.gy = gy; gd.gx = gx; gd.phase_base = 0; gd.pad = 0;
+    p.groups[grp] = gd;
+  }
+}
+
+// K2b: exclusive scans (one thread; a few thousand entries, run once per plan)
+__global__ void k_scan(Geom g, BlobPtrs p, Caps caps) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int64_t steps = 0, uni = 0, phe = 0, pairs = 0;
+  for (int grp = 0; grp < g.n_groups; ++grp) {
+    GroupDesc& gd = p.groups[grp];
+    gd.union_base = (int32_t)uni; gd.phase_base = (int32_t)phe;
+    uni += (int64_t)gd.n_phases * g.C; phe += (int64_t)gd.n_phases * g.NW;
+    for (int w = 0; w < g.NW; ++w) {
+      WaveDesc& wd = p.waves[grp * g.NW + w];
+      wd.step_begin = (int32_t)steps; steps += wd.n_steps; pairs += wd.pairs;
+    }
+  }
+  Header h;
+  memset(&h, 0, sizeof h);
+  h.magic = kMagic; h.blob_bytes = caps.bytes;
+  h.n_groups = g.n_groups; h.n_waves = g.n_groups * g.NW;
+  h.n_steps = steps; h.n_union = uni; h.n_phase_entries = phe; h.retained_pairs = pairs;
+  h.error = (steps != caps.n_steps || uni != caps.n_union || phe != caps.n_phase_entries ||
+             pairs != caps.retained_pairs) ? 1 : 0;
+  *p.hdr = h;
+}
+
+// K2c: the group's key list (token indices), padded to whole chunks with its last key
+__global__ void k_fill_union(Geom g, BlobPtrs p, Caps caps) {
+  const int grp = blockIdx.x;
+  if (p.hdr->error) return;
+  const GroupDesc gd = p.groups[grp];
+  const GroupExtent e = group_extent(g, gd.k, gd.gy, gd.gx);
+  int32_t* out = p.union_tok + gd.union_base;
+  if ((int64_t)gd.union_base + (int64_t)gd.n_phases * g.C > caps.n_union) return;
+  int ubase = 0, last_tok = 0;
+  for (int j = 0; j <= e.k; ++j) {
+    const Box b = window_box(g, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+    const int gw = b.xhi - b.xlo + 1, n = (b.yhi - b.ylo + 1) * gw;
+    for (int i = threadIdx.x; i < n; i += blockDim.x)
+      out[ubase + i] = g.off[j] + (b.ylo + i / gw) * g.s[j] + b.xlo + i % gw;
+    ubase += n;
+    last_tok = g.off[j] + b.yhi * g.s[j] + b.xhi;
+  }
+  for (int i = gd.n_union + threadIdx.x; i < gd.n_phases * g.C; i += blockDim.x) out[i] = last_tok;
+}
+
+struct FillSink {
+  uint32_t* words; int32_t* toks; uint16_t* phase_cnt; int R, C;
+  __device__ void key(int step, int idx, int upos, int tok, unsigned qmask) {
+    uint32_t* w = words + (int64_t)step * 64;
+    if (idx == 0) for (int l = 0; l < 64; ++l) w[l] = 0;
+    toks[(int64_t)step * kStepKeys + idx] = tok;
+    const uint32_t slot = (uint32_t)(upos % R);
+    w[idx] |= slot; w[idx + 32] |= slot;
+    // key idx sits in S^T tile t = idx/16, row r = idx%16, held by lane group r/4, element r%4
+    const int t = idx / 16, r = idx % 16, grp4 = r / 4, bit = 16 + 4 * t + (r % 4);
+    for (int n = 0; n < 16; ++n)
+      if (qmask >> n & 1) w[grp4 * 16 + n] |= 1u << bit;
+  }
+  __device__ void close(int step, int n, int last_upos) {
+    uint32_t* w = words + (int64_t)step * 64;
+    const uint32_t slot = (uint32_t)(last_upos % R);
+    for (int idx = n; idx < kStepKeys; ++idx) {   // padding keys: masked, point at real data
+      toks[(int64_t)step * kStepKeys + idx] = -1;
+      w[idx] |= slot; w[idx + 32] |= slot;
+    }
+    phase_cnt[last_upos / C] += 1;
+  }
+};
+
+// K2d: one thread per (group, wave): steps (ring slots, mask bits, tokens) and the
+// cumulative number of steps that are runnable after each phase
+__global__ void k_fill_steps(Geom g, BlobPtrs p, Caps caps) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= g.n_groups * g.NW) return;
+  if (p.hdr->error) return;
+  const int grp = idx / g.NW, w = idx % g.NW;
+  const GroupDesc gd = p.groups[grp];
+  const WaveDesc wd = p.waves[idx];
+  if ((int64_t)wd.step_begin + wd.n_steps > caps.n_steps ||
+      (int64_t)gd.phase_base + (int64_t)gd.n_phases * g.NW > caps.n_phase_entries) return;
+  uint16_t* pe = p.phase_end + gd.phase_base + (int64_t)w * gd.n_phases;
+  for (int i = 0; i < gd.n_phases; ++i) pe[i] = 0;
+  const GroupExtent e = group_extent(g, gd.k, gd.gy, gd.gx);
+  FillSink sink;
+  sink.words = p.step_words + (int64_t)wd.step_begin * 64;
+  sink.toks = p.step_tok + (int64_t)wd.step_begin * kStepKeys;
+  sink.phase_cnt = pe; sink.R = g.NR * g.C; sink.C = g.C;
+  walk_patch(g, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink);
+  unsigned acc = 0;
+  for (int i = 0; i < gd.n_phases; ++i) { acc += pe[i]; pe[i] = (uint16_t)acc; }
+}
+
+litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipStream_t st) {
+  const BlobPtrs p = blob_ptrs(d_blob, z.off);
+  Caps caps{z.n_steps, z.n_union, z.n_phase_entries, z.retained_pairs, z.bytes};
+  const int nwin = g.K * g.K * g.smax;
+  hipLaunchKernelGGL(k_window_table, dim3((nwin + 255) / 256), dim3(256), 0, st, g, p.win);
+  const int nw = g.n_groups * g.NW;
+  hipLaunchKernelGGL(k_count, dim3((nw + 63) / 64), dim3(64), 0, st, g, p);
+  hipLaunchKernelGGL(k_scan, dim3(1), dim3(64), 0, st, g, p, caps);
+  hipLaunchKernelGGL(k_fill_union, dim3(g.n_groups), dim3(256), 0, st, g, p, caps);
+  hipLaunchKernelGGL(k_fill_steps, dim3((nw + 63) / 64), dim3(64), 0, st, g, p, caps);
+  return hip_check(hipGetLastError(), "plan builder launch");
+}
+
+// ---- parity exports -------------------------------------------------------------
+
+__global__ void k_export_win(int K, int smax, const int16_t* win, int16_t* out) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < K * K * smax * 2) out[idx] = win[idx];
+}
+
+__global__ void k_fill_u8(uint8_t* p, size_t n, uint8_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+__global__ void k_zero_u64(unsigned long long* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
+
+// local query row handled by column n of a patch, or -1
+__device__ inline int patch_query_row(const WaveDesc& wd, int n) {
+  const int dy = n / 4, dx = n % 4;
+  return (dy < wd.ny && dx < wd.nx) ? wd.q_base + dy * wd.sk + dx : -1;
+}
+
+// one 64-lane block per (group, wave); lane (n, g4) owns the bits of query n for the
+// keys {16t + 4*g4 + i} of every step
+__global__ void k_export_dense(int L, const WaveDesc* waves, const uint32_t* words,
+                               const int32_t* toks, uint8_t* mask, unsigned long long* count) {
+  const WaveDesc wd = waves[blockIdx.x];
+  const int lane = threadIdx.x, n = lane % 16, g4 = lane / 16;
+  const int qrow = patch_query_row(wd, n);
+  unsigned long long local = 0;
+  for (int s = 0; s < wd.n_steps; ++s) {
+    const int64_t S = (int64_t)wd.step_begin + s;
+    const uint32_t bits = words[S * 64 + lane] >> 16 & 0xff;
+    for (int e = 0; e < 8; ++e) {
+      if (!(bits >> e & 1)) continue;
+      const int tok = toks[S * kStepKeys + 16 * (e / 4) + 4 * g4 + e % 4];
+      if (qrow >= 0 && tok >= 0) { mask[(size_t)qrow * L + tok] = 1; ++local; }
+    }
+  }
+  if (count && local) atomicAdd(count, local);
+}
+
+__global__ void k_csr_count(const WaveDesc* waves, const uint32_t* words, int64_t* rowptr) {
+  const WaveDesc wd = waves[blockIdx.x];
+  const int lane = threadIdx.x, n = lane % 16;
+  int cnt = 0;
+  for (int s = 0; s < wd.n_steps; ++s)
+    cnt += __popc(words[((int64_t)wd.step_begin + s) * 64 + lane] >> 16 & 0xff);
+  cnt += __shfl_xor(cnt, 16); cnt += __shfl_xor(cnt, 32);
+  const int qrow = patch_query_row(wd, n);
+  if (lane < 16 && qrow >= 0) rowptr[qrow + 1] = cnt;
+}
+
+// in-place inclusive scan of rowptr[1..n] by one 1024-thread block
+__global__ void k_csr_scan(int64_t* rowptr, int n) {
+  __shared__ int64_t part[1024];
+  const int t = threadIdx.x, per = (n + 1023) / 1024;
+  const int b = t * per, e = b + per < n ? b + per : n;
+  int64_t sum = 0;
+  for (int i = b; i < e; ++i) sum += rowptr[i + 1];
+  part[t] = sum;
+  __syncthreads();
+  if (t == 0) {
+    int64_t acc = 0;
+    for (int i = 0; i < 1024; ++i) { const int64_t v = part[i]; part[i] = acc; acc += v; }
+    rowptr[0] = 0;
+  }
+  __syncthreads();
+  int64_t acc = part[t];
+  for (int i = b; i < e; ++i) { acc += rowptr[i + 1]; rowptr[i + 1] = acc; }
+}
+
+// 16 threads per patch, one per query: walk the steps in order and list the kept tokens
+__global__ void k_csr_fill(const WaveDesc* waves, const uint32_t* words, const int32_t* toks,
+                           const int64_t* rowptr, int32_t* cols, int64_t cap) {
+  const WaveDesc wd = waves[blockIdx.x];
+  const int n = threadIdx.x;
+  const int qrow = patch_query_row(wd, n);
+  if (n >= 16 || qrow < 0) return;
+  int64_t w = rowptr[qrow];
+  const int64_t end = rowptr[qrow + 1];
+  for (int s = 0; s < wd.n_steps; ++s) {
+    const int64_t S = (int64_t)wd.step_begin + s;
+    for (int idx = 0; idx < kStepKeys; ++idx) {
+      const int r = idx % 16;
+      const uint32_t word = words[S * 64 + (r / 4) * 16 + n];
+      if (word >> (16 + 4 * (idx / 16) + r % 4) & 1) {
+        if (w < end && w < cap) cols[w] = toks[S * kStepKeys + idx];
+        ++w;
+      }
+    }
+  }
+}
+
+litevar_status export_window_table(const litevar_plan* pl, int16_t* d_out, hipStream_t st) {
+  const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
+  const int n = pl->n_scales * pl->n_scales * pl->side_max * 2;
+  hipLaunchKernelGGL(k_export_win, dim3((n + 255) / 256), dim3(256), 0, st, pl->n_scales,
+                     pl->side_max, p.win, d_out);
+  return hip_check(hipGetLastError(), "window table export launch");
+}
+
+litevar_status export_dense(const litevar_plan* pl, uint8_t* d_mask, uint64_t* d_count,
+                            hipStream_t st) {
+  const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
+  const size_t n = (size_t)pl->q_len * pl->kv_len;
+  hipLaunchKernelGGL(k_fill_u8, dim3(2048), dim3(256), 0, st, d_mask, n, (uint8_t)0);
+  if (d_count) hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(64), 0, st, (unsigned long long*)d_count);
+  hipLaunchKernelGGL(k_export_dense, dim3(pl->n_groups * pl->waves_per_group), dim3(64), 0, st,
+                     pl->kv_len, p.waves, p.step_words, p.step_tok, d_mask,
+                     (unsigned long long*)d_count);
+  return hip_check(hipGetLastError(), "dense mask export launch");
+}
+
+litevar_status export_csr(const litevar_plan* pl, int64_t* d_rowptr, int32_t* d_cols, size_t cap,
+                          hipStream_t st) {
+  const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
+  const int nw = pl->n_groups * pl->waves_per_group;
+  hipLaunchKernelGGL(k_csr_count, dim3(nw), dim3(64), 0, st, p.waves, p.step_words, d_rowptr);
+  hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, st, d_rowptr, pl->q_len);
+  hipLaunchKernelGGL(k_csr_fill, dim3(nw), dim3(64), 0, st, p.waves, p.step_words, p.step_tok,
+                     d_rowptr, d_cols, (int64_t)cap);
+  return hip_check(hipGetLastError(), "csr export launch");
+}
+
+litevar_status read_header(const litevar_plan* pl, hipStream_t st, Header& h) {
+  litevar_status rc = hip_check(hipStreamSynchronize(st), "hipStreamSynchronize");
+  if (rc) return rc;
+  return hip_check(hipMemcpy(&h, pl->d_blob, sizeof h, hipMemcpyDeviceToHost), "header copy");
+}
+
+}  // namespace lv

@@ -1,0 +1,133 @@
+"""Host-side checks of the C-ABI library that need no GPU: the library loads, exports
+every symbol the header declares, validates arguments before any HIP call, and its
+host sizing pass reproduces the closed-form pair counts."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lv():
+    import paper_2411_17178_amd as m
+    if not os.path.exists(m.lib_path()):
+        from paper_2411_17178_amd import build
+        build.build()
+    m.load_library()
+    return m
+
+
+def test_library_exports_every_declared_symbol(lv):
+    header = open(os.path.join(ROOT, "include", "litevar.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(litevar_[a-z_0-9]+)\s*\(", header))
+    assert {"litevar_mask_build", "litevar_windowed_attn_fwd", "litevar_mask_plan_bytes"} <= names
+    lib = lv.load_library()
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in litevar.h but not exported"
+    assert lib.litevar_version() >= 100
+    assert lib.litevar_status_string(0) == b"ok"
+
+
+def test_plan_struct_matches_header(lv):
+    # the ctypes mirror must have the C struct's size: 3*8 + 12*4 + 4*8 + 12*8 + 2*32*4 + 2*4
+    from paper_2411_17178_amd.binding import _Plan
+    assert C.sizeof(_Plan) == 24 + 48 + 32 + 96 + 256 + 8
+
+
+def _totals():
+    out = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "pair_counts.txt")):
+        parts = line.split()
+        if len(parts) == 3 and not line.startswith("#") and ":" not in line:
+            out[parts[0]] = int(parts[1])
+    return out
+
+
+@pytest.mark.parametrize("waves", [0, 4, 8, 16])
+def test_host_sizing_reproduces_pair_counts(lv, waves):
+    totals = _totals()
+    for name, w in workloads.CONFIGS.items():
+        st = lv.litevar_mask_plan_stats(w.scales, w.radius, None, w.n_sink, w.q_scales, waves)
+        assert st.retained_pairs == totals[name]
+        assert st.kv_len == workloads.seq_len(w.scales)
+        assert st.computed_pairs == st.n_steps * 512 >= st.retained_pairs
+        assert st.blob_bytes == lv.litevar_mask_plan_bytes(w.scales, w.radius, None, w.n_sink,
+                                                           w.q_scales, waves)
+        assert st.magic == 0 and not st.d_blob
+    st = lv.litevar_mask_plan_stats((1, 2, 3, 4), 1, None, 3)
+    assert st.retained_pairs == 471
+    st = lv.litevar_mask_plan_stats((1, 2, 3, 4), -1)
+    assert st.retained_pairs == 627
+
+
+def test_descriptor_validation(lv):
+    E = lv.LitevarError
+    bad = [
+        dict(scales=[], radius=1),
+        dict(scales=[1] * 33, radius=1),
+        dict(scales=[1, 0, 3], radius=1),
+        dict(scales=[1, 2000], radius=1),
+        dict(scales=[1, 2, 3], radius=-2),
+        dict(scales=[1, 2, 3], radius=1, radius_per_key_scale=[1, -3, 0]),
+        dict(scales=[1, 2, 3], radius=1, n_sink_scales=4),
+        dict(scales=[1, 2, 3], radius=1, q_scales=(2, 2)),
+        dict(scales=[1, 2, 3], radius=1, q_scales=(0, 4)),
+        dict(scales=[1, 2, 3], radius=1, waves_per_group=5),
+    ]
+    for kw in bad:
+        with pytest.raises(E) as ei:
+            lv.litevar_mask_plan_bytes(**kw)
+        assert ei.value.status == -1, kw
+    assert lv.litevar_mask_plan_bytes([1, 2, 3], 1) > 0
+
+
+def test_entry_points_reject_bad_arguments_before_touching_the_gpu(lv):
+    from paper_2411_17178_amd.binding import _MaskDesc, _Plan
+    lib = lv.load_library()
+    sc = (C.c_int32 * 3)(1, 2, 3)
+    d = _MaskDesc(3, sc, 1, None, 0, 0, 3)
+    plan = _Plan()
+    # NULL blob, NULL plan, misaligned blob, too-small blob
+    assert lib.litevar_mask_build(C.byref(d), None, None, C.c_size_t(1 << 20), None, C.byref(plan)) == -1
+    assert lib.litevar_mask_build(C.byref(d), None, C.c_void_p(256), C.c_size_t(1 << 20), None, None) == -1
+    assert lib.litevar_mask_build(C.byref(d), None, C.c_void_p(257), C.c_size_t(1 << 20), None, C.byref(plan)) == -1
+    assert lib.litevar_mask_build(C.byref(d), None, C.c_void_p(256), C.c_size_t(16), None, C.byref(plan)) == -3
+    assert b"bytes" in lib.litevar_last_error()
+    assert lib.litevar_mask_plan_bytes(None, None, C.byref(C.c_size_t())) == -1
+    assert lib.litevar_mask_plan_bytes(C.byref(d), None, None) == -1
+    # a handle that was never built is refused by every device entry point
+    stats = lv.litevar_mask_plan_stats([1, 2, 3], 1).handle
+    p = C.c_void_p(4096)
+    rc = lib.litevar_windowed_attn_fwd(C.byref(stats), p, p, p, p, 1, 1, 64, 0, None, None, None,
+                                       C.c_float(0.125), None, C.c_uint32(0), None)
+    assert rc == -5
+    assert lib.litevar_mask_export_dense(C.byref(stats), p, C.c_size_t(1 << 20), None, None) == -5
+    assert lib.litevar_mask_export_csr(C.byref(stats), p, p, C.c_size_t(1 << 20), None) == -5
+    assert lib.litevar_window_table_export(C.byref(stats), p, C.c_size_t(1 << 20), None) == -5
+    assert lib.litevar_plan_check(None, None) == -1
+    # forge a "built" handle to reach the argument checks of the attention call (still no HIP call)
+    stats.magic = 0x4c56415257494e31
+    stats.d_blob = 4096
+    f = lambda **kw: lib.litevar_windowed_attn_fwd(  # noqa: E731
+        C.byref(stats), kw.get("q", p), p, p, kw.get("o", C.c_void_p(8192)), kw.get("B", 2),
+        kw.get("H", 1), kw.get("D", 64), kw.get("dt", 0), kw.get("qs"), None, None,
+        C.c_float(kw.get("scale", 0.125)), kw.get("share"), C.c_uint32(kw.get("flags", 0)), None)
+    assert f(q=None) == -1
+    assert f(B=0) == -1
+    assert f(D=128) == -2
+    assert f(dt=7) == -2
+    assert f(scale=0.0) == -1
+    assert f(scale=float("nan")) == -1
+    assert f(flags=2) == -1
+    assert f(flags=1, B=3, share=p) == -1
+    assert f(flags=1, B=2, share=None) == -1
+    assert f(o=p) == -1
+    assert f(q=C.c_void_p(4100)) == -1
+    assert f(qs=(C.c_int64 * 3)(640, 640, 60)) == -1
+    assert f(qs=(C.c_int64 * 3)(641, 640, 64)) == -1
