@@ -136,16 +136,21 @@ def litevar_mask_plan_stats(scales, radius, radius_per_key_scale=None, n_sink_sc
 
 
 def litevar_mask_build(scales, radius, radius_per_key_scale=None, n_sink_scales=0, q_scales=None,
-                       waves_per_group=0, device="cuda", stream=None):
+                       waves_per_group=0, device="cuda", stream=None, blob=None):
+    """Build a plan on the device.  `blob` (optional uint8 CUDA tensor, large enough and
+    256-byte aligned) is reused as the plan's storage instead of a fresh allocation."""
     lib = load_library()
     d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
     o = _make_opts(waves_per_group)
     n = C.c_size_t(0)
     _check(lib.litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
-    blob = torch.empty(n.value, dtype=torch.uint8, device=device)
+    if blob is None:
+        blob = torch.empty(n.value, dtype=torch.uint8, device=device)
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
     handle = _Plan()
     _check(lib.litevar_mask_build(C.byref(d), C.byref(o), C.c_void_p(blob.data_ptr()),
-                                  C.c_size_t(n.value), _stream_handle(stream), C.byref(handle)))
+                                  C.c_size_t(blob.numel()), _stream_handle(stream),
+                                  C.byref(handle)))
     return Plan(handle, blob)
 
 
@@ -218,3 +223,32 @@ def litevar_windowed_attn_fwd(plan, q, k, v, sm_scale, out=None, cfg_share=None,
         C.c_int32(D), C.c_int32(dt), _strides(q), _strides(k), _strides(out),
         C.c_float(sm_scale), share_ptr, C.c_uint32(flags), _stream_handle(stream)))
     return out
+
+
+def prepare_attn_call(plan, q, k, v, sm_scale, out, cfg_share=None, stream=None):
+    """Marshal the arguments of litevar_windowed_attn_fwd once; returns a zero-argument
+    callable that enqueues the call (for launch-rate-sensitive loops).  The tensors, the
+    plan and the stream must outlive the callable."""
+    lib = load_library()
+    assert q.is_cuda and q.dtype == k.dtype == v.dtype == out.dtype
+    dt = {torch.bfloat16: DT_BF16, torch.float32: DT_F32}[q.dtype]
+    B, H, Lq, D = q.shape
+    assert Lq == plan.q_len and k.shape == (B, H, plan.kv_len, D) and v.shape == k.shape
+    assert out.shape == q.shape and k.stride() == v.stride()
+    flags, share_ptr = 0, None
+    if cfg_share is not None:
+        assert cfg_share.is_cuda and cfg_share.dtype == torch.uint8 and cfg_share.is_contiguous()
+        assert cfg_share.shape == (H, plan.n_scales)
+        flags, share_ptr = FLAG_CFG_SHARE, C.c_void_p(cfg_share.data_ptr())
+    args = (C.byref(plan.handle), C.c_void_p(q.data_ptr()), C.c_void_p(k.data_ptr()),
+            C.c_void_p(v.data_ptr()), C.c_void_p(out.data_ptr()), C.c_int32(B), C.c_int32(H),
+            C.c_int32(D), C.c_int32(dt), _strides(q), _strides(k), _strides(out),
+            C.c_float(sm_scale), share_ptr, C.c_uint32(flags), _stream_handle(stream))
+    fn = lib.litevar_windowed_attn_fwd
+
+    def call():
+        rc = fn(*args)
+        if rc != 0:
+            _check(rc)
+    call._keep = (plan, q, k, v, out, cfg_share, args)
+    return call
