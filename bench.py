@@ -34,7 +34,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="var_d30_kvstep")
     ap.add_argument("--layers", type=int, default=0, help="0 = the model's depth")
-    ap.add_argument("--waves", type=int, default=0, help="waves per workgroup (0 = library default)")
+    ap.add_argument("--waves", type=int, default=0, help="compute waves per workgroup (0 = library default)")
+    ap.add_argument("--chunk", type=int, default=0, help="keys per LDS chunk (0 = library default)")
+    ap.add_argument("--depth", type=int, default=0, help="chunks in flight (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--dense", action="store_true", help="dense block-causal path (radius -1)")
@@ -63,6 +65,7 @@ def main():
     dev = torch.device("cuda:0")
 
     w = workloads.get(args.workload)
+    tiling = (args.waves, args.chunk, args.depth)
     layers = args.layers or LAYERS[w.name]
     radius = -1 if args.dense else w.radius
     tdtype = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -80,12 +83,12 @@ def main():
     for l in range(layers):
         os_.append(torch.empty_like(qs[l]))
 
-    nbytes = lv.litevar_mask_plan_bytes(w.scales, radius, None, w.n_sink, w.q_scales, args.waves)
+    nbytes = lv.litevar_mask_plan_bytes(w.scales, radius, None, w.n_sink, w.q_scales, tiling)
     blob = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
     def build_plan():
         return lv.litevar_mask_build(w.scales, radius, None, w.n_sink, w.q_scales,
-                                     waves_per_group=args.waves, blob=blob)
+                                     waves_per_group=tiling, blob=blob)
 
     plan = build_plan()
     lv.litevar_plan_check(plan)
@@ -125,7 +128,7 @@ def main():
         per_scale = np.zeros(len(w.scales), dtype=np.int64)
         for k in range(qb, qe):
             per_scale[k] = lv.litevar_mask_plan_stats(w.scales, radius, None, w.n_sink, (k, k + 1),
-                                                      args.waves).retained_pairs
+                                                      tiling).retained_pairs
         sh = share.cpu().numpy().astype(np.int64)
         pairs -= int((sh * per_scale[None, :]).sum()) * (w.batch // 2)
     flops_layer = 256.0 * pairs
@@ -147,6 +150,7 @@ def main():
                    "batch": w.batch, "heads": w.heads, "head_dim": w.head_dim, "radius": radius,
                    "q_len": plan.q_len, "kv_len": plan.kv_len, "layers_per_step": layers,
                    "cfg_share": bool(w.cfg_share), "waves_per_group": plan.waves_per_group,
+                   "chunk_keys": plan.chunk_keys, "ring_chunks": plan.ring_chunks,
                    "step": "plan build + one attention forward per layer"},
         "us_per_layer": round(kernel_us, 3),
         "kernel_tflops_retained": round(kernel_tflops, 2),

@@ -31,7 +31,8 @@ class _MaskDesc(C.Structure):
 
 
 class _PlanOpts(C.Structure):
-    _fields_ = [("waves_per_group", C.c_int32), ("reserved", C.c_int32 * 7)]
+    _fields_ = [("waves_per_group", C.c_int32), ("chunk_keys", C.c_int32),
+                ("prefetch_chunks", C.c_int32), ("reserved", C.c_int32 * 5)]
 
 
 class _Plan(C.Structure):
@@ -96,8 +97,12 @@ def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
 
 
 def _make_opts(waves_per_group):
+    """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks); 0 = default."""
     o = _PlanOpts()
-    o.waves_per_group = int(waves_per_group)
+    if isinstance(waves_per_group, (tuple, list)):
+        o.waves_per_group, o.chunk_keys, o.prefetch_chunks = (int(x) for x in waves_per_group)
+    else:
+        o.waves_per_group = int(waves_per_group)
     return o
 
 

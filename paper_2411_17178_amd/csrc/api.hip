@@ -206,6 +206,9 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
       !strides_ok(kv_strides, B, H, plan->kv_len, D, a.ks) ||
       !strides_ok(o_strides, B, H, plan->q_len, D, a.os))
     return fail(LITEVAR_E_INVALID_ARG, "strides must be non-negative multiples of 8 with token stride >= D");
+  const int64_t esize = dt == LITEVAR_BF16 ? 2 : 4;
+  if ((int64_t)plan->kv_len * a.ks[2] * esize >= ((int64_t)1 << 31))
+    return fail(LITEVAR_E_UNSUPPORTED, "one (batch, head) slab of k/v spans 2 GiB or more");
   a.q = d_q; a.k = d_k; a.v = d_v; a.o = d_o;
   a.B = B; a.H = H; a.sm_scale = sm_scale;
   a.cfg_share = (flags & LITEVAR_FLAG_CFG_SHARE) ? d_cfg_share : nullptr;
@@ -213,9 +216,10 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   const char* blob = (const char*)plan->d_blob;
   a.groups = (const GroupDesc*)(blob + plan->off[kSecGroups]);
   a.waves = (const WaveDesc*)(blob + plan->off[kSecWaves]);
-  a.phase_end = (const uint16_t*)(blob + plan->off[kSecPhaseEnd]);
+  a.phase_end = (const int32_t*)(blob + plan->off[kSecPhaseEnd]);
   a.union_tok = (const int32_t*)(blob + plan->off[kSecUnion]);
-  a.step_words = (const uint32_t*)(blob + plan->off[kSecStepWords]);
+  a.step_addr = (const uint2*)(blob + plan->off[kSecStepAddr]);
+  a.step_mask = (const uint64_t*)(blob + plan->off[kSecStepMask]);
   a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
   a.n_groups = plan->n_groups;
   if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);

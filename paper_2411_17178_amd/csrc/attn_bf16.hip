@@ -2,18 +2,28 @@
 // O = softmax(sm_scale * Q K^T over the kept keys) V, with the Section 3 cond ->
 // uncond output reuse folded into the store.
 //
-// One workgroup = one group of up to NW 4x4 query patches (one wave each) of one
-// (batch, head).  The workgroup streams the group's key list (K and V rows) from
-// HBM/L2 through an LDS ring in chunks of C keys; each wave then runs its own
-// 32-key steps, gathering rows from the ring by slot index:
+// One workgroup = one group of up to NW 4x4 query patches of one (batch, head):
+// NW compute waves (one patch each) plus one loader wave.
+//
+// Loader wave: streams the group's key list (K and V rows, 128 B each) from HBM/L2
+// into an LDS ring with global_load_lds_dwordx4 (no registers in between), D chunks of
+// C keys in flight.  Token indices come from a small LDS token ring that is filled the
+// same way, so the loader never waits on a register-returning load (vmcnt is in-order:
+// such a wait would drain the whole prefetch queue).
+//
+// Compute waves: each runs its own list of 32-key steps, gathering rows from the ring
+// at pre-swizzled byte offsets stored in the plan:
 //   S^T (keys x queries) = K_tile (A operand, 16 keys x 64) . Q^T (B operand)
-//       -> v_mfma_f32_16x16x32_bf16, two per 16-key tile; a lane ends up holding
-//          one query column and four keys, so the softmax state is per lane;
-//   mask bits (one per lane and key) -> -inf, online softmax in base 2;
-//   O^T (64 x queries) += V^T (A operand, via ds_read_b64_tr_b16) . P^T (B operand,
-//          the lane's own eight probabilities rounded to bf16).
-// Steps that do not touch a patch's windows are simply absent from its list, so
-// fully masked tiles cost nothing.
+//       -> v_mfma_f32_16x16x32_bf16, two per 16-key tile; a lane ends up holding one
+//          query column and four keys of each tile, so the softmax state is per lane;
+//   mask: eight 64-bit lane masks per step, read with scalar loads and applied with one
+//          v_cndmask per score (SGPR-pair select);
+//   online softmax in base 2, row maxima combined across the four 16-lane rows with
+//          v_permlane32_swap / v_permlane16_swap;
+//   O^T (64 x queries) += V^T (A operand, via ds_read_b64_tr_b16) . P^T (B operand, the
+//          lane's own eight probabilities rounded to bf16).
+// Steps that do not touch a patch's windows are absent from its list, so fully masked
+// tiles cost nothing.  One s_barrier per chunk keeps loader and compute waves in step.
 #include "internal.h"
 
 namespace lv {
@@ -23,29 +33,90 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+// constant address space: a load from a wave-uniform address becomes a scalar load
+typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
 
-constexpr int kRowBytes = 144;   // 128-byte row + 16 bytes so that 16 rows hit distinct banks
-constexpr float kFloor = -1.0e30f;  // running-max floor: keeps exp2 arguments finite
+constexpr float kFloor = -1.0e30f;   // running-max floor: keeps exp2 arguments finite
+constexpr int kTokBatchChunks = 4;   // chunks covered by one token batch
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ inline s16x4 lds_read_tr16(const unsigned char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) s16x4*)(p));
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
-template <int NW, int C, int NR>
-__global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a, float c) {
-  constexpr int T = NW * 64;
-  constexpr int R = NR * C;
-  constexpr int PT = C * 16 / T;           // 16-byte pieces per thread per chunk
-  static_assert(PT >= 1 && PT * T == C * 16, "chunk must be a whole number of passes");
+// a workgroup barrier without the memory fence of __syncthreads(): the fence would wait
+// for every outstanding LDS-DMA load of the loader wave
+__device__ inline void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// keep `s` where the lane's bit of the wave-uniform `mask` is set, else -inf
+// (inverse ballot: the SGPR pair becomes the select condition of one v_cndmask)
+__device__ inline float mask_select(float s, uint64_t mask) {
+  return __builtin_amdgcn_inverse_ballot_w64(mask) ? s : -INFINITY;
+}
+
+// max over the four lanes l, l^16, l^32, l^48: v_permlane32_swap exchanges the upper half
+// of its first register with the lower half of its second, v_permlane16_swap the odd
+// 16-lane rows of the first with the even rows of the second.  (The two results are
+// copied into scalars before the float reinterpretation: a __builtin_bit_cast applied
+// directly to an element of the returned vector reads element 0 for both.)
+__device__ inline float max_across_rows(float x) {
+  const unsigned u = __float_as_uint(x);
+  auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const unsigned a0 = a[0], a1 = a[1];
+  const unsigned v = __float_as_uint(fmaxf(__uint_as_float(a0), __uint_as_float(a1)));
+  auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  const unsigned b0 = b[0], b1 = b[1];
+  return fmaxf(__uint_as_float(b0), __uint_as_float(b1));
+}
+
+template <int N> __device__ inline void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  // gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt/lgkmcnt left at max
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+
+// N consecutive-stride LDS words (stride 32 bytes) written by earlier LDS-DMA loads of this
+// wave whose completion the caller has already established.  Inline assembly, because the
+// compiler would otherwise order these reads after a vmcnt(0) wait (it cannot know which
+// DMA loads have landed) and so drain the prefetch queue.
+template <int N> __device__ inline void lds_read_tokens(const int32_t* p, int (&t)[N]);
+template <> __device__ inline void lds_read_tokens<4>(const int32_t* p, int (&t)[4]) {
+  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
+  asm volatile("ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:32\n\t"
+               "ds_read_b32 %2, %4 offset:64\n\tds_read_b32 %3, %4 offset:96\n\t"
+               "s_waitcnt lgkmcnt(0)"
+               : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]) : "v"(a) : "memory");
+}
+template <> __device__ inline void lds_read_tokens<8>(const int32_t* p, int (&t)[8]) {
+  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
+  asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %8 offset:32\n\t"
+               "ds_read_b32 %2, %8 offset:64\n\tds_read_b32 %3, %8 offset:96\n\t"
+               "ds_read_b32 %4, %8 offset:128\n\tds_read_b32 %5, %8 offset:160\n\t"
+               "ds_read_b32 %6, %8 offset:192\n\tds_read_b32 %7, %8 offset:224\n\t"
+               "s_waitcnt lgkmcnt(0)"
+               : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]),
+                 "=&v"(t[6]), "=&v"(t[7]) : "v"(a) : "memory");
+}
+
+template <int NW, int C, int A, int D>
+__global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c) {
+  constexpr int NR = A + 1 + D;                 // ring depth in chunks
+  constexpr int R = NR * C;                     // ring slots
+  constexpr int IPC = C * 2 * kRingRowBytes / 1024;   // DMA instructions per chunk (1 KiB each)
+  constexpr int TB = kTokBatchChunks * C;       // tokens per batch
+  static_assert(C % 8 == 0 && TB % 64 == 0, "chunk shape");
+  static_assert((D - 1) * IPC < 64, "prefetch depth exceeds the vmcnt range");
+  static_assert(D <= kTokBatchChunks, "token batches must land before their chunks are issued");
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* const Kring = smem;
-  unsigned char* const Vring = smem + R * kRowBytes;
+  unsigned char* const Vring = smem + R * kRingRowBytes;
+  int32_t* const tokring = (int32_t*)(smem + 2 * R * kRingRowBytes);   // 2 batches of TB tokens
 
   // workgroup i runs on XCD i % 8: keep all groups of one (batch, head) on one XCD so
-  // its K/V are fetched into a single L2
+  // that its K/V are fetched into a single L2
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   const int bh = (seq / a.n_groups) * 8 + xcd, grp = seq % a.n_groups;
   if (bh >= a.B * a.H) return;
@@ -56,32 +127,70 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a, float c) {
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int lane = tid & 63, n = lane & 15, g4 = lane >> 4;
+  const int lane = tid & 63;
+  const int P = gd.n_phases;
+
+  if (wave == NW) {
+    // ---------------- loader wave ----------------
+    const unsigned char* Kp = (const unsigned char*)((const __bf16*)a.k + b * a.ks[0] + h * a.ks[1]);
+    const unsigned char* Vp = (const unsigned char*)((const __bf16*)a.v + b * a.ks[0] + h * a.ks[1]);
+    const unsigned row_bytes = (unsigned)a.ks[2] * 2u;   // the API checks that a (batch, head) slab
+                                                         // spans less than 2 GiB
+    const int32_t* utok = a.union_tok + gd.union_base;
+    const int n_tok = P * C;
+    const int row8 = lane >> 3, pos = lane & 7;
+
+    auto issue_tokens = [&](int batch) {       // TB tokens -> half (batch & 1) of the token ring
+#pragma unroll
+      for (int i = 0; i < TB / 64; ++i) {
+        int t = batch * TB + i * 64 + lane;
+        t = t < n_tok ? t : n_tok - 1;
+        __builtin_amdgcn_global_load_lds((global_void*)(utok + t),
+                                         (lds_void*)(tokring + (batch & 1) * TB + i * 64), 4, 0, 0);
+      }
+    };
+    auto issue_chunk = [&](int chunk) {        // C keys -> ring slots (chunk % NR) * C ...
+      const int ring0 = (chunk % NR) * C;
+      int tok[C / 8];
+      lds_read_tokens<C / 8>(tokring + (chunk % (2 * kTokBatchChunks)) * C + row8, tok);
+#pragma unroll
+      for (int i = 0; i < C / 8; ++i) {
+        const int slot = ring0 + 8 * i + row8;
+        const unsigned src = (unsigned)tok[i] * row_bytes + ((pos ^ ring_swizzle(slot)) << 4);
+        __builtin_amdgcn_global_load_lds((global_void*)(Kp + src),
+                                         (lds_void*)(Kring + (ring0 + 8 * i) * kRingRowBytes), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void*)(Vp + src),
+                                         (lds_void*)(Vring + (ring0 + 8 * i) * kRingRowBytes), 16, 0, 0);
+      }
+    };
+
+    issue_tokens(0);
+    if (P > kTokBatchChunks) issue_tokens(1);
+    wait_vmcnt<0>();                           // the first token batches are needed right away
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+      if (d < P) issue_chunk(d);
+    for (int ph = 0; ph < P; ++ph) {
+      // chunk ph has landed once at most the D-1 younger chunks are outstanding
+      if (ph + D <= P) wait_vmcnt<(D - 1) * IPC>(); else wait_vmcnt<0>();
+      wg_barrier();                            // chunk ph is visible; phase ph-1 is finished
+      const int nc = ph + D;
+      if (nc < P) {
+        // token batch nb serves chunks [4 nb, 4 nb + 4).  It is issued when chunk 4 nb - 4
+        // is: every chunk of batch nb - 2 (same half of the token ring) has been issued
+        // by then, and the batch has landed before chunk 4 nb is issued because D <= 4.
+        const int nb = nc / kTokBatchChunks + 1;
+        if (nc % kTokBatchChunks == 0 && nb >= 2 && nb * kTokBatchChunks < P) issue_tokens(nb);
+        issue_chunk(nc);
+      }
+    }
+    return;
+  }
+
+  // ---------------- compute waves ----------------
+  const int n = lane & 15, g4 = lane >> 4;
   const WaveDesc wd = a.waves[grp * NW + wave];
-
-  const __bf16* Kp = (const __bf16*)a.k + b * a.ks[0] + h * a.ks[1];
-  const __bf16* Vp = (const __bf16*)a.v + b * a.ks[0] + h * a.ks[1];
-  const int32_t* utok = a.union_tok + gd.union_base;
-
-  uint4 stage[PT];
-  auto issue = [&](int chunk) {
-#pragma unroll
-    for (int p = 0; p < PT; ++p) {
-      const int id = tid + p * T, kl = id >> 4, part = id & 15;
-      const int64_t tok = utok[chunk * C + kl];
-      const __bf16* src = (part < 8 ? Kp : Vp) + tok * a.ks[2] + (part & 7) * 8;
-      stage[p] = *(const uint4*)src;
-    }
-  };
-  auto commit = [&](int chunk) {
-#pragma unroll
-    for (int p = 0; p < PT; ++p) {
-      const int id = tid + p * T, kl = id >> 4, part = id & 15;
-      const int slot = (chunk % NR) * C + kl;
-      unsigned char* dst = (part < 8 ? Kring : Vring) + slot * kRowBytes + (part & 7) * 16;
-      *(uint4*)dst = stage[p];
-    }
-  };
+  const int n_steps = __builtin_amdgcn_readfirstlane(wd.n_steps);
 
   // Q^T as the B operand: lane (n, g4) holds Q[query n][16*g4 .. 16*g4+15]
   const int dy = n >> 2, dx = n & 3;
@@ -96,37 +205,32 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a, float c) {
     qb0 = as_bf16x8(q0); qb1 = as_bf16x8(q1);
   }
 
-  issue(0);
-  commit(0);
-  __syncthreads();
-
   float m = kFloor, l = 0.f;
   f32x4 O[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const uint16_t* pe = a.phase_end + gd.phase_base + wave * gd.n_phases;
-  const uint32_t* words = a.step_words + (int64_t)wd.step_begin * 64 + lane;
+  const int32_t* pe = a.phase_end + gd.phase_base + wave * P;
+  const int64_t step0 = __builtin_amdgcn_readfirstlane(wd.step_begin);
+  const uint2* addrs = a.step_addr + step0 * 64 + lane;
+  const uint64_t* masks = a.step_mask + step0 * 8;
   int done = 0;
-  uint32_t w_next = wd.n_steps > 0 ? words[0] : 0u;
+  uint2 ad_next = n_steps > 0 ? addrs[0] : make_uint2(0u, 0u);
 
-  for (int ph = 0; ph < gd.n_phases; ++ph) {
-    const bool more = ph + 1 < gd.n_phases;
-    if (more) issue(ph + 1);
-    const int end = __builtin_amdgcn_readfirstlane((int)pe[ph]);
+  for (int ph = 0; ph < P; ++ph) {
+    wg_barrier();                              // chunk ph is in the ring
+    const int end = __builtin_amdgcn_readfirstlane(pe[ph]);
     for (; done < end; ++done) {
-      const uint32_t w = w_next;
-      if (done + 1 < wd.n_steps) w_next = words[(int64_t)(done + 1) * 64];
-      const uint32_t bits = w >> 16;
-      const int ks0 = __shfl((int)w, n) & 0xffff, ks1 = __shfl((int)w, 16 + n) & 0xffff;
-      const int vs0 = __shfl((int)w, 4 * g4 + (n >> 2)) & 0xffff;
-      const int vs1 = __shfl((int)w, 16 + 4 * g4 + (n >> 2)) & 0xffff;
+      const uint2 ad = ad_next;
+      if (done + 1 < n_steps) ad_next = addrs[(int64_t)(done + 1) * 64];
+      const const_u64_ptr mk = (const_u64_ptr)(masks + (int64_t)done * 8);
 
       // S^T tiles: keys x queries
-      const unsigned char* k0p = Kring + ks0 * kRowBytes + g4 * 32;
-      const unsigned char* k1p = Kring + ks1 * kRowBytes + g4 * 32;
-      const bf16x8 k00 = as_bf16x8(*(const uint4*)k0p), k01 = as_bf16x8(*(const uint4*)(k0p + 16));
-      const bf16x8 k10 = as_bf16x8(*(const uint4*)k1p), k11 = as_bf16x8(*(const uint4*)(k1p + 16));
+      const unsigned ka0 = ad.x & 0xffffu, ka1 = ad.x >> 16;
+      const bf16x8 k00 = as_bf16x8(*(const uint4*)(Kring + ka0));
+      const bf16x8 k01 = as_bf16x8(*(const uint4*)(Kring + (ka0 ^ 16u)));
+      const bf16x8 k10 = as_bf16x8(*(const uint4*)(Kring + ka1));
+      const bf16x8 k11 = as_bf16x8(*(const uint4*)(Kring + (ka1 ^ 16u)));
       f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
       S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k00, qb0, S0, 0, 0, 0);
       S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k10, qb0, S1, 0, 0, 0);
@@ -134,22 +238,20 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a, float c) {
       S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k11, qb1, S1, 0, 0, 0);
 
       // V^T operand: transposing LDS reads, 4 keys x 16 dims per 16-lane block
-      const unsigned char* v0p = Vring + vs0 * kRowBytes + (n & 3) * 8;
-      const unsigned char* v1p = Vring + vs1 * kRowBytes + (n & 3) * 8;
+      const unsigned v0 = ad.y & 0xffffu, v1 = ad.y >> 16;
       s16x4 va[4][2];
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) {
-        va[dt][0] = lds_read_tr16(v0p + dt * 32);
-        va[dt][1] = lds_read_tr16(v1p + dt * 32);
+        va[dt][0] = lds_read_tr16(Vring + (v0 ^ (unsigned)(dt << 5)));
+        va[dt][1] = lds_read_tr16(Vring + (v1 ^ (unsigned)(dt << 5)));
       }
 
       float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sv[e] = (bits >> e & 1) ? sv[e] : -INFINITY;
+      for (int e = 0; e < 8; ++e) sv[e] = mask_select(sv[e], mk[e]);
       float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                        fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      mx = max_across_rows(mx);
       const float m_new = fmaxf(m, mx);
       const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
       const float mc = m_new * c;
@@ -171,8 +273,6 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a, float c) {
         O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb, O[dt], 0, 0, 0);
       }
     }
-    if (more) commit(ph + 1);
-    __syncthreads();
   }
 
   l += __shfl_xor(l, 16);
@@ -190,13 +290,14 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a, float c) {
   }
 }
 
-template <int NW, int C, int NR>
+template <int NW, int C, int A, int D>
 static litevar_status launch(const AttnArgs& a, hipStream_t st) {
-  const size_t smem = (size_t)NR * C * kRowBytes * 2;
+  constexpr int NR = A + 1 + D;
+  const size_t smem = (size_t)NR * C * kRingRowBytes * 2 + 2 * kTokBatchChunks * C * sizeof(int32_t);
   static thread_local bool attr_set = false;
   if (!attr_set) {
     litevar_status rc = hip_check(
-        hipFuncSetAttribute((const void*)k_attn_bf16<NW, C, NR>,
+        hipFuncSetAttribute((const void*)k_attn_bf16<NW, C, A, D>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
         "hipFuncSetAttribute(max dynamic LDS)");
     if (rc) return rc;
@@ -206,15 +307,25 @@ static litevar_status launch(const AttnArgs& a, hipStream_t st) {
   const int64_t blocks = bh8 * a.n_groups;
   if (blocks > 0x7fffffff) return fail(LITEVAR_E_UNSUPPORTED, "grid too large");
   const float c = a.sm_scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((k_attn_bf16<NW, C, NR>), dim3((unsigned)blocks), dim3(NW * 64), smem, st, a, c);
+  hipLaunchKernelGGL((k_attn_bf16<NW, C, A, D>), dim3((unsigned)blocks), dim3((NW + 1) * 64), smem, st,
+                     a, c);
   return hip_check(hipGetLastError(), "bf16 attention launch");
 }
 
 litevar_status launch_attn_bf16(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
   const int nw = pl->waves_per_group, C = pl->chunk_keys, NR = pl->ring_chunks;
-  if (nw == 16 && C == 128 && NR == 3) return launch<16, 128, 3>(a, st);
-  if (nw == 8 && C == 64 && NR == 3) return launch<8, 64, 3>(a, st);
-  if (nw == 4 && C == 64 && NR == 3) return launch<4, 64, 3>(a, st);
+  const int key = nw * 1000 + C * 10 + (NR - 2);
+  switch (key) {
+    case 8322: return launch<8, 32, 1, 2>(a, st);
+    case 8323: return launch<8, 32, 1, 3>(a, st);
+    case 8642: return launch<8, 64, 1, 2>(a, st);
+    case 8643: return launch<8, 64, 1, 3>(a, st);
+    case 4322: return launch<4, 32, 1, 2>(a, st);
+    case 4323: return launch<4, 32, 1, 3>(a, st);
+    case 4642: return launch<4, 64, 1, 2>(a, st);
+    case 4643: return launch<4, 64, 1, 3>(a, st);
+    default: break;
+  }
   return fail(LITEVAR_E_PLAN_CORRUPT, "no kernel for waves=%d chunk=%d ring=%d", nw, C, NR);
 }
 

@@ -1,7 +1,7 @@
 // fp32 windowed attention forward: the accuracy path (1e-5 against the fp64 oracle).
 // One 64-lane wave per (batch, head, query patch).  Lane (n, g4) = query column n of
 // the patch, head-dim slice [16*g4, 16*g4+16).  It walks the same per-patch steps
-// and mask bits as the bf16 MFMA kernel, reading K and V rows straight from global
+// and lane masks as the bf16 MFMA kernel, reading K and V rows straight from global
 // memory, with a scalar online softmax (Section 2 of the paper: softmax over the
 // kept keys only).
 #include "internal.h"
@@ -42,8 +42,7 @@ __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a, int n_waves) {
       dot += __shfl_xor(dot, 16);
       dot += __shfl_xor(dot, 32);
       const int r = i % 16;
-      const uint32_t word = a.step_words[S * 64 + (r / 4) * 16 + n];
-      const bool keep = word >> (16 + 4 * (i / 16) + r % 4) & 1;
+      const bool keep = a.step_mask[S * 8 + 4 * (i / 16) + r % 4] >> ((r / 4) * 16 + n) & 1;
       if (keep) {
         const float z = dot * a.sm_scale;
         const float m_new = fmaxf(m, z);

@@ -35,8 +35,9 @@ struct AttnArgs {
   const uint8_t* cfg_share;      // [H][K] or nullptr
   int n_scales;
   // plan sections
-  const GroupDesc* groups; const WaveDesc* waves; const uint16_t* phase_end;
-  const int32_t* union_tok; const uint32_t* step_words; const int32_t* step_tok;
+  const GroupDesc* groups; const WaveDesc* waves; const int32_t* phase_end;
+  const int32_t* union_tok; const uint2* step_addr; const uint64_t* step_mask;
+  const int32_t* step_tok;
   int n_groups;
 };
 

@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#define LV_HD __host__ __device__ inline
+
 namespace lv {
 
 constexpr int kMaxScales = 32;
@@ -25,13 +27,14 @@ constexpr int kStepKeys = 32;
 constexpr int kPatch = 4;
 constexpr uint64_t kMagic = 0x4c56415257494e31ull;  // "LVARWIN1"
 
-#define LV_HD __host__ __device__ inline
 
 struct Geom {
   int K, qb, qe, n_sink;
   int L, Lq, q0, smax;
   int NW, RH, RW;       // waves per group; group shape in patches (RH x RW)
-  int C, NR, A;         // chunk keys, ring depth in chunks, look-back in chunks
+  int C, NR, A, D;      // chunk keys (a power of two), ring depth in chunks, look-back and
+                        // prefetch depth in chunks; NR = A + 1 + D
+  int logC;
   int n_groups, n_patches;
   int s[kMaxScales];
   int off[kMaxScales + 1];
@@ -46,7 +49,7 @@ struct GroupDesc {   // 32 bytes
   int32_t n_phases;    // ceil(n_union / C), >= 1
   int32_t k;           // query scale
   int32_t gy, gx;      // group position in units of groups
-  int32_t phase_base;  // first entry in phase_end (NW * n_phases entries, wave-major)
+  int32_t phase_base;  // first entry in phase_end (NW * n_phases int32 entries, wave-major)
   int32_t pad;
 };
 
@@ -75,7 +78,14 @@ struct Header {      // first 256 bytes of the blob
 static_assert(sizeof(Header) == 256, "header size");
 
 enum Section { kSecHeader = 0, kSecWin, kSecGroups, kSecWaves, kSecPhaseEnd, kSecUnion,
-               kSecStepWords, kSecStepTok, kSecEnd, kNumSections };
+               kSecStepAddr, kSecStepMask, kSecStepTok, kSecEnd, kNumSections };
+
+// LDS ring geometry of the bf16 kernel: one 128-byte row per key in each of the K and V
+// rings; the 16-byte piece c of the row in slot s is stored at piece position
+// c ^ swizzle(s), so that 16 lanes reading one piece column of 16 consecutive slots
+// touch 16 different bank groups.
+constexpr int kRingRowBytes = 128;
+LV_HD unsigned ring_swizzle(unsigned slot) { return (slot ^ (slot >> 3)) & 7u; }
 
 // ---- window definition -------------------------------------------------------
 // Inclusive interval of key coordinates of scale j kept along one axis by query
@@ -159,35 +169,42 @@ LV_HD PatchExtent patch_extent(const Geom& g, int k, int gy, int gx, int wave) {
 template <class Sink>
 LV_HD int walk_patch(const Geom& g, const GroupExtent& e, const PatchExtent& p, Sink& sink) {
   if (p.ny == 0) return 0;
+  const int logC = g.logC, A = g.A;
   int step = 0, cnt = 0, first_chunk = 0, last_upos = 0, ubase = 0;
   for (int j = 0; j <= e.k; ++j) {
     const Box gb = window_box(g, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
     const int gw = gb.xhi - gb.xlo + 1;
     const Box pb = window_box(g, e.k, j, p.y0, p.y0 + p.ny - 1, p.x0, p.x0 + p.nx - 1);
+    const int sj = g.s[j], offj = g.off[j];
     const Interval none = {1, 0};
     Interval rw[kPatch], cw[kPatch];
+#pragma unroll
     for (int d = 0; d < kPatch; ++d) {
       rw[d] = d < p.ny ? win_interval(g, e.k, j, p.y0 + d) : none;
       cw[d] = d < p.nx ? win_interval(g, e.k, j, p.x0 + d) : none;
     }
     for (int y = pb.ylo; y <= pb.yhi; ++y) {
       unsigned rb = 0;
+#pragma unroll
       for (int d = 0; d < kPatch; ++d) rb |= (unsigned)(y >= rw[d].lo && y <= rw[d].hi) << d;
       if (!rb) continue;
+      const unsigned rowmask = ((rb & 1) ? 0x000fu : 0u) | ((rb & 2) ? 0x00f0u : 0u) |
+                               ((rb & 4) ? 0x0f00u : 0u) | ((rb & 8) ? 0xf000u : 0u);
+      const int urow = ubase + (y - gb.ylo) * gw - gb.xlo, trow = offj + y * sj;
       for (int x = pb.xlo; x <= pb.xhi; ++x) {
         unsigned cb = 0;
+#pragma unroll
         for (int d = 0; d < kPatch; ++d) cb |= (unsigned)(x >= cw[d].lo && x <= cw[d].hi) << d;
         if (!cb) continue;
-        unsigned qmask = 0;
-        for (int d = 0; d < kPatch; ++d) if (rb >> d & 1) qmask |= cb << (4 * d);
-        const int upos = ubase + (y - gb.ylo) * gw + (x - gb.xlo);
-        const int chunk = upos / g.C;
-        if (cnt == kStepKeys || (cnt > 0 && chunk - first_chunk > g.A)) {
+        const unsigned qmask = (cb * 0x1111u) & rowmask;
+        const int upos = urow + x;
+        const int chunk = upos >> logC;
+        if (cnt == kStepKeys || (cnt > 0 && chunk - first_chunk > A)) {
           sink.close(step, cnt, last_upos);
           ++step; cnt = 0;
         }
         if (cnt == 0) first_chunk = chunk;
-        sink.key(step, cnt, upos, g.off[j] + y * g.s[j] + x, qmask);
+        sink.key(step, cnt, upos, trow + x, qmask);
         ++cnt; last_upos = upos;
       }
     }
@@ -197,11 +214,7 @@ LV_HD int walk_patch(const Geom& g, const GroupExtent& e, const PatchExtent& p, 
   return step;
 }
 
-LV_HD int popcount32(unsigned v) {
-  int n = 0;
-  while (v) { v &= v - 1; ++n; }
-  return n;
-}
+LV_HD int popcount32(unsigned v) { return __builtin_popcount(v); }
 
 struct CountSink {
   int64_t pairs = 0;

@@ -9,12 +9,14 @@ namespace lv {
 
 // ---- host: descriptor -> geometry ------------------------------------------
 
-static void choose_tiling(Geom& g, int waves) {
+static void choose_tiling(Geom& g, int waves, int chunk, int depth) {
   g.NW = waves;
-  if (waves == 16) { g.RH = 4; g.RW = 4; g.C = 128; g.NR = 3; }
-  else if (waves == 8) { g.RH = 2; g.RW = 4; g.C = 64; g.NR = 3; }
-  else { g.RH = 2; g.RW = 2; g.C = 64; g.NR = 3; }
-  g.A = g.NR - 2;
+  g.C = chunk; g.D = depth; g.A = 1;
+  if (waves == 8) { g.RH = 4; g.RW = 2; }   // 16 rows x 8 columns of queries
+  else { g.RH = 2; g.RW = 2; }              // 8 x 8 queries
+  g.NR = g.A + 1 + g.D;
+  g.logC = 0;
+  while ((1 << g.logC) < g.C) ++g.logC;
 }
 
 litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* opts, Geom& g) {
@@ -53,11 +55,18 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
   if (waves == 0) {
     int sq = 0;
     for (int k = g.qb; k < g.qe; ++k) if (g.s[k] > sq) sq = g.s[k];
-    waves = sq >= 12 ? 16 : (sq >= 8 ? 8 : 4);
+    waves = sq >= 8 ? 8 : 4;
   }
-  if (waves != 4 && waves != 8 && waves != 16)
-    return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4, 8 or 16 (got %d)", waves);
-  choose_tiling(g, waves);
+  if (waves != 4 && waves != 8)
+    return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4 or 8 (got %d)", waves);
+  int chunk = opts ? opts->chunk_keys : 0, depth = opts ? opts->prefetch_chunks : 0;
+  if (chunk == 0) chunk = 32;
+  if (depth == 0) depth = 2;
+  if (chunk != 32 && chunk != 64)
+    return fail(LITEVAR_E_INVALID_ARG, "chunk_keys must be 0, 32 or 64 (got %d)", chunk);
+  if (depth != 2 && depth != 3)
+    return fail(LITEVAR_E_INVALID_ARG, "prefetch_chunks must be 0, 2 or 3 (got %d)", depth);
+  choose_tiling(g, waves, chunk, depth);
 
   int64_t ng = 0, np = 0;
   for (int i = 0; i < g.qe - g.qb; ++i) {
@@ -98,9 +107,10 @@ litevar_status size_plan(const Geom& g, PlanSizes& z) {
   z.off[kSecWin] = o; o = align256(o + (uint64_t)g.K * g.K * g.smax * 2 * sizeof(int16_t));
   z.off[kSecGroups] = o; o = align256(o + (uint64_t)g.n_groups * sizeof(GroupDesc));
   z.off[kSecWaves] = o; o = align256(o + (uint64_t)g.n_groups * g.NW * sizeof(WaveDesc));
-  z.off[kSecPhaseEnd] = o; o = align256(o + (uint64_t)z.n_phase_entries * sizeof(uint16_t));
+  z.off[kSecPhaseEnd] = o; o = align256(o + (uint64_t)z.n_phase_entries * sizeof(int32_t));
   z.off[kSecUnion] = o; o = align256(o + (uint64_t)z.n_union * sizeof(int32_t));
-  z.off[kSecStepWords] = o; o = align256(o + (uint64_t)z.n_steps * 64 * sizeof(uint32_t));
+  z.off[kSecStepAddr] = o; o = align256(o + (uint64_t)z.n_steps * 64 * sizeof(uint2));
+  z.off[kSecStepMask] = o; o = align256(o + (uint64_t)z.n_steps * 8 * sizeof(uint64_t));
   z.off[kSecStepTok] = o; o = align256(o + (uint64_t)z.n_steps * kStepKeys * sizeof(int32_t));
   z.off[kSecEnd] = o;
   z.bytes = o;
@@ -110,8 +120,8 @@ litevar_status size_plan(const Geom& g, PlanSizes& z) {
 // ---- device: builder kernels -------------------------------------------------
 
 struct BlobPtrs {
-  Header* hdr; int16_t* win; GroupDesc* groups; WaveDesc* waves; uint16_t* phase_end;
-  int32_t* union_tok; uint32_t* step_words; int32_t* step_tok;
+  Header* hdr; int16_t* win; GroupDesc* groups; WaveDesc* waves; int32_t* phase_end;
+  int32_t* union_tok; uint2* step_addr; uint64_t* step_mask; int32_t* step_tok;
 };
 
 static BlobPtrs blob_ptrs(void* blob, const uint64_t* off) {
@@ -119,8 +129,9 @@ static BlobPtrs blob_ptrs(void* blob, const uint64_t* off) {
   BlobPtrs p;
   p.hdr = (Header*)(b + off[kSecHeader]); p.win = (int16_t*)(b + off[kSecWin]);
   p.groups = (GroupDesc*)(b + off[kSecGroups]); p.waves = (WaveDesc*)(b + off[kSecWaves]);
-  p.phase_end = (uint16_t*)(b + off[kSecPhaseEnd]); p.union_tok = (int32_t*)(b + off[kSecUnion]);
-  p.step_words = (uint32_t*)(b + off[kSecStepWords]); p.step_tok = (int32_t*)(b + off[kSecStepTok]);
+  p.phase_end = (int32_t*)(b + off[kSecPhaseEnd]); p.union_tok = (int32_t*)(b + off[kSecUnion]);
+  p.step_addr = (uint2*)(b + off[kSecStepAddr]); p.step_mask = (uint64_t*)(b + off[kSecStepMask]);
+  p.step_tok = (int32_t*)(b + off[kSecStepTok]);
   return p;
 }
 
@@ -207,51 +218,78 @@ __global__ void k_fill_union(Geom g, BlobPtrs p, Caps caps) {
   for (int i = gd.n_union + threadIdx.x; i < gd.n_phases * g.C; i += blockDim.x) out[i] = last_tok;
 }
 
+// Per-lane view of the step being filled: all 64 lanes of a wave walk the patch in
+// lock-step, each keeping only what it will need in the attention kernel in registers;
+// a finished step is written with coalesced stores.  Lane (n, g4) = (lane % 16, lane / 16):
+//   K operand  rows of keys n and 16 + n          -> byte offset of its first 16-byte piece
+//   V operand  rows of keys 4*g4 + n/4 (+16)      -> byte offset of its d-tile-0 8-byte read
+//   mask bits  element e = 4*t + i  <->  key 16*t + 4*g4 + i against query n
 struct FillSink {
-  uint32_t* words; int32_t* toks; uint16_t* phase_cnt; int R, C;
-  __device__ void key(int step, int idx, int upos, int tok, unsigned qmask) {
-    uint32_t* w = words + (int64_t)step * 64;
-    if (idx == 0) for (int l = 0; l < 64; ++l) w[l] = 0;
-    toks[(int64_t)step * kStepKeys + idx] = tok;
-    const uint32_t slot = (uint32_t)(upos % R);
-    w[idx] |= slot; w[idx + 32] |= slot;
-    // key idx sits in S^T tile t = idx/16, row r = idx%16, held by lane group r/4, element r%4
-    const int t = idx / 16, r = idx % 16, grp4 = r / 4, bit = 16 + 4 * t + (r % 4);
-    for (int n = 0; n < 16; ++n)
-      if (qmask >> n & 1) w[grp4 * 16 + n] |= 1u << bit;
+  uint2* addr; uint64_t* mask; int32_t* toks; int32_t* phase_cnt;
+  int R, logC, lane;
+  uint32_t k0, k1, v0, v1, bits; int32_t tok;
+  __device__ static uint32_t k_off(uint32_t slot, int g4) {
+    return slot * kRingRowBytes + (((2u * g4) ^ ring_swizzle(slot)) << 4);
+  }
+  __device__ static uint32_t v_off(uint32_t slot, int n) {
+    const uint32_t sw = ring_swizzle(slot), b = (n >> 1) & 1, half = n & 1;
+    return slot * kRingRowBytes + 8u * half + 16u * ((b ^ sw) & 1u) + ((sw >> 1) << 5);
+  }
+  __device__ void place(int idx, uint32_t slot) {
+    const int n = lane & 15, g4 = lane >> 4;
+    if (idx == n) k0 = k_off(slot, g4);
+    if (idx == 16 + n) k1 = k_off(slot, g4);
+    if (idx == 4 * g4 + (n >> 2)) v0 = v_off(slot, n);
+    if (idx == 16 + 4 * g4 + (n >> 2)) v1 = v_off(slot, n);
+  }
+  __device__ void key(int, int idx, int upos, int t, unsigned qmask) {
+    if (idx == 0) { bits = 0; tok = -1; }
+    if (lane == idx) tok = t;
+    place(idx, (uint32_t)(upos % R));
+    const int r = idx & 15;
+    if ((r >> 2) == (lane >> 4) && (qmask >> (lane & 15) & 1)) bits |= 1u << (4 * (idx >> 4) + (r & 3));
   }
   __device__ void close(int step, int n, int last_upos) {
-    uint32_t* w = words + (int64_t)step * 64;
-    const uint32_t slot = (uint32_t)(last_upos % R);
-    for (int idx = n; idx < kStepKeys; ++idx) {   // padding keys: masked, point at real data
-      toks[(int64_t)step * kStepKeys + idx] = -1;
-      w[idx] |= slot; w[idx + 32] |= slot;
+    for (int idx = n; idx < kStepKeys; ++idx) place(idx, (uint32_t)(last_upos % R));  // padding keys
+    addr[(int64_t)step * 64 + lane] = make_uint2(k0 | (k1 << 16), v0 | (v1 << 16));
+    uint64_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint64_t bal = __ballot((bits >> e) & 1u);
+      if (lane == e) mine = bal;
     }
-    phase_cnt[last_upos / C] += 1;
+    if (lane < 8) mask[(int64_t)step * 8 + lane] = mine;
+    if (lane < kStepKeys) toks[(int64_t)step * kStepKeys + lane] = tok;
+    if (lane == 0) phase_cnt[last_upos >> logC] += 1;
   }
 };
 
-// K2d: one thread per (group, wave): steps (ring slots, mask bits, tokens) and the
+// K2d: one wave per (group, wave): steps (ring addresses, lane masks, tokens) and the
 // cumulative number of steps that are runnable after each phase
-__global__ void k_fill_steps(Geom g, BlobPtrs p, Caps caps) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= g.n_groups * g.NW) return;
+__global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps) {
+  const int idx = blockIdx.x, lane = threadIdx.x;
   if (p.hdr->error) return;
   const int grp = idx / g.NW, w = idx % g.NW;
   const GroupDesc gd = p.groups[grp];
   const WaveDesc wd = p.waves[idx];
   if ((int64_t)wd.step_begin + wd.n_steps > caps.n_steps ||
       (int64_t)gd.phase_base + (int64_t)gd.n_phases * g.NW > caps.n_phase_entries) return;
-  uint16_t* pe = p.phase_end + gd.phase_base + (int64_t)w * gd.n_phases;
-  for (int i = 0; i < gd.n_phases; ++i) pe[i] = 0;
+  int32_t* pe = p.phase_end + gd.phase_base + (int64_t)w * gd.n_phases;
+  for (int i = lane; i < gd.n_phases; i += 64) pe[i] = 0;
+  __syncthreads();
   const GroupExtent e = group_extent(g, gd.k, gd.gy, gd.gx);
   FillSink sink;
-  sink.words = p.step_words + (int64_t)wd.step_begin * 64;
+  sink.addr = p.step_addr + (int64_t)wd.step_begin * 64;
+  sink.mask = p.step_mask + (int64_t)wd.step_begin * 8;
   sink.toks = p.step_tok + (int64_t)wd.step_begin * kStepKeys;
-  sink.phase_cnt = pe; sink.R = g.NR * g.C; sink.C = g.C;
+  sink.phase_cnt = pe; sink.R = g.NR * g.C; sink.logC = g.logC; sink.lane = lane;
+  sink.k0 = sink.k1 = sink.v0 = sink.v1 = sink.bits = 0; sink.tok = -1;
   walk_patch(g, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink);
-  unsigned acc = 0;
-  for (int i = 0; i < gd.n_phases; ++i) { acc += pe[i]; pe[i] = (uint16_t)acc; }
+  __syncthreads();
+  if (lane == 0) {
+    int acc = 0;
+    for (int i = 0; i < gd.n_phases; ++i) { acc += pe[i]; pe[i] = acc; }
+  }
 }
 
 litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipStream_t st) {
@@ -263,7 +301,7 @@ litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipSt
   hipLaunchKernelGGL(k_count, dim3((nw + 63) / 64), dim3(64), 0, st, g, p);
   hipLaunchKernelGGL(k_scan, dim3(1), dim3(64), 0, st, g, p, caps);
   hipLaunchKernelGGL(k_fill_union, dim3(g.n_groups), dim3(256), 0, st, g, p, caps);
-  hipLaunchKernelGGL(k_fill_steps, dim3((nw + 63) / 64), dim3(64), 0, st, g, p, caps);
+  hipLaunchKernelGGL(k_fill_steps, dim3(nw), dim3(64), 0, st, g, p, caps);
   return hip_check(hipGetLastError(), "plan builder launch");
 }
 
@@ -290,7 +328,7 @@ __device__ inline int patch_query_row(const WaveDesc& wd, int n) {
 
 // one 64-lane block per (group, wave); lane (n, g4) owns the bits of query n for the
 // keys {16t + 4*g4 + i} of every step
-__global__ void k_export_dense(int L, const WaveDesc* waves, const uint32_t* words,
+__global__ void k_export_dense(int L, const WaveDesc* waves, const uint64_t* masks,
                                const int32_t* toks, uint8_t* mask, unsigned long long* count) {
   const WaveDesc wd = waves[blockIdx.x];
   const int lane = threadIdx.x, n = lane % 16, g4 = lane / 16;
@@ -298,9 +336,8 @@ __global__ void k_export_dense(int L, const WaveDesc* waves, const uint32_t* wor
   unsigned long long local = 0;
   for (int s = 0; s < wd.n_steps; ++s) {
     const int64_t S = (int64_t)wd.step_begin + s;
-    const uint32_t bits = words[S * 64 + lane] >> 16 & 0xff;
     for (int e = 0; e < 8; ++e) {
-      if (!(bits >> e & 1)) continue;
+      if (!(masks[S * 8 + e] >> lane & 1)) continue;
       const int tok = toks[S * kStepKeys + 16 * (e / 4) + 4 * g4 + e % 4];
       if (qrow >= 0 && tok >= 0) { mask[(size_t)qrow * L + tok] = 1; ++local; }
     }
@@ -308,12 +345,12 @@ __global__ void k_export_dense(int L, const WaveDesc* waves, const uint32_t* wor
   if (count && local) atomicAdd(count, local);
 }
 
-__global__ void k_csr_count(const WaveDesc* waves, const uint32_t* words, int64_t* rowptr) {
+__global__ void k_csr_count(const WaveDesc* waves, const uint64_t* masks, int64_t* rowptr) {
   const WaveDesc wd = waves[blockIdx.x];
   const int lane = threadIdx.x, n = lane % 16;
   int cnt = 0;
   for (int s = 0; s < wd.n_steps; ++s)
-    cnt += __popc(words[((int64_t)wd.step_begin + s) * 64 + lane] >> 16 & 0xff);
+    for (int e = 0; e < 8; ++e) cnt += (int)(masks[((int64_t)wd.step_begin + s) * 8 + e] >> lane & 1);
   cnt += __shfl_xor(cnt, 16); cnt += __shfl_xor(cnt, 32);
   const int qrow = patch_query_row(wd, n);
   if (lane < 16 && qrow >= 0) rowptr[qrow + 1] = cnt;
@@ -339,7 +376,7 @@ __global__ void k_csr_scan(int64_t* rowptr, int n) {
 }
 
 // 16 threads per patch, one per query: walk the steps in order and list the kept tokens
-__global__ void k_csr_fill(const WaveDesc* waves, const uint32_t* words, const int32_t* toks,
+__global__ void k_csr_fill(const WaveDesc* waves, const uint64_t* masks, const int32_t* toks,
                            const int64_t* rowptr, int32_t* cols, int64_t cap) {
   const WaveDesc wd = waves[blockIdx.x];
   const int n = threadIdx.x;
@@ -351,8 +388,7 @@ __global__ void k_csr_fill(const WaveDesc* waves, const uint32_t* words, const i
     const int64_t S = (int64_t)wd.step_begin + s;
     for (int idx = 0; idx < kStepKeys; ++idx) {
       const int r = idx % 16;
-      const uint32_t word = words[S * 64 + (r / 4) * 16 + n];
-      if (word >> (16 + 4 * (idx / 16) + r % 4) & 1) {
+      if (masks[S * 8 + 4 * (idx / 16) + r % 4] >> ((r / 4) * 16 + n) & 1) {
         if (w < end && w < cap) cols[w] = toks[S * kStepKeys + idx];
         ++w;
       }
@@ -375,7 +411,7 @@ litevar_status export_dense(const litevar_plan* pl, uint8_t* d_mask, uint64_t* d
   hipLaunchKernelGGL(k_fill_u8, dim3(2048), dim3(256), 0, st, d_mask, n, (uint8_t)0);
   if (d_count) hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(64), 0, st, (unsigned long long*)d_count);
   hipLaunchKernelGGL(k_export_dense, dim3(pl->n_groups * pl->waves_per_group), dim3(64), 0, st,
-                     pl->kv_len, p.waves, p.step_words, p.step_tok, d_mask,
+                     pl->kv_len, p.waves, p.step_mask, p.step_tok, d_mask,
                      (unsigned long long*)d_count);
   return hip_check(hipGetLastError(), "dense mask export launch");
 }
@@ -384,9 +420,9 @@ litevar_status export_csr(const litevar_plan* pl, int64_t* d_rowptr, int32_t* d_
                           hipStream_t st) {
   const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
   const int nw = pl->n_groups * pl->waves_per_group;
-  hipLaunchKernelGGL(k_csr_count, dim3(nw), dim3(64), 0, st, p.waves, p.step_words, d_rowptr);
+  hipLaunchKernelGGL(k_csr_count, dim3(nw), dim3(64), 0, st, p.waves, p.step_mask, d_rowptr);
   hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, st, d_rowptr, pl->q_len);
-  hipLaunchKernelGGL(k_csr_fill, dim3(nw), dim3(64), 0, st, p.waves, p.step_words, p.step_tok,
+  hipLaunchKernelGGL(k_csr_fill, dim3(nw), dim3(64), 0, st, p.waves, p.step_mask, p.step_tok,
                      d_rowptr, d_cols, (int64_t)cap);
   return hip_check(hipGetLastError(), "csr export launch");
 }
