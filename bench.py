@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--waves", type=int, default=0, help="compute waves per workgroup (0 = library default)")
     ap.add_argument("--chunk", type=int, default=0, help="keys per LDS chunk (0 = library default)")
     ap.add_argument("--depth", type=int, default=0, help="chunks in flight (0 = library default)")
+    ap.add_argument("--spare", type=int, default=-1, help="spare ring chunks (-1 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--dense", action="store_true", help="dense block-causal path (radius -1)")
@@ -65,7 +66,7 @@ def main():
     dev = torch.device("cuda:0")
 
     w = workloads.get(args.workload)
-    tiling = (args.waves, args.chunk, args.depth)
+    tiling = (args.waves, args.chunk, args.depth, args.spare)
     layers = args.layers or LAYERS[w.name]
     radius = -1 if args.dense else w.radius
     tdtype = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -151,6 +152,7 @@ def main():
                    "q_len": plan.q_len, "kv_len": plan.kv_len, "layers_per_step": layers,
                    "cfg_share": bool(w.cfg_share), "waves_per_group": plan.waves_per_group,
                    "chunk_keys": plan.chunk_keys, "ring_chunks": plan.ring_chunks,
+                   "prefetch_chunks": plan.prefetch_chunks,
                    "step": "plan build + one attention forward per layer"},
         "us_per_layer": round(kernel_us, 3),
         "kernel_tflops_retained": round(kernel_tflops, 2),

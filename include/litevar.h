@@ -86,7 +86,8 @@ typedef struct litevar_plan {
   int32_t side_max;         /* largest s_k */
   int32_t waves_per_group;  /* 4x4 query patches handled by one workgroup */
   int32_t chunk_keys;       /* keys staged into LDS per phase */
-  int32_t ring_chunks;      /* LDS ring depth in chunks = look-back (1) + 1 + prefetch depth */
+  int32_t ring_chunks;      /* LDS ring depth in chunks = look-back (1) + 1 + prefetch + spare */
+  int32_t prefetch_chunks;  /* chunks the loader keeps in flight */
   int32_t n_groups;         /* workgroup tiles per (batch, head) */
   int32_t n_patches;        /* 4x4 query patches per (batch, head) */
   int64_t n_steps;          /* 32-key MFMA steps per (batch, head) */
@@ -97,15 +98,17 @@ typedef struct litevar_plan {
   int32_t scales[LITEVAR_MAX_SCALES];
   int32_t radii[LITEVAR_MAX_SCALES];
   int32_t n_sink_scales;
-  int32_t reserved;
 } litevar_plan;
 
 /* Tuning knobs of the plan; zero-initialise for the defaults. */
 typedef struct litevar_plan_opts {
   int32_t waves_per_group;  /* compute waves (4x4 query patches) per workgroup: 0 = choose; else 4 or 8 */
   int32_t chunk_keys;       /* keys per LDS ring chunk: 0 = choose; else 32 or 64 */
-  int32_t prefetch_chunks;  /* chunks kept in flight by the loader wave: 0 = choose; else 2 or 3 */
-  int32_t reserved[5];
+  int32_t prefetch_chunks;  /* chunks kept in flight by the loader wave: 0 = choose */
+  int32_t spare_chunks;     /* extra ring chunks that let waves drift apart: -1 = choose.
+                               Supported (chunk, prefetch, spare): (32,2,0) (32,2,2) (32,3,2) (32,4,3)
+                               (64,2,0) (64,2,1) */
+  int32_t reserved[4];
 } litevar_plan_opts;
 
 /*

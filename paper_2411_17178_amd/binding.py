@@ -32,7 +32,8 @@ class _MaskDesc(C.Structure):
 
 class _PlanOpts(C.Structure):
     _fields_ = [("waves_per_group", C.c_int32), ("chunk_keys", C.c_int32),
-                ("prefetch_chunks", C.c_int32), ("reserved", C.c_int32 * 5)]
+                ("prefetch_chunks", C.c_int32), ("spare_chunks", C.c_int32),
+                ("reserved", C.c_int32 * 4)]
 
 
 class _Plan(C.Structure):
@@ -41,12 +42,11 @@ class _Plan(C.Structure):
                 ("kv_len", C.c_int32), ("q_len", C.c_int32), ("q_token_begin", C.c_int32),
                 ("side_max", C.c_int32), ("waves_per_group", C.c_int32),
                 ("chunk_keys", C.c_int32), ("ring_chunks", C.c_int32),
-                ("n_groups", C.c_int32), ("n_patches", C.c_int32),
+                ("prefetch_chunks", C.c_int32), ("n_groups", C.c_int32), ("n_patches", C.c_int32),
                 ("n_steps", C.c_int64), ("n_union_keys", C.c_int64),
                 ("retained_pairs", C.c_int64), ("computed_pairs", C.c_int64),
                 ("off", C.c_uint64 * 12), ("scales", C.c_int32 * MAX_SCALES),
-                ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32)]
 
 
 def lib_path():
@@ -97,10 +97,14 @@ def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
 
 
 def _make_opts(waves_per_group):
-    """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks); 0 = default."""
+    """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks, spare_chunks);
+    0 (spare: -1) = library default."""
     o = _PlanOpts()
+    o.spare_chunks = -1
     if isinstance(waves_per_group, (tuple, list)):
-        o.waves_per_group, o.chunk_keys, o.prefetch_chunks = (int(x) for x in waves_per_group)
+        vals = [int(x) for x in waves_per_group] + [0, 0, -1]
+        o.waves_per_group, o.chunk_keys, o.prefetch_chunks = vals[0], vals[1], vals[2]
+        o.spare_chunks = vals[3] if len(waves_per_group) > 3 else -1
     else:
         o.waves_per_group = int(waves_per_group)
     return o

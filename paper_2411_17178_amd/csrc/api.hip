@@ -74,6 +74,7 @@ static void fill_handle(const Geom& g, const PlanSizes& z, litevar_plan* plan) {
   plan->kv_len = g.L; plan->q_len = g.Lq; plan->q_token_begin = g.q0;
   plan->side_max = g.smax;
   plan->waves_per_group = g.NW; plan->chunk_keys = g.C; plan->ring_chunks = g.NR;
+  plan->prefetch_chunks = g.D;
   plan->n_groups = g.n_groups; plan->n_patches = g.n_patches;
   plan->n_steps = z.n_steps; plan->n_union_keys = z.n_union;
   plan->retained_pairs = z.retained_pairs;

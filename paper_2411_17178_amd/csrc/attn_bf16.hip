@@ -23,7 +23,13 @@
 //   O^T (64 x queries) += V^T (A operand, via ds_read_b64_tr_b16) . P^T (B operand, the
 //          lane's own eight probabilities rounded to bf16).
 // Steps that do not touch a patch's windows are absent from its list, so fully masked
-// tiles cost nothing.  One s_barrier per chunk keeps loader and compute waves in step.
+// tiles cost nothing.
+//
+// Synchronisation is producer/consumer through LDS words, not barriers: the loader
+// publishes the number of chunks that have landed, every compute wave publishes the
+// phase it has reached; a compute wave waits only when its next keys are not there yet,
+// the loader only when the ring slot it wants to refill is still being read.  Waves of
+// one workgroup may therefore be several chunks apart (the ring has S spare chunks).
 #include "internal.h"
 
 namespace lv {
@@ -37,19 +43,18 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 // constant address space: a load from a wave-uniform address becomes a scalar load
 typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
 
-constexpr float kFloor = -1.0e30f;   // running-max floor: keeps exp2 arguments finite
-constexpr int kTokBatchChunks = 4;   // chunks covered by one token batch
+constexpr float kFloor = -1.0e30f;   // initial softmax reference: keeps exp2 arguments finite
+constexpr float kSlack = 6.0f;       // base-2 exponent by which a score may exceed the reference
+constexpr int kTokBatchChunks = 8;   // chunks covered by one token batch
+constexpr int kAhead = 4;            // step descriptors fetched ahead by a compute wave
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 __device__ inline s16x4 lds_read_tr16(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
-
-// a workgroup barrier without the memory fence of __syncthreads(): the fence would wait
-// for every outstanding LDS-DMA load of the loader wave
-__device__ inline void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // keep `s` where the lane's bit of the wave-uniform `mask` is set, else -inf
 // (inverse ballot: the SGPR pair becomes the select condition of one v_cndmask)
@@ -101,19 +106,44 @@ template <> __device__ inline void lds_read_tokens<8>(const int32_t* p, int (&t)
                  "=&v"(t[6]), "=&v"(t[7]) : "v"(a) : "memory");
 }
 
-template <int NW, int C, int A, int D>
+// LDS accesses of the loader wave that must not wait for its outstanding LDS-DMA loads
+// (the compiler orders ordinary LDS accesses after vmcnt(0) once a DMA load is pending)
+__device__ inline void lds_store_i32_nowait(int32_t* p, int v) {
+  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) int32_t*)p;
+  asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(v) : "memory");
+}
+template <int NW> __device__ inline int lds_min_progress(const int32_t* p) {
+  static_assert(NW == 4 || NW == 8, "progress words are read four at a time");
+  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
+  typedef __attribute__((ext_vector_type(4))) int i32x4;
+  i32x4 x, y;
+  if constexpr (NW == 8) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(x), "=&v"(y) : "v"(a) : "memory");
+  } else {
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(x) : "v"(a) : "memory");
+    y = x;
+  }
+  const int m0 = min(min(x[0], x[1]), min(x[2], x[3])), m1 = min(min(y[0], y[1]), min(y[2], y[3]));
+  return min(m0, m1);
+}
+
+template <int NW, int C, int A, int D, int S>
 __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c) {
-  constexpr int NR = A + 1 + D;                 // ring depth in chunks
+  constexpr int NR = A + 1 + D + S;             // ring depth in chunks: look-back, current, in flight, spare
   constexpr int R = NR * C;                     // ring slots
   constexpr int IPC = C * 2 * kRingRowBytes / 1024;   // DMA instructions per chunk (1 KiB each)
   constexpr int TB = kTokBatchChunks * C;       // tokens per batch
   static_assert(C % 8 == 0 && TB % 64 == 0, "chunk shape");
   static_assert((D - 1) * IPC < 64, "prefetch depth exceeds the vmcnt range");
   static_assert(D <= kTokBatchChunks, "token batches must land before their chunks are issued");
-  extern __shared__ __align__(16) unsigned char smem[];
+  // statically sized, so that ring addresses fold into the DS instructions' offset fields
+  __shared__ __align__(1024) unsigned char smem[2 * R * kRingRowBytes + 2 * TB * sizeof(int32_t) + 64];
   unsigned char* const Kring = smem;
   unsigned char* const Vring = smem + R * kRingRowBytes;
   int32_t* const tokring = (int32_t*)(smem + 2 * R * kRingRowBytes);   // 2 batches of TB tokens
+  int32_t* const progress = tokring + 2 * TB;   // [NW] phase each compute wave has reached
+  int32_t* const landed = progress + 8;         // number of chunks that are in the ring
 
   // workgroup i runs on XCD i % 8: keep all groups of one (batch, head) on one XCD so
   // that its K/V are fetched into a single L2
@@ -129,6 +159,8 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int P = gd.n_phases;
+  if (tid < 16) progress[tid] = 0;             // progress[0..7], landed (and padding)
+  __syncthreads();
 
   if (wave == NW) {
     // ---------------- loader wave ----------------
@@ -173,12 +205,18 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
     for (int ph = 0; ph < P; ++ph) {
       // chunk ph has landed once at most the D-1 younger chunks are outstanding
       if (ph + D <= P) wait_vmcnt<(D - 1) * IPC>(); else wait_vmcnt<0>();
-      wg_barrier();                            // chunk ph is visible; phase ph-1 is finished
+      if (lane == 0) lds_store_i32_nowait(landed, ph + 1);
       const int nc = ph + D;
       if (nc < P) {
-        // token batch nb serves chunks [4 nb, 4 nb + 4).  It is issued when chunk 4 nb - 4
-        // is: every chunk of batch nb - 2 (same half of the token ring) has been issued
-        // by then, and the batch has landed before chunk 4 nb is issued because D <= 4.
+        // chunk nc reuses the slot of chunk nc - NR, which steps of phases up to
+        // nc - NR + A may still read: wait until every compute wave is past them
+        const int need = nc - NR + A + 1;
+        if (need > 0)
+          while (lds_min_progress<NW>(progress) < need) __builtin_amdgcn_s_sleep(1);
+        // token batch nb serves chunks [T nb, T nb + T), T = kTokBatchChunks.  It is issued
+        // together with chunk T (nb - 1): every chunk of batch nb - 2 (same half of the token
+        // ring) has been issued by then, and the batch has landed before chunk T nb is issued
+        // because D <= T.
         const int nb = nc / kTokBatchChunks + 1;
         if (nc % kTokBatchChunks == 0 && nb >= 2 && nb * kTokBatchChunks < P) issue_tokens(nb);
         issue_chunk(nc);
@@ -205,80 +243,123 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
     qb0 = as_bf16x8(q0); qb1 = as_bf16x8(q1);
   }
 
-  float m = kFloor, l = 0.f;
-  f32x4 O[4];
+  // Softmax state per lane (one query column): running reference m (not necessarily the
+  // exact maximum, see below), O^T accumulators, and the row sum l, which is accumulated
+  // by a fifth MFMA whose A operand is all ones (every row of Lacc holds the same sum of
+  // the bf16-rounded probabilities of this query, over all four lane groups).
+  float m = kFloor;
+  f32x4 O[4], Lacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+  // The reference m only moves when a score exceeds it by more than kSlack in the base-2
+  // exponent, so probabilities stay below 2^kSlack and the accumulators are rescaled rarely.
+  const float slack = kSlack / c;
 
-  const int32_t* pe = a.phase_end + gd.phase_base + wave * P;
+  // scalar loads (constant address space) for the wave-uniform tables
+  const const_i32_ptr pe = (const_i32_ptr)(a.phase_end + gd.phase_base + wave * P);
   const int64_t step0 = __builtin_amdgcn_readfirstlane(wd.step_begin);
   const uint2* addrs = a.step_addr + step0 * 64 + lane;
   const uint64_t* masks = a.step_mask + step0 * 8;
-  int done = 0;
-  uint2 ad_next = n_steps > 0 ? addrs[0] : make_uint2(0u, 0u);
 
-  for (int ph = 0; ph < P; ++ph) {
-    wg_barrier();                              // chunk ph is in the ring
-    const int end = __builtin_amdgcn_readfirstlane(pe[ph]);
-    for (; done < end; ++done) {
-      const uint2 ad = ad_next;
-      if (done + 1 < n_steps) ad_next = addrs[(int64_t)(done + 1) * 64];
-      const const_u64_ptr mk = (const_u64_ptr)(masks + (int64_t)done * 8);
+  // One step: 32 keys against the 16 queries.  `cur` is the lane's descriptor of step s
+  // (ring byte offsets of its K rows and V reads); it is replaced by that of step
+  // s + kAhead, so that descriptor loads run kAhead steps ahead of their use (one step is
+  // shorter than an L2 hit).
+  auto run_step = [&](uint2& desc, int s) {
+    const uint2 cur = desc;
+    if (s + kAhead < n_steps) desc = addrs[(int64_t)(s + kAhead) * 64];
+    const const_u64_ptr mk = (const_u64_ptr)(masks + (int64_t)s * 8);
 
-      // S^T tiles: keys x queries
-      const unsigned ka0 = ad.x & 0xffffu, ka1 = ad.x >> 16;
-      const bf16x8 k00 = as_bf16x8(*(const uint4*)(Kring + ka0));
-      const bf16x8 k01 = as_bf16x8(*(const uint4*)(Kring + (ka0 ^ 16u)));
-      const bf16x8 k10 = as_bf16x8(*(const uint4*)(Kring + ka1));
-      const bf16x8 k11 = as_bf16x8(*(const uint4*)(Kring + (ka1 ^ 16u)));
-      f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
-      S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k00, qb0, S0, 0, 0, 0);
-      S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k10, qb0, S1, 0, 0, 0);
-      S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k01, qb1, S0, 0, 0, 0);
-      S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k11, qb1, S1, 0, 0, 0);
+    // S^T tiles: keys x queries
+    const unsigned ka0 = cur.x & 0xffffu, ka1 = cur.x >> 16;
+    const bf16x8 k00 = as_bf16x8(*(const uint4*)(Kring + ka0));
+    const bf16x8 k01 = as_bf16x8(*(const uint4*)(Kring + (ka0 ^ 16u)));
+    const bf16x8 k10 = as_bf16x8(*(const uint4*)(Kring + ka1));
+    const bf16x8 k11 = as_bf16x8(*(const uint4*)(Kring + (ka1 ^ 16u)));
+    f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
+    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k00, qb0, S0, 0, 0, 0);
+    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k10, qb0, S1, 0, 0, 0);
+    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k01, qb1, S0, 0, 0, 0);
+    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k11, qb1, S1, 0, 0, 0);
 
-      // V^T operand: transposing LDS reads, 4 keys x 16 dims per 16-lane block
-      const unsigned v0 = ad.y & 0xffffu, v1 = ad.y >> 16;
-      s16x4 va[4][2];
+    // V^T operand: transposing LDS reads, 4 keys x 16 dims per 16-lane block
+    const unsigned v0 = cur.y & 0xffffu, v1 = cur.y >> 16;
+    s16x4 va[4][2];
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        va[dt][0] = lds_read_tr16(Vring + (v0 ^ (unsigned)(dt << 5)));
-        va[dt][1] = lds_read_tr16(Vring + (v1 ^ (unsigned)(dt << 5)));
-      }
+    for (int dt = 0; dt < 4; ++dt) {
+      va[dt][0] = lds_read_tr16(Vring + (v0 ^ (unsigned)(dt << 5)));
+      va[dt][1] = lds_read_tr16(Vring + (v1 ^ (unsigned)(dt << 5)));
+    }
 
-      float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
+    float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sv[e] = mask_select(sv[e], mk[e]);
-      float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                       fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-      mx = max_across_rows(mx);
-      const float m_new = fmaxf(m, mx);
+    for (int e = 0; e < 8; ++e) sv[e] = mask_select(sv[e], mk[e]);
+    float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                     fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    mx = max_across_rows(mx);
+    const bool grow = mx > m + slack;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {      // rare after the first steps
+      const float m_new = grow ? mx : m;
       const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-      const float mc = m_new * c;
       m = m_new;
-      float p[8], psum = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c, -mc)); psum += p[e]; }
-      l = fmaf(l, alpha, psum);
+      Lacc *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) O[dt] *= alpha;
+    }
+    const float mc = m * c;
+    float p[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c, -mc));
 
-      bf16x8 pb;
+    bf16x8 pb;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];
+    for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        s16x8 v8 = {va[dt][0][0], va[dt][0][1], va[dt][0][2], va[dt][0][3],
-                    va[dt][1][0], va[dt][1][1], va[dt][1][2], va[dt][1][3]};
-        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb, O[dt], 0, 0, 0);
+    for (int dt = 0; dt < 4; ++dt) {
+      s16x8 v8 = {va[dt][0][0], va[dt][0][1], va[dt][0][2], va[dt][0][3],
+                  va[dt][1][0], va[dt][1][1], va[dt][1][2], va[dt][1][3]};
+      O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, v8), pb, O[dt], 0, 0, 0);
+    }
+    Lacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb, Lacc, 0, 0, 0);
+  };
+
+  uint2 ad[kAhead];
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) ad[i] = i < n_steps ? addrs[(int64_t)i * 64] : make_uint2(0u, 0u);
+
+  // steps are listed in phase order; pe[ph] = number of steps runnable once chunk ph is in
+  volatile int32_t* const landed_v = landed;
+  volatile int32_t* const my_progress = progress + wave;
+  auto enter_phase = [&](int ph) {             // all steps of earlier phases are done
+    if (lane == 0) *my_progress = ph;
+    while (*landed_v <= ph) __builtin_amdgcn_s_sleep(1);
+  };
+  int ph = 0;
+  if (n_steps > 0) {
+    enter_phase(0);
+    int end = pe[0];
+    for (int s0 = 0; s0 < n_steps; s0 += kAhead) {
+#pragma unroll
+      for (int i = 0; i < kAhead; ++i) {
+        const int s = s0 + i;
+        if (s < n_steps) {
+          if (s >= end) {
+            do { ++ph; end = pe[ph]; } while (s >= end);
+            enter_phase(ph);
+          }
+          run_step(ad[i], s);
+        }
       }
     }
   }
+  // every LDS read of this wave has returned (its results fed the MFMAs above)
+  if (lane == 0) *my_progress = P;
 
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
   if (qrow < 0) return;
-  const float inv = 1.f / l;
+  const float inv = 1.f / Lacc[0];
   __bf16* op = (__bf16*)a.o + b * a.os[0] + h * a.os[1] + qrow * a.os[2] + 4 * g4;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) {
@@ -290,40 +371,27 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
   }
 }
 
-template <int NW, int C, int A, int D>
+template <int NW, int C, int A, int D, int S>
 static litevar_status launch(const AttnArgs& a, hipStream_t st) {
-  constexpr int NR = A + 1 + D;
-  const size_t smem = (size_t)NR * C * kRingRowBytes * 2 + 2 * kTokBatchChunks * C * sizeof(int32_t);
-  static thread_local bool attr_set = false;
-  if (!attr_set) {
-    litevar_status rc = hip_check(
-        hipFuncSetAttribute((const void*)k_attn_bf16<NW, C, A, D>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem),
-        "hipFuncSetAttribute(max dynamic LDS)");
-    if (rc) return rc;
-    attr_set = true;
-  }
   const int64_t bh8 = ((int64_t)a.B * a.H + 7) / 8 * 8;
   const int64_t blocks = bh8 * a.n_groups;
   if (blocks > 0x7fffffff) return fail(LITEVAR_E_UNSUPPORTED, "grid too large");
   const float c = a.sm_scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((k_attn_bf16<NW, C, A, D>), dim3((unsigned)blocks), dim3((NW + 1) * 64), smem, st,
-                     a, c);
+  hipLaunchKernelGGL((k_attn_bf16<NW, C, A, D, S>), dim3((unsigned)blocks), dim3((NW + 1) * 64), 0, st, a, c);
   return hip_check(hipGetLastError(), "bf16 attention launch");
 }
 
 litevar_status launch_attn_bf16(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
   const int nw = pl->waves_per_group, C = pl->chunk_keys, NR = pl->ring_chunks;
-  const int key = nw * 1000 + C * 10 + (NR - 2);
+  const int D = pl->prefetch_chunks, S = NR - 2 - D;
+  const int key = nw * 10000 + C * 100 + D * 10 + S;
   switch (key) {
-    case 8322: return launch<8, 32, 1, 2>(a, st);
-    case 8323: return launch<8, 32, 1, 3>(a, st);
-    case 8642: return launch<8, 64, 1, 2>(a, st);
-    case 8643: return launch<8, 64, 1, 3>(a, st);
-    case 4322: return launch<4, 32, 1, 2>(a, st);
-    case 4323: return launch<4, 32, 1, 3>(a, st);
-    case 4642: return launch<4, 64, 1, 2>(a, st);
-    case 4643: return launch<4, 64, 1, 3>(a, st);
+#define LV_CASE(nw_, c_, d_, s_) case nw_ * 10000 + c_ * 100 + d_ * 10 + s_: return launch<nw_, c_, 1, d_, s_>(a, st);
+    LV_CASE(8, 32, 2, 0) LV_CASE(8, 32, 2, 2) LV_CASE(8, 32, 3, 2) LV_CASE(8, 32, 4, 3)
+    LV_CASE(8, 64, 2, 0) LV_CASE(8, 64, 2, 1)
+    LV_CASE(4, 32, 2, 0) LV_CASE(4, 32, 2, 2) LV_CASE(4, 32, 3, 2) LV_CASE(4, 32, 4, 3)
+    LV_CASE(4, 64, 2, 0) LV_CASE(4, 64, 2, 1)
+#undef LV_CASE
     default: break;
   }
   return fail(LITEVAR_E_PLAN_CORRUPT, "no kernel for waves=%d chunk=%d ring=%d", nw, C, NR);

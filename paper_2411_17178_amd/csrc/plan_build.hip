@@ -9,12 +9,12 @@ namespace lv {
 
 // ---- host: descriptor -> geometry ------------------------------------------
 
-static void choose_tiling(Geom& g, int waves, int chunk, int depth) {
+static void choose_tiling(Geom& g, int waves, int chunk, int depth, int spare) {
   g.NW = waves;
   g.C = chunk; g.D = depth; g.A = 1;
   if (waves == 8) { g.RH = 4; g.RW = 2; }   // 16 rows x 8 columns of queries
   else { g.RH = 2; g.RW = 2; }              // 8 x 8 queries
-  g.NR = g.A + 1 + g.D;
+  g.NR = g.A + 1 + g.D + spare;
   g.logC = 0;
   while ((1 << g.logC) < g.C) ++g.logC;
 }
@@ -60,13 +60,17 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
   if (waves != 4 && waves != 8)
     return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4 or 8 (got %d)", waves);
   int chunk = opts ? opts->chunk_keys : 0, depth = opts ? opts->prefetch_chunks : 0;
+  int spare = opts ? opts->spare_chunks : -1;
   if (chunk == 0) chunk = 32;
   if (depth == 0) depth = 2;
-  if (chunk != 32 && chunk != 64)
-    return fail(LITEVAR_E_INVALID_ARG, "chunk_keys must be 0, 32 or 64 (got %d)", chunk);
-  if (depth != 2 && depth != 3)
-    return fail(LITEVAR_E_INVALID_ARG, "prefetch_chunks must be 0, 2 or 3 (got %d)", depth);
-  choose_tiling(g, waves, chunk, depth);
+  if (spare < 0) spare = chunk == 32 ? 2 : 1;
+  static const int ok[][3] = {{32, 2, 0}, {32, 2, 2}, {32, 3, 2}, {32, 4, 3}, {64, 2, 0}, {64, 2, 1}};
+  bool found = false;
+  for (const auto& t : ok) found |= (t[0] == chunk && t[1] == depth && t[2] == spare);
+  if (!found)
+    return fail(LITEVAR_E_INVALID_ARG, "unsupported (chunk_keys, prefetch_chunks, spare_chunks) = (%d, %d, %d)",
+                chunk, depth, spare);
+  choose_tiling(g, waves, chunk, depth, spare);
 
   int64_t ng = 0, np = 0;
   for (int i = 0; i < g.qe - g.qb; ++i) {

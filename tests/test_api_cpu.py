@@ -34,10 +34,20 @@ def test_library_exports_every_declared_symbol(lv):
     assert lib.litevar_status_string(0) == b"ok"
 
 
-def test_plan_struct_matches_header(lv):
-    # the ctypes mirror must have the C struct's size: 3*8 + 12*4 + 4*8 + 12*8 + 2*32*4 + 2*4
-    from paper_2411_17178_amd.binding import _Plan
-    assert C.sizeof(_Plan) == 24 + 48 + 32 + 96 + 256 + 8
+def test_plan_struct_matches_header(lv, tmp_path):
+    # the ctypes mirrors must have the C structs' sizes and field offsets (asked of gcc)
+    import subprocess
+    from paper_2411_17178_amd.binding import _MaskDesc, _Plan, _PlanOpts
+    src = tmp_path / "sz.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "litevar.h"\n'
+                   'int main(void){printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(litevar_plan), '
+                   'sizeof(litevar_plan_opts), sizeof(litevar_mask_desc), offsetof(litevar_plan, n_steps), '
+                   'offsetof(litevar_plan, off), offsetof(litevar_plan, n_sink_scales));return 0;}\n')
+    exe = tmp_path / "sz"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert got == [C.sizeof(_Plan), C.sizeof(_PlanOpts), C.sizeof(_MaskDesc), _Plan.n_steps.offset,
+                   _Plan.off.offset, _Plan.n_sink_scales.offset]
 
 
 def _totals():
@@ -79,6 +89,8 @@ def test_descriptor_validation(lv):
         dict(scales=[1, 2, 3], radius=1, q_scales=(2, 2)),
         dict(scales=[1, 2, 3], radius=1, q_scales=(0, 4)),
         dict(scales=[1, 2, 3], radius=1, waves_per_group=5),
+        dict(scales=[1, 2, 3], radius=1, waves_per_group=(4, 48, 2)),
+        dict(scales=[1, 2, 3], radius=1, waves_per_group=(4, 32, 5, 0)),
     ]
     for kw in bad:
         with pytest.raises(E) as ei:
