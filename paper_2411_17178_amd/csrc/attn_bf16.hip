@@ -112,6 +112,12 @@ __device__ inline void lds_store_i32_nowait(int32_t* p, int v) {
   const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) int32_t*)p;
   asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(v) : "memory");
 }
+__device__ inline int lds_load_i32_nowait(const int32_t* p) {   // waits for LDS only, not for vector memory
+  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
+  int v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+  return v;
+}
 template <int NW> __device__ inline int lds_min_progress(const int32_t* p) {
   static_assert(NW == 4 || NW == 8, "progress words are read four at a time");
   const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
@@ -331,11 +337,12 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
   for (int i = 0; i < kAhead; ++i) ad[i] = i < n_steps ? addrs[(int64_t)i * 64] : make_uint2(0u, 0u);
 
   // steps are listed in phase order; pe[ph] = number of steps runnable once chunk ph is in
-  volatile int32_t* const landed_v = landed;
-  volatile int32_t* const my_progress = progress + wave;
+  // (flag accesses in inline assembly: a volatile access would also wait for the wave's
+  // outstanding descriptor prefetches)
+  int32_t* const my_progress = progress + wave;
   auto enter_phase = [&](int ph) {             // all steps of earlier phases are done
-    if (lane == 0) *my_progress = ph;
-    while (*landed_v <= ph) __builtin_amdgcn_s_sleep(1);
+    if (lane == 0) lds_store_i32_nowait(my_progress, ph);
+    while (lds_load_i32_nowait(landed) <= ph) __builtin_amdgcn_s_sleep(1);
   };
   int ph = 0;
   if (n_steps > 0) {
@@ -356,7 +363,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
     }
   }
   // every LDS read of this wave has returned (its results fed the MFMAs above)
-  if (lane == 0) *my_progress = P;
+  if (lane == 0) lds_store_i32_nowait(my_progress, P);
 
   if (qrow < 0) return;
   const float inv = 1.f / Lacc[0];
