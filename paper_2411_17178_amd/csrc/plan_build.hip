@@ -86,7 +86,21 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
 
 static uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
 
+// The sizing walk visits every (patch, key) pair on the host (tens of milliseconds for the
+// largest plans).  Callers size and then build with the same descriptor, often repeatedly,
+// so the last result is remembered per thread, keyed by the whole geometry.
+static thread_local struct { bool valid; Geom g; PlanSizes z; } g_last_sizing = {false, {}, {}};
+
+static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z);
+
 litevar_status size_plan(const Geom& g, PlanSizes& z) {
+  if (g_last_sizing.valid && memcmp(&g_last_sizing.g, &g, sizeof g) == 0) { z = g_last_sizing.z; return LITEVAR_OK; }
+  const litevar_status rc = size_plan_uncached(g, z);
+  if (rc == LITEVAR_OK) { g_last_sizing.g = g; g_last_sizing.z = z; g_last_sizing.valid = true; }
+  return rc;
+}
+
+static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z) {
   memset(&z, 0, sizeof z);
   for (int grp = 0; grp < g.n_groups; ++grp) {
     int k, gy, gx;
@@ -179,27 +193,53 @@ __global__ void k_count(Geom g, BlobPtrs p) {
   }
 }
 
-// K2b: exclusive scans (one thread; a few thousand entries, run once per plan)
-__global__ void k_scan(Geom g, BlobPtrs p, Caps caps) {
-  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+// K2b: exclusive scans over groups (union keys, phase entries) and waves (steps) by one
+// 1024-thread block: per-thread partial sums over a contiguous slice, a serial scan of the
+// 1024 partials, then the slice is revisited
+__global__ __launch_bounds__(1024) void k_scan(Geom g, BlobPtrs p, Caps caps) {
+  __shared__ int64_t part[3][1024];
+  const int t = threadIdx.x;
+  const int per = (g.n_groups + 1023) / 1024;
+  const int g0 = t * per < g.n_groups ? t * per : g.n_groups;
+  const int g1 = g0 + per < g.n_groups ? g0 + per : g.n_groups;
   int64_t steps = 0, uni = 0, phe = 0, pairs = 0;
-  for (int grp = 0; grp < g.n_groups; ++grp) {
+  for (int grp = g0; grp < g1; ++grp) {
+    uni += (int64_t)p.groups[grp].n_phases * g.C; phe += (int64_t)p.groups[grp].n_phases * g.NW;
+    for (int w = 0; w < g.NW; ++w) { steps += p.waves[grp * g.NW + w].n_steps; pairs += p.waves[grp * g.NW + w].pairs; }
+  }
+  part[0][t] = steps; part[1][t] = uni; part[2][t] = phe;
+  // total of the kept pairs: a plain tree reduction through LDS
+  __shared__ int64_t psum[1024];
+  __shared__ int64_t tot[3];
+  psum[t] = pairs;
+  __syncthreads();
+  for (int d = 512; d > 0; d >>= 1) { if (t < d) psum[t] += psum[t + d]; __syncthreads(); }
+  if (t < 3) {
+    int64_t acc = 0;
+    for (int i = 0; i < 1024; ++i) { const int64_t v = part[t][i]; part[t][i] = acc; acc += v; }
+    tot[t] = acc;                              // total steps, union keys, phase entries
+  }
+  __syncthreads();
+  steps = part[0][t]; uni = part[1][t]; phe = part[2][t];
+  for (int grp = g0; grp < g1; ++grp) {
     GroupDesc& gd = p.groups[grp];
     gd.union_base = (int32_t)uni; gd.phase_base = (int32_t)phe;
     uni += (int64_t)gd.n_phases * g.C; phe += (int64_t)gd.n_phases * g.NW;
     for (int w = 0; w < g.NW; ++w) {
       WaveDesc& wd = p.waves[grp * g.NW + w];
-      wd.step_begin = (int32_t)steps; steps += wd.n_steps; pairs += wd.pairs;
+      wd.step_begin = (int32_t)steps; steps += wd.n_steps;
     }
   }
-  Header h;
-  memset(&h, 0, sizeof h);
-  h.magic = kMagic; h.blob_bytes = caps.bytes;
-  h.n_groups = g.n_groups; h.n_waves = g.n_groups * g.NW;
-  h.n_steps = steps; h.n_union = uni; h.n_phase_entries = phe; h.retained_pairs = pairs;
-  h.error = (steps != caps.n_steps || uni != caps.n_union || phe != caps.n_phase_entries ||
-             pairs != caps.retained_pairs) ? 1 : 0;
-  *p.hdr = h;
+  if (t == 0) {
+    Header h;
+    memset(&h, 0, sizeof h);
+    h.magic = kMagic; h.blob_bytes = caps.bytes;
+    h.n_groups = g.n_groups; h.n_waves = g.n_groups * g.NW;
+    h.n_steps = tot[0]; h.n_union = tot[1]; h.n_phase_entries = tot[2]; h.retained_pairs = psum[0];
+    h.error = (h.n_steps != caps.n_steps || h.n_union != caps.n_union ||
+               h.n_phase_entries != caps.n_phase_entries || h.retained_pairs != caps.retained_pairs) ? 1 : 0;
+    *p.hdr = h;
+  }
 }
 
 // K2c: the group's key list (token indices), padded to whole chunks with its last key
@@ -303,7 +343,7 @@ litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipSt
   hipLaunchKernelGGL(k_window_table, dim3((nwin + 255) / 256), dim3(256), 0, st, g, p.win);
   const int nw = g.n_groups * g.NW;
   hipLaunchKernelGGL(k_count, dim3((nw + 63) / 64), dim3(64), 0, st, g, p);
-  hipLaunchKernelGGL(k_scan, dim3(1), dim3(64), 0, st, g, p, caps);
+  hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, st, g, p, caps);
   hipLaunchKernelGGL(k_fill_union, dim3(g.n_groups), dim3(256), 0, st, g, p, caps);
   hipLaunchKernelGGL(k_fill_steps, dim3(nw), dim3(64), 0, st, g, p, caps);
   return hip_check(hipGetLastError(), "plan builder launch");
