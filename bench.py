@@ -44,6 +44,24 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload
+    (FETCH_SIZE and WRITE_SIZE runs, each scaled by a known-size copy kernel); None when
+    no summary exists for this kernel instance."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        f"k_attn_bf16_{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    for line in open(path):
+        if " = " in line:
+            a, b = line.split(" = ", 1)
+            kv[a.strip()] = b.strip()
+    if kv.get("kernel") != kernel or kv.get("workload") != workload:
+        return None
+    return int(kv["traffic_bytes_per_launch"])
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -141,6 +159,13 @@ def main():
     bytes_layer = BH * (2 * plan.q_len * 64 * esize + 2 * plan.kv_len * 64 * esize)
     achieved = bytes_layer / (kernel_us * 1e-6) / 1e9
 
+    if w.dtype == "bf16":
+        kname = (f"k_attn_bf16<{plan.waves_per_group}, {plan.chunk_keys}, 1, {plan.prefetch_chunks}, "
+                 f"{plan.ring_chunks - plan.prefetch_chunks - 2}>")
+    else:
+        kname = "k_attn_f32"
+    traffic = None if args.dense else measured_traffic(w.name, kname)
+
     out = {
         "metric": "windowed-attn effective TFLOP/s (retained pairs)",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -159,8 +184,8 @@ def main():
         "mfma_frac_retained": round(kernel_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "tile_density": round(plan.retained_pairs / plan.computed_pairs, 4),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "k_attn_bf16" if w.dtype == "bf16" else "k_attn_f32",
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "kernel": kname,
                      "bytes_per_launch": bytes_layer, "kernel_us": round(kernel_us, 3)},
     }
 

@@ -13,13 +13,11 @@ def _lq(scales, q_scales):
     return int(sum(int(s) * int(s) for s in scales[q_scales[0]:q_scales[1]]))
 
 
-def make_qkv(scales, batch, heads, head_dim, dtype, seed, input_scale=1.0, q_scales=None,
-             bh_limit=None):
+def make_qkv(scales, batch, heads, head_dim, dtype, seed, input_scale=1.0, q_scales=None):
     """Q [B,H,Lq,D], K, V [B,H,L,D] as CPU torch tensors of `dtype` ("f32"|"bf16").
 
     Draws fp32 N(0,1) in the order Q, K, V from torch.Generator(seed), multiplies
-    by input_scale, casts once.  bh_limit is unused for generation order; callers
-    slice afterwards.
+    by input_scale, casts once.
     """
     g = torch.Generator(device="cpu").manual_seed(int(seed))
     L, Lq = seq_len(scales), _lq(scales, q_scales)
