@@ -30,112 +30,14 @@
 // phase it has reached; a compute wave waits only when its next keys are not there yet,
 // the loader only when the ring slot it wants to refill is still being read.  Waves of
 // one workgroup may therefore be several chunks apart (the ring has S spare chunks).
-#include "internal.h"
+#include <type_traits>
+
+#include "attn_bf16_common.h"
 
 namespace lv {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((address_space(3))) void lds_void;
-typedef const __attribute__((address_space(1))) void global_void;
-// constant address space: a load from a wave-uniform address becomes a scalar load
-typedef const __attribute__((address_space(4))) uint64_t* const_u64_ptr;
-typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
-
-constexpr float kFloor = -1.0e30f;   // initial softmax reference: keeps exp2 arguments finite
-constexpr float kSlack = 6.0f;       // base-2 exponent by which a score may exceed the reference
-constexpr int kTokBatchChunks = 8;   // chunks covered by one token batch
-constexpr int kAhead = 4;            // step descriptors fetched ahead by a compute wave
-
-__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-__device__ inline s16x4 lds_read_tr16(const unsigned char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-}
-
-// keep `s` where the lane's bit of the wave-uniform `mask` is set, else -inf
-// (inverse ballot: the SGPR pair becomes the select condition of one v_cndmask)
-__device__ inline float mask_select(float s, uint64_t mask) {
-  return __builtin_amdgcn_inverse_ballot_w64(mask) ? s : -INFINITY;
-}
-
-// max over the four lanes l, l^16, l^32, l^48: v_permlane32_swap exchanges the upper half
-// of its first register with the lower half of its second, v_permlane16_swap the odd
-// 16-lane rows of the first with the even rows of the second.  (The two results are
-// copied into scalars before the float reinterpretation: a __builtin_bit_cast applied
-// directly to an element of the returned vector reads element 0 for both.)
-__device__ inline float max_across_rows(float x) {
-  const unsigned u = __float_as_uint(x);
-  auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  const unsigned a0 = a[0], a1 = a[1];
-  const unsigned v = __float_as_uint(fmaxf(__uint_as_float(a0), __uint_as_float(a1)));
-  auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-  const unsigned b0 = b[0], b1 = b[1];
-  return fmaxf(__uint_as_float(b0), __uint_as_float(b1));
-}
-
-template <int N> __device__ inline void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  // gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt/lgkmcnt left at max
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
-}
-
-// N consecutive-stride LDS words (stride 32 bytes) written by earlier LDS-DMA loads of this
-// wave whose completion the caller has already established.  Inline assembly, because the
-// compiler would otherwise order these reads after a vmcnt(0) wait (it cannot know which
-// DMA loads have landed) and so drain the prefetch queue.
-template <int N> __device__ inline void lds_read_tokens(const int32_t* p, int (&t)[N]);
-template <> __device__ inline void lds_read_tokens<4>(const int32_t* p, int (&t)[4]) {
-  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
-  asm volatile("ds_read_b32 %0, %4\n\tds_read_b32 %1, %4 offset:32\n\t"
-               "ds_read_b32 %2, %4 offset:64\n\tds_read_b32 %3, %4 offset:96\n\t"
-               "s_waitcnt lgkmcnt(0)"
-               : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]) : "v"(a) : "memory");
-}
-template <> __device__ inline void lds_read_tokens<8>(const int32_t* p, int (&t)[8]) {
-  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
-  asm volatile("ds_read_b32 %0, %8\n\tds_read_b32 %1, %8 offset:32\n\t"
-               "ds_read_b32 %2, %8 offset:64\n\tds_read_b32 %3, %8 offset:96\n\t"
-               "ds_read_b32 %4, %8 offset:128\n\tds_read_b32 %5, %8 offset:160\n\t"
-               "ds_read_b32 %6, %8 offset:192\n\tds_read_b32 %7, %8 offset:224\n\t"
-               "s_waitcnt lgkmcnt(0)"
-               : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]),
-                 "=&v"(t[6]), "=&v"(t[7]) : "v"(a) : "memory");
-}
-
-// LDS accesses of the loader wave that must not wait for its outstanding LDS-DMA loads
-// (the compiler orders ordinary LDS accesses after vmcnt(0) once a DMA load is pending)
-__device__ inline void lds_store_i32_nowait(int32_t* p, int v) {
-  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) int32_t*)p;
-  asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(v) : "memory");
-}
-__device__ inline int lds_load_i32_nowait(const int32_t* p) {   // waits for LDS only, not for vector memory
-  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
-  int v;
-  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
-  return v;
-}
-template <int NW> __device__ inline int lds_min_progress(const int32_t* p) {
-  static_assert(NW == 4 || NW == 8, "progress words are read four at a time");
-  const unsigned a = (unsigned)(uintptr_t)(__attribute__((address_space(3))) const int32_t*)p;
-  typedef __attribute__((ext_vector_type(4))) int i32x4;
-  i32x4 x, y;
-  if constexpr (NW == 8) {
-    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %2 offset:16\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(x), "=&v"(y) : "v"(a) : "memory");
-  } else {
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(x) : "v"(a) : "memory");
-    y = x;
-  }
-  const int m0 = min(min(x[0], x[1]), min(x[2], x[3])), m1 = min(min(y[0], y[1]), min(y[2], y[3]));
-  return min(m0, m1);
-}
-
 template <int NW, int C, int A, int D, int S>
-__global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c) {
+__global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(6, 8))) void k_attn_bf16(AttnArgs a, float c) {
   constexpr int NR = A + 1 + D + S;             // ring depth in chunks: look-back, current, in flight, spare
   constexpr int R = NR * C;                     // ring slots
   constexpr int IPC = C * 2 * kRingRowBytes / 1024;   // DMA instructions per chunk (1 KiB each)
@@ -274,9 +176,13 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
   // (ring byte offsets of its K rows and V reads); it is replaced by that of step
   // s + kAhead, so that descriptor loads run kAhead steps ahead of their use (one step is
   // shorter than an L2 hit).
-  auto run_step = [&](uint2& desc, int s) {
+  // The prefetch is unconditional (clamped to the wave's last step) so that the number of
+  // loads in flight is the same on every path and the wait before `cur` is used can leave
+  // the kAhead - 1 younger ones outstanding.
+  const int last_step = n_steps - 1;
+  auto run_step = [&](uint2& desc, int s, auto prefetch) {
     const uint2 cur = desc;
-    if (s + kAhead < n_steps) desc = addrs[(int64_t)(s + kAhead) * 64];
+    if constexpr (decltype(prefetch)::value) desc = addrs[(int64_t)min(s + kAhead, last_step) * 64];
     const const_u64_ptr mk = (const_u64_ptr)(masks + (int64_t)s * 8);
 
     // S^T tiles: keys x queries
@@ -334,7 +240,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
 
   uint2 ad[kAhead];
 #pragma unroll
-  for (int i = 0; i < kAhead; ++i) ad[i] = i < n_steps ? addrs[(int64_t)i * 64] : make_uint2(0u, 0u);
+  for (int i = 0; i < kAhead; ++i) ad[i] = addrs[(int64_t)max(min(i, last_step), 0) * 64];
 
   // steps are listed in phase order; pe[ph] = number of steps runnable once chunk ph is in
   // (flag accesses in inline assembly: a volatile access would also wait for the wave's
@@ -348,17 +254,25 @@ __global__ __launch_bounds__((NW + 1) * 64) void k_attn_bf16(AttnArgs a, float c
   if (n_steps > 0) {
     enter_phase(0);
     int end = pe[0];
-    for (int s0 = 0; s0 < n_steps; s0 += kAhead) {
+    auto advance_to = [&](int s) {             // wait until step s may run
+      if (s >= end) {
+        do { ++ph; end = pe[ph]; } while (s >= end);
+        enter_phase(ph);
+      }
+    };
+    int s0 = 0;
+    for (; s0 + kAhead <= n_steps; s0 += kAhead) {
 #pragma unroll
       for (int i = 0; i < kAhead; ++i) {
-        const int s = s0 + i;
-        if (s < n_steps) {
-          if (s >= end) {
-            do { ++ph; end = pe[ph]; } while (s >= end);
-            enter_phase(ph);
-          }
-          run_step(ad[i], s);
-        }
+        advance_to(s0 + i);
+        run_step(ad[i], s0 + i, std::true_type{});
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < kAhead - 1; ++i) {
+      if (s0 + i < n_steps) {
+        advance_to(s0 + i);
+        run_step(ad[i], s0 + i, std::false_type{});
       }
     }
   }
@@ -390,6 +304,7 @@ static litevar_status launch(const AttnArgs& a, hipStream_t st) {
 
 litevar_status launch_attn_bf16(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
   const int nw = pl->waves_per_group, C = pl->chunk_keys, NR = pl->ring_chunks;
+  if (nw == 16) return launch_attn_bf16_pair(pl, a, st);
   const int D = pl->prefetch_chunks, S = NR - 2 - D;
   const int key = nw * 10000 + C * 100 + D * 10 + S;
   switch (key) {

@@ -43,5 +43,6 @@ struct AttnArgs {
 
 litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
 litevar_status launch_attn_bf16(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
+litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
 
 }  // namespace lv

@@ -31,7 +31,7 @@ constexpr uint64_t kMagic = 0x4c56415257494e31ull;  // "LVARWIN1"
 struct Geom {
   int K, qb, qe, n_sink;
   int L, Lq, q0, smax;
-  int NW, RH, RW;       // waves per group; group shape in patches (RH x RW)
+  int NW, RH, RW;       // patches per group; group shape in patches (RH x RW)
   int C, NR, A, D;      // chunk keys (a power of two), ring depth in chunks, look-back and
                         // prefetch depth in chunks; NR = A + 1 + D
   int logC;
@@ -50,7 +50,7 @@ struct GroupDesc {   // 32 bytes
   int32_t k;           // query scale
   int32_t gy, gx;      // group position in units of groups
   int32_t phase_base;  // first entry in phase_end (NW * n_phases int32 entries, wave-major)
-  int32_t pad;
+  int32_t ident;       // union entries [0, ident) hold token i at position i
 };
 
 struct WaveDesc {    // 32 bytes
@@ -218,8 +218,19 @@ LV_HD int popcount32(unsigned v) { return __builtin_popcount(v); }
 
 struct CountSink {
   int64_t pairs = 0;
+  int logC = 0, last_phase = -1, run = 0, max_phase_steps = 0;   // most steps ending in one chunk
   LV_HD void key(int, int, int, int, unsigned qmask) { pairs += popcount32(qmask); }
-  LV_HD void close(int, int, int) {}
+  LV_HD void close(int, int, int last_upos) {
+    const int ph = last_upos >> logC;
+    run = ph == last_phase ? run + 1 : 1;
+    last_phase = ph;
+    if (run > max_phase_steps) max_phase_steps = run;
+  }
 };
+
+// steps of one patch that may end in one chunk for the 16-patch kernel, which prefetches
+// exactly this many step descriptors per patch and phase (with 64-key chunks and 32-key
+// steps a chunk can end a straddling step, one full step and one more)
+constexpr int kMaxPhaseSteps = 3;
 
 }  // namespace lv

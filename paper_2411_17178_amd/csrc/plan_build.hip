@@ -12,8 +12,9 @@ namespace lv {
 static void choose_tiling(Geom& g, int waves, int chunk, int depth, int spare) {
   g.NW = waves;
   g.C = chunk; g.D = depth; g.A = 1;
-  if (waves == 8) { g.RH = 4; g.RW = 2; }   // 16 rows x 8 columns of queries
-  else { g.RH = 2; g.RW = 2; }              // 8 x 8 queries
+  if (waves == 16) { g.RH = 4; g.RW = 4; }       // 16 x 16 queries
+  else if (waves == 8) { g.RH = 4; g.RW = 2; }   // 16 rows x 8 columns of queries
+  else { g.RH = 2; g.RW = 2; }                   // 8 x 8 queries
   g.NR = g.A + 1 + g.D + spare;
   g.logC = 0;
   while ((1 << g.logC) < g.C) ++g.logC;
@@ -55,15 +56,17 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
   if (waves == 0) {
     int sq = 0;
     for (int k = g.qb; k < g.qe; ++k) if (g.s[k] > sq) sq = g.s[k];
-    waves = sq >= 8 ? 8 : 4;
+    waves = sq >= 8 ? 16 : 4;
   }
-  if (waves != 4 && waves != 8)
-    return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4 or 8 (got %d)", waves);
+  if (waves != 4 && waves != 8 && waves != 16)
+    return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4, 8 or 16 (got %d)", waves);
   int chunk = opts ? opts->chunk_keys : 0, depth = opts ? opts->prefetch_chunks : 0;
   int spare = opts ? opts->spare_chunks : -1;
-  if (chunk == 0) chunk = 32;
+  if (chunk == 0) chunk = waves == 16 ? 64 : 32;
   if (depth == 0) depth = 2;
-  if (spare < 0) spare = chunk == 32 ? 2 : 1;
+  if (spare < 0) spare = waves == 16 ? 0 : chunk == 32 ? 2 : 1;
+  if (waves == 16 && (chunk != 64 || depth != 2 || spare != 0))
+    return fail(LITEVAR_E_INVALID_ARG, "16 patches per group need (chunk_keys, prefetch_chunks, spare_chunks) = (64, 2, 0)");
   static const int ok[][3] = {{32, 2, 0}, {32, 2, 2}, {32, 3, 2}, {32, 4, 3}, {64, 2, 0}, {64, 2, 1}};
   bool found = false;
   for (const auto& t : ok) found |= (t[0] == chunk && t[1] == depth && t[2] == spare);
@@ -112,8 +115,12 @@ static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z) {
     z.n_phase_entries += (int64_t)nph * g.NW;
     for (int w = 0; w < g.NW; ++w) {
       CountSink sink;
+      sink.logC = g.logC;
       const int ns = walk_patch(g, e, patch_extent(g, k, gy, gx, w), sink);
       if (ns > 65535) return fail(LITEVAR_E_UNSUPPORTED, "a query patch needs more than 65535 steps");
+      if (g.NW == 16 && sink.max_phase_steps > kMaxPhaseSteps)
+        return fail(LITEVAR_E_UNSUPPORTED, "a query patch has %d steps ending in one chunk (limit %d)",
+                    sink.max_phase_steps, kMaxPhaseSteps);
       z.n_steps += ns;
       z.retained_pairs += sink.pairs;
     }
@@ -188,7 +195,19 @@ __global__ void k_count(Geom g, BlobPtrs p) {
     GroupDesc gd;
     gd.union_base = 0; gd.n_union = group_union_keys(g, e);
     gd.n_phases = (gd.n_union + g.C - 1) / g.C;
-    gd.k = k; gd.gy = gy; gd.gx = gx; gd.phase_base = 0; gd.pad = 0;
+    gd.k = k; gd.gy = gy; gd.gx = gx; gd.phase_base = 0;
+    // leading union entries whose token equals their position: whole key scales from
+    // scale 0 on, then the first rows of the next box if it starts at the scale's origin
+    int ident = 0;
+    for (int j = 0; j <= k; ++j) {
+      const Box b = window_box(g, k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+      const int gw = b.xhi - b.xlo + 1, rows = b.yhi - b.ylo + 1;
+      if (b.ylo != 0 || b.xlo != 0 || g.off[j] != ident) break;
+      if (gw != g.s[j]) { ident += gw; break; }
+      ident += rows * gw;
+      if (rows != g.s[j]) break;
+    }
+    gd.ident = ident;
     p.groups[grp] = gd;
   }
 }

@@ -59,7 +59,7 @@ def _totals():
     return out
 
 
-@pytest.mark.parametrize("waves", [0, 4, 8])
+@pytest.mark.parametrize("waves", [0, 4, 8, 16])
 def test_host_sizing_reproduces_pair_counts(lv, waves):
     totals = _totals()
     for name, w in workloads.CONFIGS.items():

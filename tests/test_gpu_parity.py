@@ -72,7 +72,7 @@ def _window_table_from_oracle(scales, radii, n_sink):
 
 
 @pytest.mark.parametrize("name", ["tiny_f32", "var_d16", "var_d30_kvstep", "var_d36_512"])
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
 def test_mask_bit_exact(lv, name, waves):
     w = workloads.get(name)
     radii = oracle.expand_radii(w.scales, w.radius)
@@ -109,7 +109,7 @@ def test_index_sets_2k(lv):
     assert (cols.cpu().numpy() == cols_ref).all()
 
 
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
 def test_csr_matches_dense_small(lv, waves):
     scales, radii = (1, 2, 3, 5, 7, 10), [0, 1, 2, 1, 3, 2]
     plan = lv.litevar_mask_build(scales, 0, radii, 1, None, waves_per_group=waves)
@@ -135,7 +135,7 @@ MASK_CASES = [
 
 
 @pytest.mark.parametrize("case", range(len(MASK_CASES)))
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
 def test_mask_edge_cases(lv, case, waves):
     scales, rad, n_sink, q_scales = MASK_CASES[case]
     per = rad if isinstance(rad, list) else None
@@ -155,7 +155,7 @@ def test_tiny_f32(lv):
     w = workloads.get("tiny_f32")
     q, k, v = workloads.make_workload_qkv(w)
     for n_sink in (0, 3):
-        for waves in (4, 8):
+        for waves in (4, 8, 16):
             plan = _plan(lv, w, waves, n_sink=n_sink)
             o = _gpu_attn(lv, plan, q, k, v, w.sm_scale)
             ref = _oracle_attn(w.scales, [1] * 4, q, k, v, w.sm_scale, n_sink)
@@ -165,14 +165,14 @@ def test_tiny_f32(lv):
 def test_tiny_bf16_kernel_on_tiny_shape(lv):
     w = workloads.get("tiny_f32")
     q, k, v = workloads.make_qkv(w.scales, 1, 1, 64, "bf16", 0)
-    for waves in (4, 8):
+    for waves in (4, 8, 16):
         plan = _plan(lv, w, waves)
         o = _gpu_attn(lv, plan, q, k, v, w.sm_scale)
         ref = _oracle_attn(w.scales, [1] * 4, q, k, v, w.sm_scale)
         assert _maxerr(o, ref) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
 def test_var_d16(lv, waves):
     w = workloads.get("var_d16")
     q, k, v = workloads.make_workload_qkv(w)
@@ -186,7 +186,7 @@ def test_var_d16(lv, waves):
     assert torch.equal(o[:, :, 0].cpu(), v[:, :, 0])
 
 
-@pytest.mark.parametrize("waves", [0, 4, 8])
+@pytest.mark.parametrize("waves", [0, 4, 8, 16])
 def test_var_d30_kv_step(lv, waves):
     w = workloads.get("var_d30_kvstep")
     q, k, v = workloads.make_workload_qkv(w)
@@ -270,7 +270,7 @@ ATTN_CASES = [
 
 @pytest.mark.parametrize("case", range(len(ATTN_CASES)))
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 16])
 def test_attn_edge_cases(lv, case, dtype, waves):
     scales, rad, n_sink, q_scales, B, H = ATTN_CASES[case]
     per = rad if isinstance(rad, list) else None
