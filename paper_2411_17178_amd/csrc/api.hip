@@ -223,6 +223,7 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   a.step_mask = (const uint64_t*)(blob + plan->off[kSecStepMask]);
   a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
   a.n_groups = plan->n_groups;
+  a.q_len = plan->q_len;
   if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);
   return launch_attn_bf16(plan, a, (hipStream_t)stream);
 }

@@ -10,7 +10,7 @@
 // (one 128-byte K row and one 128-byte V row per key, 16-byte pieces XOR-swizzled by
 // slot).  Phase c = the steps whose last key lies in chunk c; they read chunks c and c-1.
 // At the start of phase c every wave issues, in this order,
-//   the descriptor loads of its steps of phase c+1 (register-returning, always six),
+//   the descriptor loads of its steps of phase c+1 (register-returning, at most six),
 //   the token load for its rows of chunk c+3,
 //   two global_load_lds_dwordx4 for its eight K rows and eight V rows of chunk c+2
 //   (the slot held chunk c-2, which nobody reads after phase c-1),
@@ -38,6 +38,7 @@ namespace {
 
 constexpr int kPairWaves = 8;         // waves per workgroup
 constexpr int kPairChunk = 64;        // keys per chunk
+constexpr int kPrefetched = 2;        // step descriptors per patch and phase that are fetched a phase ahead
 
 __device__ inline unsigned lds_addr(const void* p) {
   return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
@@ -77,7 +78,7 @@ __device__ inline void lds_wait(uint2 (&va)[4][2]) {
 struct PatchState {       // one query patch of a wave
   bf16x8 qb0, qb1;        // Q^T as the B operand: lane (n, g4) holds Q[query n][16 g4 .. +15]
   f32x4 O[4], Lacc;       // O^T accumulators and row sums
-  float m;                // softmax reference
+  float thr, negmc;       // softmax reference m as m + slack (scores above it move m) and -m c
   int qrow;               // local query row of this lane's query column, -1 = none
 };
 
@@ -123,50 +124,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     __builtin_amdgcn_global_load_lds((global_void*)(Kp + src), (lds_void*)(Kring + slot0 * kRingRowBytes), 16, 0, 0);
     __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
   };
-
-  // ---- the wave's two patches: p and its partner two patch rows below, columns swapped ----
-  const int pa = wave, pb_ = ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1);
-  const WaveDesc wdA = a.waves[grp * 16 + pa], wdB = a.waves[grp * 16 + pb_];
-  const int nsA = __builtin_amdgcn_readfirstlane(wdA.n_steps), nsB = __builtin_amdgcn_readfirstlane(wdB.n_steps);
-  const int64_t sbA = __builtin_amdgcn_readfirstlane(wdA.step_begin), sbB = __builtin_amdgcn_readfirstlane(wdB.step_begin);
-  const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * P);
-  const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * P);
-  // (an idle patch has no steps of its own: its clamped descriptor loads read step 0 of the plan)
-  const uint2* addrA = a.step_addr + (nsA > 0 ? sbA : 0) * 64 + lane;
-  const uint2* addrB = a.step_addr + (nsB > 0 ? sbB : 0) * 64 + lane;
-  const uint64_t* maskA = a.step_mask + sbA * 8;
-  const uint64_t* maskB = a.step_mask + sbB * 8;
-
-  auto init_patch = [&](PatchState& ps, const WaveDesc& wd) {
-    const int dy = n >> 2, dx = n & 3;
-    ps.qrow = (dy < wd.ny && dx < wd.nx) ? wd.q_base + dy * wd.sk + dx : -1;
-    uint4 z = {0, 0, 0, 0}, q0 = z, q1 = z;
-    if (ps.qrow >= 0) {
-      const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ps.qrow * a.qs[2] + 16 * g4;
-      q0 = *(const uint4*)qp; q1 = *(const uint4*)(qp + 8);
-    }
-    ps.qb0 = as_bf16x8(q0); ps.qb1 = as_bf16x8(q1);
-    ps.m = kFloor;
-    ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt) ps.O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  };
-  PatchState A, B;
-  init_patch(A, wdA);
-  init_patch(B, wdB);
-
-  bf16x8 ones;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
-  const float slack = kSlack / c;
-
-  // descriptors of the steps of one phase: always kMaxPhaseSteps loads per patch (clamped
-  // to the patch's last step), so that the number of loads in flight is static
-  auto load_desc = [&](uint2 (&d)[kMaxPhaseSteps], const uint2* addrs, int first, int n_steps) {
-#pragma unroll
-    for (int i = 0; i < kMaxPhaseSteps; ++i)
-      d[i] = addrs[(int64_t)max(min(first + i, n_steps - 1), 0) * 64];
-  };
   // this lane's row of chunk t (the load is unconditional so that the number of vector
   // memory operations per phase is static)
   auto load_tok = [&](int t) -> int {
@@ -175,17 +132,93 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     return i < ident ? i : v;
   };
 
-  // ---- prologue: descriptors of phase 0, tokens of chunks 0..2, chunks 0 and 1 ----
-  uint2 dA[kMaxPhaseSteps], dB[kMaxPhaseSteps], dAn[kMaxPhaseSteps], dBn[kMaxPhaseSteps];
-  load_desc(dA, addrA, 0, nsA);
-  load_desc(dB, addrB, 0, nsB);
-  int tok_next = load_tok(P > 2 ? 2 : 0);               // token of the chunk issued next
-  {
+  // ---- prologue, first half: chunks 0 and 1 go out before anything else.  The key list
+  // usually starts with whole key scales (token = position), which needs no token load.
+  if (ident >= 2 * C || ident >= P * C) {
+    issue_chunk(0, row);
+    if (P > 1) issue_chunk(1, C + row);
+  } else {
     const int t0 = load_tok(0), t1 = load_tok(P > 1 ? 1 : 0);
     issue_chunk(0, t0);
     if (P > 1) issue_chunk(1, t1);
   }
-  if (P > 1) wait_vmcnt<2>(); else wait_vmcnt<0>();     // chunk 0 is in; chunk 1 may be in flight
+
+  // ---- the wave's two patches: p and its partner two patch rows below, columns swapped.
+  // Descriptor words through scalar loads: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16}
+  const int pa = wave, pb_ = ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1);
+  const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp * 16 + pa), wB = (const_i32_ptr)(a.waves + grp * 16 + pb_);
+  const int64_t sbA = wA[0], sbB = wB[0];
+  const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * P);
+  const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * P);
+  const uint2* addrA = a.step_addr + sbA * 64 + lane;
+  const uint2* addrB = a.step_addr + sbB * 64 + lane;
+  const uint64_t* maskA = a.step_mask + sbA * 8;
+  const uint64_t* maskB = a.step_mask + sbB * 8;
+
+  // Q rows are loaded unconditionally (from a clamped row) and zeroed afterwards where the
+  // lane has no query, so that the loads of both patches go out back to back
+  auto init_patch = [&](PatchState& ps, const const_i32_ptr w) {
+    const int q_base = w[2], sk = w[3] & 0xffff, ny = w[3] >> 16, nx = w[4] & 0xffff;
+    const int dy = n >> 2, dx = n & 3;
+    const bool valid = dy < ny && dx < nx;
+    ps.qrow = valid ? q_base + dy * sk + dx : -1;
+    const int ld_row = max(min(q_base + dy * sk + dx, a.q_len - 1), 0);
+    const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
+    uint4 q0 = *(const uint4*)qp, q1 = *(const uint4*)(qp + 8);
+    const uint4 z = {0, 0, 0, 0};
+    if (!valid) { q0 = z; q1 = z; }
+    ps.qb0 = as_bf16x8(q0); ps.qb1 = as_bf16x8(q1);
+    ps.thr = kFloor; ps.negmc = -kFloor * c;
+    ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) ps.O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  };
+  PatchState A, B;
+  init_patch(A, wA);
+  init_patch(B, wB);
+
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+  const float slack = kSlack / c;
+
+  // descriptors of the `count` steps of one phase that start at step `first`.  The loads
+  // are conditional, but all of them are older than the unconditional tail of a phase's
+  // vector memory operations (token load, two DMA loads), so the waits stay exact.
+  auto load_desc = [&](uint2 (&d)[kPrefetched], const uint2* addrs, int first, int count) {
+#pragma unroll
+    for (int i = 0; i < kPrefetched; ++i)
+      if (i < count) d[i] = addrs[(int64_t)(first + i) * 64];
+  };
+
+  // ---- prologue, second half: descriptors of phase 0 and the token of chunk 2; then
+  // everything (both chunks included: they were issued first) has to be in ----
+  uint2 dA[kPrefetched], dB[kPrefetched], dAn[kPrefetched], dBn[kPrefetched];
+  // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
+  // phase ph + 2 is fetched during phase ph
+  int endA = peA[0], endB = peB[0];
+  int end1A = peA[P > 1 ? 1 : 0], end1B = peB[P > 1 ? 1 : 0];
+#pragma unroll
+  for (int i = 0; i < kPrefetched; ++i) { dA[i] = make_uint2(0u, 0u); dB[i] = dA[i]; dAn[i] = dA[i]; dBn[i] = dA[i]; }
+  load_desc(dA, addrA, 0, endA);
+  load_desc(dB, addrB, 0, endB);
+  int tok_next = load_tok(P > 2 ? 2 : 0);               // token of the chunk issued next
+  // Touch every 128-byte line of the group's step descriptors and lane masks once.  All
+  // workgroups walk the same plan in lock-step, so without this each phase's first access
+  // to its part of the plan would be an HBM miss on the critical path; the loads complete
+  // while the first chunks are on their way anyway.
+  {
+    const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
+    const int64_t first = wF[0];
+    const int n_group_steps = wL[0] + wL[1] - wF[0];
+    const char* da = (const char*)(a.step_addr + first * 64);
+    const char* ma = (const char*)(a.step_mask + first * 8);
+    int acc = 0;
+    for (int off = tid * 128; off < n_group_steps * 512; off += kPairWaves * 64 * 128) acc ^= *(const int*)(da + off);
+    for (int off = tid * 128; off < n_group_steps * 64; off += kPairWaves * 64 * 128) acc ^= *(const int*)(ma + off);
+    asm volatile("" : : "v"(acc));                       // keeps the loads
+  }
+  wait_vmcnt<0>();
   asm volatile("s_barrier" ::: "memory");
 
   // One step: 32 keys against the 16 queries of patch ps.
@@ -202,26 +235,31 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
 #pragma unroll
     for (int e = 0; e < 8; ++e) sv[e] = mask_select(sv[e], mk[e]);
-    float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                     fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-    mx = max_across_rows(mx);
-    const bool grow = mx > ps.m + slack;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {      // rare after the first steps
-      const float m_new = grow ? mx : ps.m;
-      const float alpha = __builtin_amdgcn_exp2f((ps.m - m_new) * c);
-      ps.m = m_new;
+    // The reference m of a query only moves when one of its scores exceeds it by more than
+    // the slack (probabilities stay below 2^kSlack).  The common case needs the lane's own
+    // maximum only; the maximum over the query's four lanes is formed when some lane of the
+    // wave has crossed its threshold.
+    const float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                           fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    if (__builtin_amdgcn_ballot_w64(mx > ps.thr) != 0) {   // rare after the first steps
+      const float mxr = max_across_rows(mx);
+      const bool grow = mxr > ps.thr;
+      const float negmc_new = grow ? -mxr * c : ps.negmc;
+      const float alpha = __builtin_amdgcn_exp2f(negmc_new - ps.negmc);
+      ps.negmc = negmc_new;
+      ps.thr = grow ? mxr + slack : ps.thr;
       ps.Lacc *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) ps.O[dt] *= alpha;
     }
-    const float mc = ps.m * c;
+    const float negmc = ps.negmc;
     // V^T operands: issued here rather than before the softmax, where sixteen more live
     // registers would not fit
     uint2 va[4][2];
     lds_read_v<VOFF>(lds_addr(Kring + (cur.y & 0xffffu)), lds_addr(Kring + (cur.y >> 16)), va);
     float p[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c, -mc));
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c, negmc));
     bf16x8 pb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];
@@ -241,23 +279,29 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   int doneA = 0, doneB = 0;                             // steps finished so far
   auto run_phase = [&](int ph, auto dma, auto next) {
     constexpr bool DMA = decltype(dma)::value, NEXT = decltype(next)::value;
-    const int endA = nsA > 0 ? peA[ph] : 0, endB = nsB > 0 ? peB[ph] : 0;
-    if constexpr (NEXT) {                               // descriptors of the next phase
-      load_desc(dAn, addrA, endA, nsA);
-      load_desc(dBn, addrB, endB, nsB);
+    int end2A = 0, end2B = 0;                           // (scalar loads, two phases ahead of their use)
+    if constexpr (NEXT) {
+      end2A = peA[min(ph + 2, P - 1)]; end2B = peB[min(ph + 2, P - 1)];
+      load_desc(dAn, addrA, endA, end1A - endA);        // descriptors of the next phase
+      load_desc(dBn, addrB, endB, end1B - endB);
     }
     if constexpr (DMA) {
       const int tok = tok_next;
       tok_next = load_tok(min(ph + 3, P - 1));
       issue_chunk(ph + 2, tok);
     }
+    // (a patch rarely has more than kPrefetched steps in a phase; the descriptors of the
+    // others are loaded on the spot, which also waits for the DMA loads just issued)
 #pragma unroll
-    for (int i = 0; i < kMaxPhaseSteps; ++i)
+    for (int i = 0; i < kPrefetched; ++i)
       if (doneA + i < endA) run_step(A, dA[i], maskA, doneA + i);
+    for (int s = doneA + kPrefetched; s < endA; ++s) run_step(A, addrA[(int64_t)s * 64], maskA, s);
 #pragma unroll
-    for (int i = 0; i < kMaxPhaseSteps; ++i)
+    for (int i = 0; i < kPrefetched; ++i)
       if (doneB + i < endB) run_step(B, dB[i], maskB, doneB + i);
+    for (int s = doneB + kPrefetched; s < endB; ++s) run_step(B, addrB[(int64_t)s * 64], maskB, s);
     doneA = endA; doneB = endB;
+    endA = end1A; endB = end1B; end1A = end2A; end1B = end2B;
     if constexpr (NEXT) {
       // everything but the two DMA loads just issued has landed: chunk ph + 1, the next
       // descriptors and tokens.  All LDS reads of this phase have returned (each step
@@ -265,7 +309,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       if constexpr (DMA) wait_vmcnt<2>(); else wait_vmcnt<0>();
       asm volatile("s_barrier" ::: "memory");
 #pragma unroll
-      for (int i = 0; i < kMaxPhaseSteps; ++i) { dA[i] = dAn[i]; dB[i] = dBn[i]; }
+      for (int i = 0; i < kPrefetched; ++i) { dA[i] = dAn[i]; dB[i] = dBn[i]; }
     }
   };
   {

@@ -39,6 +39,7 @@ struct AttnArgs {
   const int32_t* union_tok; const uint2* step_addr; const uint64_t* step_mask;
   const int32_t* step_tok;
   int n_groups;
+  int q_len;                     // query rows per (batch, head)
 };
 
 litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);

@@ -218,19 +218,8 @@ LV_HD int popcount32(unsigned v) { return __builtin_popcount(v); }
 
 struct CountSink {
   int64_t pairs = 0;
-  int logC = 0, last_phase = -1, run = 0, max_phase_steps = 0;   // most steps ending in one chunk
   LV_HD void key(int, int, int, int, unsigned qmask) { pairs += popcount32(qmask); }
-  LV_HD void close(int, int, int last_upos) {
-    const int ph = last_upos >> logC;
-    run = ph == last_phase ? run + 1 : 1;
-    last_phase = ph;
-    if (run > max_phase_steps) max_phase_steps = run;
-  }
+  LV_HD void close(int, int, int) {}
 };
-
-// steps of one patch that may end in one chunk for the 16-patch kernel, which prefetches
-// exactly this many step descriptors per patch and phase (with 64-key chunks and 32-key
-// steps a chunk can end a straddling step, one full step and one more)
-constexpr int kMaxPhaseSteps = 3;
 
 }  // namespace lv

@@ -115,12 +115,8 @@ static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z) {
     z.n_phase_entries += (int64_t)nph * g.NW;
     for (int w = 0; w < g.NW; ++w) {
       CountSink sink;
-      sink.logC = g.logC;
       const int ns = walk_patch(g, e, patch_extent(g, k, gy, gx, w), sink);
       if (ns > 65535) return fail(LITEVAR_E_UNSUPPORTED, "a query patch needs more than 65535 steps");
-      if (g.NW == 16 && sink.max_phase_steps > kMaxPhaseSteps)
-        return fail(LITEVAR_E_UNSUPPORTED, "a query patch has %d steps ending in one chunk (limit %d)",
-                    sink.max_phase_steps, kMaxPhaseSteps);
       z.n_steps += ns;
       z.retained_pairs += sink.pairs;
     }
