@@ -132,15 +132,16 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     return i < ident ? i : v;
   };
 
-  // ---- prologue, first half: chunks 0 and 1 go out before anything else.  The key list
-  // usually starts with whole key scales (token = position), which needs no token load.
+  // ---- prologue, first part: chunk 0 goes out before anything else.  The key list usually
+  // starts with whole key scales (token = position), which needs no token load.
+  int tok1;
   if (ident >= 2 * C || ident >= P * C) {
     issue_chunk(0, row);
-    if (P > 1) issue_chunk(1, C + row);
+    tok1 = P > 1 ? C + row : row;
   } else {
-    const int t0 = load_tok(0), t1 = load_tok(P > 1 ? 1 : 0);
+    const int t0 = load_tok(0);
+    tok1 = load_tok(P > 1 ? 1 : 0);
     issue_chunk(0, t0);
-    if (P > 1) issue_chunk(1, t1);
   }
 
   // ---- the wave's two patches: p and its partner two patch rows below, columns swapped.
@@ -155,8 +156,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const uint64_t* maskA = a.step_mask + sbA * 8;
   const uint64_t* maskB = a.step_mask + sbB * 8;
 
-  // Q rows are loaded unconditionally (from a clamped row) and zeroed afterwards where the
-  // lane has no query, so that the loads of both patches go out back to back
+  // Q rows are loaded unconditionally, from a clamped row where the lane has no query: such
+  // a column of S^T holds scores of some other query, all of its mask bits are clear and it
+  // is never stored, and MFMA columns do not mix
   auto init_patch = [&](PatchState& ps, const const_i32_ptr w) {
     const int q_base = w[2], sk = w[3] & 0xffff, ny = w[3] >> 16, nx = w[4] & 0xffff;
     const int dy = n >> 2, dx = n & 3;
@@ -164,10 +166,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     ps.qrow = valid ? q_base + dy * sk + dx : -1;
     const int ld_row = max(min(q_base + dy * sk + dx, a.q_len - 1), 0);
     const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
-    uint4 q0 = *(const uint4*)qp, q1 = *(const uint4*)(qp + 8);
-    const uint4 z = {0, 0, 0, 0};
-    if (!valid) { q0 = z; q1 = z; }
-    ps.qb0 = as_bf16x8(q0); ps.qb1 = as_bf16x8(q1);
+    ps.qb0 = as_bf16x8(*(const uint4*)qp); ps.qb1 = as_bf16x8(*(const uint4*)(qp + 8));
     ps.thr = kFloor; ps.negmc = -kFloor * c;
     ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -203,22 +202,32 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   load_desc(dA, addrA, 0, endA);
   load_desc(dB, addrB, 0, endB);
   int tok_next = load_tok(P > 2 ? 2 : 0);               // token of the chunk issued next
-  // Touch every 128-byte line of the group's step descriptors and lane masks once.  All
-  // workgroups walk the same plan in lock-step, so without this each phase's first access
-  // to its part of the plan would be an HBM miss on the critical path; the loads complete
-  // while the first chunks are on their way anyway.
+  // All workgroups walk the same plan in lock-step, so each phase's first access to its part
+  // of the plan would be an HBM miss on every workgroup's critical path.  The workgroups of
+  // one XCD (they share an L2) therefore touch the group's step descriptors and lane masks
+  // once, each its own slice of the 128-byte lines, while the first chunk is on its way.
+  int warm = 0;
   {
     const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
     const int64_t first = wF[0];
     const int n_group_steps = wL[0] + wL[1] - wF[0];
     const char* da = (const char*)(a.step_addr + first * 64);
     const char* ma = (const char*)(a.step_mask + first * 8);
-    int acc = 0;
-    for (int off = tid * 128; off < n_group_steps * 512; off += kPairWaves * 64 * 128) acc ^= *(const int*)(da + off);
-    for (int off = tid * 128; off < n_group_steps * 64; off += kPairWaves * 64 * 128) acc ^= *(const int*)(ma + off);
-    asm volatile("" : : "v"(acc));                       // keeps the loads
+    const int n_share = (a.B * a.H + 7) / 8, me = seq / a.n_groups;    // workgroups of this group on this XCD
+    const int lines_d = n_group_steps * 4, lines = lines_d + (n_group_steps + 1) / 2;
+    const int per = (lines + n_share - 1) / n_share;
+    // one unconditional load per thread (a static count keeps the compiler's waits exact);
+    // a slice longer than the workgroup is touched in part only, which costs nothing but speed
+    const int l = min(me * per + min(tid, per - 1), lines - 1);
+    const char* src = l < lines_d ? da + (int64_t)l * 128 : ma + (int64_t)(l - lines_d) * 128;
+    warm = *(const int*)src;
   }
-  wait_vmcnt<0>();
+  // chunk 1 last: everything before it is in once at most its two loads are outstanding.
+  // (Unconditional, so that the wait is exact on every path: a one-chunk list loads chunk 0
+  // a second time into the unused slot 1.)
+  issue_chunk(1, tok1);
+  wait_vmcnt<2>();
+  asm volatile("" : : "v"(warm));                        // the only use of the plan-touching load: keeps it
   asm volatile("s_barrier" ::: "memory");
 
   // One step: 32 keys against the 16 queries of patch ps.
@@ -320,6 +329,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   }
 
   // ---- epilogue ----
+  wait_vmcnt<0>();        // no LDS-DMA load may outlive the workgroup (one-phase lists get here with one in flight)
   auto store_patch = [&](const PatchState& ps) {
     if (ps.qrow < 0) return;
     const float inv = 1.f / ps.Lacc[0];
