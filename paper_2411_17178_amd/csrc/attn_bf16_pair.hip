@@ -79,7 +79,6 @@ struct PatchState {       // one query patch of a wave
   bf16x8 qb0, qb1;        // Q^T as the B operand: lane (n, g4) holds Q[query n][16 g4 .. +15]
   f32x4 O[4], Lacc;       // O^T accumulators and row sums
   float thr, negmc;       // softmax reference m as m + slack (scores above it move m) and -m c
-  int qrow;               // local query row of this lane's query column, -1 = none
 };
 
 }  // namespace
@@ -132,8 +131,29 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     return i < ident ? i : v;
   };
 
-  // ---- prologue, first part: chunk 0 goes out before anything else.  The key list usually
-  // starts with whole key scales (token = position), which needs no token load.
+  // ---- prologue, scalar part.  Everything that comes through scalar loads (patch
+  // descriptors, phase tables, the extent of the group's steps) is fetched before the first
+  // vector memory operation: behind the burst of first chunks of all workgroups a scalar
+  // miss would take microseconds, and the vector loads below depend on these values.
+  // Patch descriptor words: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16}
+  const int pa = wave, pb_ = ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1);   // p and its partner two patch rows below, columns swapped
+  const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp * 16 + pa), wB = (const_i32_ptr)(a.waves + grp * 16 + pb_);
+  const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
+  const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * P);
+  const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * P);
+  struct PatchWords { int step_begin, q_base, sk_ny, nx_kq; };
+  const PatchWords pwA = {wA[0], wA[2], wA[3], wA[4]}, pwB = {wB[0], wB[2], wB[3], wB[4]};
+  const int first_step = wF[0], n_group_steps = wL[0] + wL[1] - first_step;
+  // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
+  // phase ph + 2 is fetched during phase ph
+  int endA = peA[0], endB = peB[0];
+  int end1A = peA[P > 1 ? 1 : 0], end1B = peB[P > 1 ? 1 : 0];
+  asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.nx_kq),
+               "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.nx_kq),
+               "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
+
+  // ---- prologue, vector part: chunk 0 first.  The key list usually starts with whole key
+  // scales (token = position), which needs no token load.
   int tok1;
   if (ident >= 2 * C || ident >= P * C) {
     issue_chunk(0, row);
@@ -144,27 +164,25 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     issue_chunk(0, t0);
   }
 
-  // ---- the wave's two patches: p and its partner two patch rows below, columns swapped.
-  // Descriptor words through scalar loads: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16}
-  const int pa = wave, pb_ = ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1);
-  const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp * 16 + pa), wB = (const_i32_ptr)(a.waves + grp * 16 + pb_);
-  const int64_t sbA = wA[0], sbB = wB[0];
-  const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * P);
-  const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * P);
+  const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
   const uint2* addrA = a.step_addr + sbA * 64 + lane;
   const uint2* addrB = a.step_addr + sbB * 64 + lane;
   const uint64_t* maskA = a.step_mask + sbA * 8;
   const uint64_t* maskB = a.step_mask + sbB * 8;
 
+  // local query row of this lane's query column (-1 = none)
+  auto query_row = [&](const PatchWords& w, int n, bool clamped) -> int {
+    const int sk = w.sk_ny & 0xffff, ny = w.sk_ny >> 16, nx = w.nx_kq & 0xffff;
+    const int dy = n >> 2, dx = n & 3;
+    const int r = w.q_base + dy * sk + dx;
+    if (clamped) return max(min(r, a.q_len - 1), 0);
+    return (dy < ny && dx < nx) ? r : -1;
+  };
   // Q rows are loaded unconditionally, from a clamped row where the lane has no query: such
   // a column of S^T holds scores of some other query, all of its mask bits are clear and it
   // is never stored, and MFMA columns do not mix
-  auto init_patch = [&](PatchState& ps, const const_i32_ptr w) {
-    const int q_base = w[2], sk = w[3] & 0xffff, ny = w[3] >> 16, nx = w[4] & 0xffff;
-    const int dy = n >> 2, dx = n & 3;
-    const bool valid = dy < ny && dx < nx;
-    ps.qrow = valid ? q_base + dy * sk + dx : -1;
-    const int ld_row = max(min(q_base + dy * sk + dx, a.q_len - 1), 0);
+  auto init_patch = [&](PatchState& ps, const PatchWords& w) {
+    const int ld_row = query_row(w, n, true);
     const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
     ps.qb0 = as_bf16x8(*(const uint4*)qp); ps.qb1 = as_bf16x8(*(const uint4*)(qp + 8));
     ps.thr = kFloor; ps.negmc = -kFloor * c;
@@ -173,8 +191,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     for (int dt = 0; dt < 4; ++dt) ps.O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   };
   PatchState A, B;
-  init_patch(A, wA);
-  init_patch(B, wB);
+  init_patch(A, pwA);
+  init_patch(B, pwB);
 
   bf16x8 ones;
 #pragma unroll
@@ -190,13 +208,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       if (i < count) d[i] = addrs[(int64_t)(first + i) * 64];
   };
 
-  // ---- prologue, second half: descriptors of phase 0 and the token of chunk 2; then
-  // everything (both chunks included: they were issued first) has to be in ----
+  // descriptors of phase 0 and the token of chunk 2
   uint2 dA[kPrefetched], dB[kPrefetched], dAn[kPrefetched], dBn[kPrefetched];
-  // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
-  // phase ph + 2 is fetched during phase ph
-  int endA = peA[0], endB = peB[0];
-  int end1A = peA[P > 1 ? 1 : 0], end1B = peB[P > 1 ? 1 : 0];
 #pragma unroll
   for (int i = 0; i < kPrefetched; ++i) { dA[i] = make_uint2(0u, 0u); dB[i] = dA[i]; dAn[i] = dA[i]; dBn[i] = dA[i]; }
   load_desc(dA, addrA, 0, endA);
@@ -208,11 +221,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // once, each its own slice of the 128-byte lines, while the first chunk is on its way.
   int warm = 0;
   {
-    const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
-    const int64_t first = wF[0];
-    const int n_group_steps = wL[0] + wL[1] - wF[0];
-    const char* da = (const char*)(a.step_addr + first * 64);
-    const char* ma = (const char*)(a.step_mask + first * 8);
+    const char* da = (const char*)(a.step_addr + (int64_t)first_step * 64);
+    const char* ma = (const char*)(a.step_mask + (int64_t)first_step * 8);
     const int n_share = (a.B * a.H + 7) / 8, me = seq / a.n_groups;    // workgroups of this group on this XCD
     const int lines_d = n_group_steps * 4, lines = lines_d + (n_group_steps + 1) / 2;
     const int per = (lines + n_share - 1) / n_share;
@@ -294,16 +304,21 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       load_desc(dAn, addrA, endA, end1A - endA);        // descriptors of the next phase
       load_desc(dBn, addrB, endB, end1B - endB);
     }
+    int tok = 0;
     if constexpr (DMA) {
-      const int tok = tok_next;
+      tok = tok_next;
       tok_next = load_tok(min(ph + 3, P - 1));
-      issue_chunk(ph + 2, tok);
     }
     // (a patch rarely has more than kPrefetched steps in a phase; the descriptors of the
     // others are loaded on the spot, which also waits for the DMA loads just issued)
 #pragma unroll
-    for (int i = 0; i < kPrefetched; ++i)
+    for (int i = 0; i < kPrefetched; ++i) {
       if (doneA + i < endA) run_step(A, dA[i], maskA, doneA + i);
+      // The chunk goes out after the wave's first step rather than right behind the barrier,
+      // where all eight waves' loads would queue up in front of the first K reads; it still
+      // is the youngest vector memory operation of the phase.
+      if constexpr (DMA) { if (i == 0) issue_chunk(ph + 2, tok); }
+    }
     for (int s = doneA + kPrefetched; s < endA; ++s) run_step(A, addrA[(int64_t)s * 64], maskA, s);
 #pragma unroll
     for (int i = 0; i < kPrefetched; ++i)
@@ -330,10 +345,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   // ---- epilogue ----
   wait_vmcnt<0>();        // no LDS-DMA load may outlive the workgroup (one-phase lists get here with one in flight)
-  auto store_patch = [&](const PatchState& ps) {
-    if (ps.qrow < 0) return;
+  auto store_patch = [&](const PatchState& ps, const PatchWords& w) {
+    int n_again = n;                           // recomputed from scratch: the row is not worth a
+    asm volatile("" : "+v"(n_again));          // register (or a spill slot) through the loop
+    const int qrow = query_row(w, n_again, false);
+    if (qrow < 0) return;
     const float inv = 1.f / ps.Lacc[0];
-    __bf16* op = (__bf16*)a.o + b * a.os[0] + h * a.os[1] + ps.qrow * a.os[2] + 4 * g4;
+    __bf16* op = (__bf16*)a.o + b * a.os[0] + h * a.os[1] + qrow * a.os[2] + 4 * g4;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {
       bf16x4 r;
@@ -343,8 +361,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       if (shared) *(bf16x4*)(op + (a.B / 2) * a.os[0] + 16 * dt) = r;
     }
   };
-  store_patch(A);
-  store_patch(B);
+  store_patch(A, pwA);
+  store_patch(B, pwB);
 }
 
 litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
