@@ -103,11 +103,12 @@ typedef struct litevar_plan {
 /* Tuning knobs of the plan; zero-initialise for the defaults. */
 typedef struct litevar_plan_opts {
   int32_t waves_per_group;  /* 4x4 query patches per workgroup: 0 = choose; else 4, 8 or 16 */
-  int32_t chunk_keys;       /* keys per LDS ring chunk: 0 = choose; else 32 or 64 */
+  int32_t chunk_keys;       /* keys per phase of the key stream: 0 = choose; else 32, 64 or 128 */
   int32_t prefetch_chunks;  /* chunks kept in flight: 0 = choose */
   int32_t spare_chunks;     /* extra ring chunks that let waves drift apart: -1 = choose.
                                Supported (chunk, prefetch, spare): (32,2,0) (32,2,2) (32,3,2) (32,4,3)
-                               (64,2,0) (64,2,1); 16 patches per group take (64,2,0) only */
+                               (64,2,0) (64,2,1); 16 patches per group take (128,2,0) only: phases
+                               of 128 keys, ring and prefetch depth counted in 64-key chunks */
   int32_t reserved[4];
 } litevar_plan_opts;
 

@@ -6,23 +6,27 @@
 // one scale) of one (batch, head).  Every wave owns two patches (a top and a bottom one,
 // so that it has keys in most parts of the stream) and one eighth of the loading.
 //
-// The group's key list is streamed once through an LDS ring of NRB chunks of 64 keys
+// The group's key list is streamed once through an LDS ring of five chunks of 64 keys
 // (one 128-byte K row and one 128-byte V row per key, 16-byte pieces XOR-swizzled by
-// slot).  Phase c = the steps whose last key lies in chunk c; they read chunks c and c-1.
-// At the start of phase c every wave issues, in this order,
-//   the descriptor loads of its steps of phase c+1 (register-returning, at most six),
-//   the token load for its rows of chunk c+3,
-//   two global_load_lds_dwordx4 for its eight K rows and eight V rows of chunk c+2
-//   (the slot held chunk c-2, which nobody reads after phase c-1),
-// then runs its steps of phase c, waits until at most the two youngest of its vector
-// memory operations (the two LDS-DMA loads just issued) are outstanding -- vmcnt is
-// in-order, so chunk c+1 and everything else has landed -- and joins the barrier.  Two
-// chunks (32 KiB) per workgroup are therefore in flight at any time, and a key row is
-// moved from HBM/L2 to LDS exactly once per (batch, head, group).
+// slot; 80 KiB, so that two workgroups share a CU).  A phase is two chunks: phase p = the
+// steps whose last key lies in chunk 2p or 2p+1.  A step spans at most two consecutive
+// chunks, so these steps read chunks 2p-1 .. 2p+1, while chunks 2p+2 and 2p+3 land in the
+// other two slots (chunk t lives in slot t mod 5; those slots held chunks 2p-3 and 2p-2,
+// which nobody reads after the barrier that ends phase p-1).  In phase p a wave
+//   issues the descriptor loads of its steps of this phase beyond the first of each patch
+//     and of the first step of each patch of phase p+1, and the token loads for its rows
+//     of chunks 2p+4 and 2p+5,
+//   runs the first step of each patch,
+//   issues four global_load_lds_dwordx4: its eight K rows and eight V rows of chunks 2p+2
+//     and 2p+3 (not right behind the barrier, where the loads of all eight waves would
+//     queue up in front of the first K reads),
+//   runs its other steps, waits for all its vector memory operations and joins the barrier.
+// Two chunks (32 KiB) per workgroup are in flight during a phase, and a key row is moved
+// from HBM/L2 to LDS exactly once per (batch, head, group).
 //
 // A wave that issues LDS-DMA loads must read LDS through inline assembly: the compiler
 // cannot tell which of them a plain LDS read depends on and would wait for all
-// (vmcnt(0)), which would serialise the stream.
+// (vmcnt(0)) before every read.
 //
 // Step arithmetic is that of the 8-patch kernel: S^T = K_tile . Q^T by
 // v_mfma_f32_16x16x32_bf16 (a lane owns one query column and four keys per tile), scalar
@@ -37,8 +41,11 @@ namespace lv {
 namespace {
 
 constexpr int kPairWaves = 8;         // waves per workgroup
-constexpr int kPairChunk = 64;        // keys per chunk
-constexpr int kPrefetched = 2;        // step descriptors per patch and phase that are fetched a phase ahead
+constexpr int kDmaKeys = 64;          // keys per chunk (the unit of loading and of ring slot reuse)
+constexpr int kPhaseChunks = 2;       // chunks per phase
+constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two landing
+constexpr int kLater = 2;             // descriptors per patch, beyond the first step of a phase, that are
+                                      // fetched at the start of the phase
 
 __device__ inline unsigned lds_addr(const void* p) {
   return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
@@ -83,13 +90,11 @@ struct PatchState {       // one query patch of a wave
 
 }  // namespace
 
-template <int NRB>
 __global__ __launch_bounds__(kPairWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void k_attn_bf16_pair(AttnArgs a, float c) {
-  constexpr int C = kPairChunk;
-  constexpr int R = NRB * C;                       // ring slots
+  constexpr int C = kDmaKeys;
+  constexpr int R = kRingChunks * C;               // ring slots
   constexpr int VOFF = R * kRingRowBytes;          // V ring follows the K ring
-  static_assert(2 * R * kRingRowBytes <= 65536, "static LDS");
   __shared__ __align__(1024) unsigned char smem[2 * R * kRingRowBytes];
   unsigned char* const Kring = smem;
   unsigned char* const Vring = smem + VOFF;
@@ -108,6 +113,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int lane = tid & 63;
   const int n = lane & 15, g4 = lane >> 4;
   const int P = __builtin_amdgcn_readfirstlane(gd.n_phases);
+  const int NC = kPhaseChunks * P;                 // chunks of the (padded) key list
 
   // ---- loading duty: rows [8 wave, 8 wave + 8) of every chunk ----
   const unsigned char* Kp = (const unsigned char*)((const __bf16*)a.k + b * a.ks[0] + h * a.ks[1]);
@@ -116,17 +122,15 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int32_t* utok = a.union_tok + gd.union_base;
   const int ident = __builtin_amdgcn_readfirstlane(gd.ident);   // union entries [0, ident) are token i at position i
   const int row = 8 * wave + (lane >> 3), pos = lane & 7;
-  auto issue_chunk = [&](int t, int tok) {             // chunk t -> ring slots (t % NRB) * 64 ...
-    const int slot0 = (t % NRB) * C + 8 * wave;
+  auto issue_chunk = [&](int t, int tok) {             // chunk t -> ring slots (t % 5) * 64 ...
+    const int slot0 = (t % kRingChunks) * C + 8 * wave;
     const unsigned slot = (unsigned)(slot0 + (lane >> 3));
     const unsigned src = (unsigned)tok * row_bytes + (((unsigned)pos ^ ring_swizzle(slot)) << 4);
     __builtin_amdgcn_global_load_lds((global_void*)(Kp + src), (lds_void*)(Kring + slot0 * kRingRowBytes), 16, 0, 0);
     __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
   };
-  // this lane's row of chunk t (the load is unconditional so that the number of vector
-  // memory operations per phase is static)
-  auto load_tok = [&](int t) -> int {
-    const int i = t * C + row;
+  auto load_tok = [&](int t) -> int {                  // this lane's row of chunk t (clamped to the last chunk)
+    const int i = min(t, NC - 1) * C + row;
     const int v = utok[i];
     return i < ident ? i : v;
   };
@@ -145,23 +149,22 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const PatchWords pwA = {wA[0], wA[2], wA[3], wA[4]}, pwB = {wB[0], wB[2], wB[3], wB[4]};
   const int first_step = wF[0], n_group_steps = wL[0] + wL[1] - first_step;
   // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
-  // phase ph + 2 is fetched during phase ph
+  // phase p + 2 is fetched during phase p
   int endA = peA[0], endB = peB[0];
   int end1A = peA[P > 1 ? 1 : 0], end1B = peB[P > 1 ? 1 : 0];
   asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.nx_kq),
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.nx_kq),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
 
-  // ---- prologue, vector part: chunk 0 first.  The key list usually starts with whole key
-  // scales (token = position), which needs no token load.
-  int tok1;
-  if (ident >= 2 * C || ident >= P * C) {
+  // ---- prologue, vector part: chunks 0 and 1 first.  The key list usually starts with
+  // whole key scales (token = position), which needs no token load.
+  if (ident >= 2 * C || ident >= NC * C) {
     issue_chunk(0, row);
-    tok1 = P > 1 ? C + row : row;
+    issue_chunk(1, C + row);
   } else {
-    const int t0 = load_tok(0);
-    tok1 = load_tok(P > 1 ? 1 : 0);
+    const int t0 = load_tok(0), t1 = load_tok(1);
     issue_chunk(0, t0);
+    issue_chunk(1, t1);
   }
 
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
@@ -199,26 +202,26 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
   const float slack = kSlack / c;
 
-  // descriptors of the `count` steps of one phase that start at step `first`.  The loads
-  // are conditional, but all of them are older than the unconditional tail of a phase's
-  // vector memory operations (token load, two DMA loads), so the waits stay exact.
-  auto load_desc = [&](uint2 (&d)[kPrefetched], const uint2* addrs, int first, int count) {
+  // Step descriptors of a patch for one phase: the first step's is fetched during the phase
+  // before (d0), those of the next kLater steps at the start of the phase (dl).
+  uint2 dA0 = make_uint2(0u, 0u), dB0 = dA0, dAl[kLater], dBl[kLater];
 #pragma unroll
-    for (int i = 0; i < kPrefetched; ++i)
-      if (i < count) d[i] = addrs[(int64_t)(first + i) * 64];
+  for (int i = 0; i < kLater; ++i) { dAl[i] = dA0; dBl[i] = dA0; }
+  // (all loads of a phase are unconditional, from clamped indices, so that their number is
+  // static and the compiler's waits stay exact: a conditional load would make it wait for
+  // everything, the chunks in flight included, before each later use of a loaded register)
+  const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
+  auto load_later = [&](uint2 (&d)[kLater], const uint2* addrs, int first, int last) {
+#pragma unroll
+    for (int i = 0; i < kLater; ++i) d[i] = addrs[(int64_t)min(first + 1 + i, last) * 64];
   };
-
-  // descriptors of phase 0 and the token of chunk 2
-  uint2 dA[kPrefetched], dB[kPrefetched], dAn[kPrefetched], dBn[kPrefetched];
-#pragma unroll
-  for (int i = 0; i < kPrefetched; ++i) { dA[i] = make_uint2(0u, 0u); dB[i] = dA[i]; dAn[i] = dA[i]; dBn[i] = dA[i]; }
-  load_desc(dA, addrA, 0, endA);
-  load_desc(dB, addrB, 0, endB);
-  int tok_next = load_tok(P > 2 ? 2 : 0);               // token of the chunk issued next
+  dA0 = addrA[0];
+  dB0 = addrB[0];
+  int tokn0 = load_tok(2), tokn1 = load_tok(3);         // tokens of the chunks issued in phase 0
   // All workgroups walk the same plan in lock-step, so each phase's first access to its part
   // of the plan would be an HBM miss on every workgroup's critical path.  The workgroups of
   // one XCD (they share an L2) therefore touch the group's step descriptors and lane masks
-  // once, each its own slice of the 128-byte lines, while the first chunk is on its way.
+  // once, each its own slice of the 128-byte lines, while the first chunks are on their way.
   int warm = 0;
   {
     const char* da = (const char*)(a.step_addr + (int64_t)first_step * 64);
@@ -226,17 +229,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     const int n_share = (a.B * a.H + 7) / 8, me = seq / a.n_groups;    // workgroups of this group on this XCD
     const int lines_d = n_group_steps * 4, lines = lines_d + (n_group_steps + 1) / 2;
     const int per = (lines + n_share - 1) / n_share;
-    // one unconditional load per thread (a static count keeps the compiler's waits exact);
-    // a slice longer than the workgroup is touched in part only, which costs nothing but speed
+    // one load per thread; a slice longer than the workgroup is touched in part only, which
+    // costs nothing but speed
     const int l = min(me * per + min(tid, per - 1), lines - 1);
     const char* src = l < lines_d ? da + (int64_t)l * 128 : ma + (int64_t)(l - lines_d) * 128;
     warm = *(const int*)src;
   }
-  // chunk 1 last: everything before it is in once at most its two loads are outstanding.
-  // (Unconditional, so that the wait is exact on every path: a one-chunk list loads chunk 0
-  // a second time into the unused slot 1.)
-  issue_chunk(1, tok1);
-  wait_vmcnt<2>();
+  wait_vmcnt<0>();
   asm volatile("" : : "v"(warm));                        // the only use of the plan-touching load: keeps it
   asm volatile("s_barrier" ::: "memory");
 
@@ -293,58 +292,50 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   };
 
   // ---- phases ----
-  // DMA: chunk ph + 2 exists and is issued; NEXT: phase ph + 1 exists.  All vector memory
-  // operations of a phase are unconditional, so the compiler's own waits are exact.
   int doneA = 0, doneB = 0;                             // steps finished so far
-  auto run_phase = [&](int ph, auto dma, auto next) {
-    constexpr bool DMA = decltype(dma)::value, NEXT = decltype(next)::value;
-    int end2A = 0, end2B = 0;                           // (scalar loads, two phases ahead of their use)
+  auto run_phase = [&](int ph, auto has_next) {
+    constexpr bool NEXT = decltype(has_next)::value;
+    // (scalar loads, two phases ahead of their use)
+    const int end2A = peA[min(ph + 2, P - 1)], end2B = peB[min(ph + 2, P - 1)];
+    load_later(dAl, addrA, doneA, lastA);
+    load_later(dBl, addrB, doneB, lastB);
+    if (doneA < endA) run_step(A, dA0, maskA, doneA);
+    if (doneB < endB) run_step(B, dB0, maskB, doneB);
     if constexpr (NEXT) {
-      end2A = peA[min(ph + 2, P - 1)]; end2B = peB[min(ph + 2, P - 1)];
-      load_desc(dAn, addrA, endA, end1A - endA);        // descriptors of the next phase
-      load_desc(dBn, addrB, endB, end1B - endB);
+      // The later descriptors have had two steps to arrive; with nothing else outstanding
+      // when the chunks go out, no later use of a loaded register has to wait for them
+      // (the compiler would otherwise wait for everything, the chunks included).
+      wait_vmcnt<0>();
+      issue_chunk(2 * ph + 2, tokn0); issue_chunk(2 * ph + 3, tokn1);
+      // first descriptors and tokens of the next phase: in place, their users are done
+      dA0 = addrA[(int64_t)min(endA, lastA) * 64];
+      dB0 = addrB[(int64_t)min(endB, lastB) * 64];
+      tokn0 = load_tok(2 * ph + 4); tokn1 = load_tok(2 * ph + 5);
     }
-    int tok = 0;
-    if constexpr (DMA) {
-      tok = tok_next;
-      tok_next = load_tok(min(ph + 3, P - 1));
-    }
-    // (a patch rarely has more than kPrefetched steps in a phase; the descriptors of the
-    // others are loaded on the spot, which also waits for the DMA loads just issued)
 #pragma unroll
-    for (int i = 0; i < kPrefetched; ++i) {
-      if (doneA + i < endA) run_step(A, dA[i], maskA, doneA + i);
-      // The chunk goes out after the wave's first step rather than right behind the barrier,
-      // where all eight waves' loads would queue up in front of the first K reads; it still
-      // is the youngest vector memory operation of the phase.
-      if constexpr (DMA) { if (i == 0) issue_chunk(ph + 2, tok); }
-    }
-    for (int s = doneA + kPrefetched; s < endA; ++s) run_step(A, addrA[(int64_t)s * 64], maskA, s);
+    for (int i = 0; i < kLater; ++i)
+      if (doneA + 1 + i < endA) run_step(A, dAl[i], maskA, doneA + 1 + i);
+    // (a patch rarely has more steps in a phase; their descriptors are loaded on the spot)
+    for (int s = doneA + 1 + kLater; s < endA; ++s) run_step(A, addrA[(int64_t)s * 64], maskA, s);
 #pragma unroll
-    for (int i = 0; i < kPrefetched; ++i)
-      if (doneB + i < endB) run_step(B, dB[i], maskB, doneB + i);
-    for (int s = doneB + kPrefetched; s < endB; ++s) run_step(B, addrB[(int64_t)s * 64], maskB, s);
+    for (int i = 0; i < kLater; ++i)
+      if (doneB + 1 + i < endB) run_step(B, dBl[i], maskB, doneB + 1 + i);
+    for (int s = doneB + 1 + kLater; s < endB; ++s) run_step(B, addrB[(int64_t)s * 64], maskB, s);
     doneA = endA; doneB = endB;
     endA = end1A; endB = end1B; end1A = end2A; end1B = end2B;
-    if constexpr (NEXT) {
-      // everything but the two DMA loads just issued has landed: chunk ph + 1, the next
-      // descriptors and tokens.  All LDS reads of this phase have returned (each step
-      // waits for its own), so the slot of chunk ph - 1 may be overwritten after the barrier.
-      if constexpr (DMA) wait_vmcnt<2>(); else wait_vmcnt<0>();
-      asm volatile("s_barrier" ::: "memory");
-#pragma unroll
-      for (int i = 0; i < kPrefetched; ++i) { dA[i] = dAn[i]; dB[i] = dBn[i]; }
-    }
+    // Chunks 2 ph + 2 and 2 ph + 3, the next descriptors and tokens are in once nothing of
+    // this wave is outstanding.  All LDS reads of the phase have returned (each step waits
+    // for its own), so after the barrier the slots of chunks 2 ph - 1 and 2 ph are free.
+    wait_vmcnt<0>();
+    if constexpr (NEXT) asm volatile("s_barrier" ::: "memory");
   };
   {
     int ph = 0;
-    for (; ph + 2 < P; ++ph) run_phase(ph, std::true_type{}, std::true_type{});
-    if (ph + 1 < P) { run_phase(ph, std::false_type{}, std::true_type{}); ++ph; }
-    run_phase(ph, std::false_type{}, std::false_type{});
+    for (; ph + 1 < P; ++ph) run_phase(ph, std::true_type{});
+    run_phase(ph, std::false_type{});
   }
 
   // ---- epilogue ----
-  wait_vmcnt<0>();        // no LDS-DMA load may outlive the workgroup (one-phase lists get here with one in flight)
   auto store_patch = [&](const PatchState& ps, const PatchWords& w) {
     int n_again = n;                           // recomputed from scratch: the row is not worth a
     asm volatile("" : "+v"(n_again));          // register (or a spill slot) through the loop
@@ -366,13 +357,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 }
 
 litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
-  if (pl->waves_per_group != 16 || pl->chunk_keys != kPairChunk || pl->ring_chunks != 4)
+  if (pl->waves_per_group != 16 || pl->chunk_keys != kPhaseChunks * kDmaKeys || pl->ring_chunks != kRingChunks)
     return fail(LITEVAR_E_PLAN_CORRUPT, "no 16-patch kernel for chunk=%d ring=%d", pl->chunk_keys, pl->ring_chunks);
   const int64_t bh8 = ((int64_t)a.B * a.H + 7) / 8 * 8;
   const int64_t blocks = bh8 * a.n_groups;
   if (blocks > 0x7fffffff) return fail(LITEVAR_E_UNSUPPORTED, "grid too large");
   const float c = a.sm_scale * 1.4426950408889634f;
-  hipLaunchKernelGGL((k_attn_bf16_pair<4>), dim3((unsigned)blocks), dim3(kPairWaves * 64), 0, st, a, c);
+  hipLaunchKernelGGL(k_attn_bf16_pair, dim3((unsigned)blocks), dim3(kPairWaves * 64), 0, st, a, c);
   return hip_check(hipGetLastError(), "bf16 attention launch");
 }
 

@@ -35,6 +35,8 @@ struct Geom {
   int C, NR, A, D;      // chunk keys (a power of two), ring depth in chunks, look-back and
                         // prefetch depth in chunks; NR = A + 1 + D
   int logC;
+  int logS;             // a step spans at most A + 1 consecutive blocks of 2^logS keys (logS <= logC)
+  int R;                // ring slots
   int n_groups, n_patches;
   int s[kMaxScales];
   int off[kMaxScales + 1];
@@ -163,13 +165,13 @@ LV_HD PatchExtent patch_extent(const Geom& g, int k, int gy, int gx, int wave) {
 //   key(step, idx_in_step, upos, token, qmask16)   for every kept key, and
 //   close(step, n_keys, last_upos)                 when a step is complete.
 // qmask16 bit (4*dy + dx) is set iff query (y0+dy, x0+dx) keeps the key.
-// A step is closed when it holds 32 keys or when the next key's chunk lies more
-// than A chunks after the chunk of the step's first key (LDS ring constraint).
+// A step is closed when it holds 32 keys or when the next key's 2^logS-key block lies more
+// than A blocks after the block of the step's first key (LDS ring constraint).
 // Returns the number of steps.
 template <class Sink>
 LV_HD int walk_patch(const Geom& g, const GroupExtent& e, const PatchExtent& p, Sink& sink) {
   if (p.ny == 0) return 0;
-  const int logC = g.logC, A = g.A;
+  const int logS = g.logS, A = g.A;
   int step = 0, cnt = 0, first_chunk = 0, last_upos = 0, ubase = 0;
   for (int j = 0; j <= e.k; ++j) {
     const Box gb = window_box(g, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
@@ -198,7 +200,7 @@ LV_HD int walk_patch(const Geom& g, const GroupExtent& e, const PatchExtent& p, 
         if (!cb) continue;
         const unsigned qmask = (cb * 0x1111u) & rowmask;
         const int upos = urow + x;
-        const int chunk = upos >> logC;
+        const int chunk = upos >> logS;
         if (cnt == kStepKeys || (cnt > 0 && chunk - first_chunk > A)) {
           sink.close(step, cnt, last_upos);
           ++step; cnt = 0;

@@ -18,6 +18,12 @@ static void choose_tiling(Geom& g, int waves, int chunk, int depth, int spare) {
   g.NR = g.A + 1 + g.D + spare;
   g.logC = 0;
   while ((1 << g.logC) < g.C) ++g.logC;
+  g.logS = g.logC; g.R = g.NR * g.C;
+  if (waves == 16) {
+    // phases of 128 keys over a ring of five 64-key chunks: one chunk of look-back, the two
+    // of the phase and the two that are landing; ring and prefetch depth count 64-key chunks
+    g.logS = 6; g.NR = 5; g.R = 320;
+  }
 }
 
 litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* opts, Geom& g) {
@@ -62,14 +68,15 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
     return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4, 8 or 16 (got %d)", waves);
   int chunk = opts ? opts->chunk_keys : 0, depth = opts ? opts->prefetch_chunks : 0;
   int spare = opts ? opts->spare_chunks : -1;
-  if (chunk == 0) chunk = waves == 16 ? 64 : 32;
+  if (chunk == 0) chunk = waves == 16 ? 128 : 32;
   if (depth == 0) depth = 2;
   if (spare < 0) spare = waves == 16 ? 0 : chunk == 32 ? 2 : 1;
-  if (waves == 16 && (chunk != 64 || depth != 2 || spare != 0))
-    return fail(LITEVAR_E_INVALID_ARG, "16 patches per group need (chunk_keys, prefetch_chunks, spare_chunks) = (64, 2, 0)");
+  if (waves == 16 && (chunk != 128 || depth != 2 || spare != 0))
+    return fail(LITEVAR_E_INVALID_ARG, "16 patches per group need (chunk_keys, prefetch_chunks, spare_chunks) = (128, 2, 0)");
   static const int ok[][3] = {{32, 2, 0}, {32, 2, 2}, {32, 3, 2}, {32, 4, 3}, {64, 2, 0}, {64, 2, 1}};
   bool found = false;
   for (const auto& t : ok) found |= (t[0] == chunk && t[1] == depth && t[2] == spare);
+  found |= waves == 16;
   if (!found)
     return fail(LITEVAR_E_INVALID_ARG, "unsupported (chunk_keys, prefetch_chunks, spare_chunks) = (%d, %d, %d)",
                 chunk, depth, spare);
@@ -341,7 +348,7 @@ __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps
   sink.addr = p.step_addr + (int64_t)wd.step_begin * 64;
   sink.mask = p.step_mask + (int64_t)wd.step_begin * 8;
   sink.toks = p.step_tok + (int64_t)wd.step_begin * kStepKeys;
-  sink.phase_cnt = pe; sink.R = g.NR * g.C; sink.logC = g.logC; sink.lane = lane;
+  sink.phase_cnt = pe; sink.R = g.R; sink.logC = g.logC; sink.lane = lane;
   sink.k0 = sink.k1 = sink.v0 = sink.v1 = sink.bits = 0; sink.tok = -1;
   walk_patch(g, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink);
   __syncthreads();
