@@ -49,7 +49,7 @@ def measured_traffic(workload, kernel):
     (FETCH_SIZE and WRITE_SIZE runs, each scaled by a known-size copy kernel); None when
     no summary exists for this kernel instance."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                        f"k_attn_bf16_{workload}_pmc.txt")
+                        f"{kernel.split(chr(60))[0]}_{workload}_pmc.txt")
     if not os.path.exists(path):
         return None
     kv = {}
@@ -159,7 +159,9 @@ def main():
     bytes_layer = BH * (2 * plan.q_len * 64 * esize + 2 * plan.kv_len * 64 * esize)
     achieved = bytes_layer / (kernel_us * 1e-6) / 1e9
 
-    if w.dtype == "bf16":
+    if w.dtype == "bf16" and plan.waves_per_group == 16:
+        kname = "k_attn_bf16_pair"
+    elif w.dtype == "bf16":
         kname = (f"k_attn_bf16<{plan.waves_per_group}, {plan.chunk_keys}, 1, {plan.prefetch_chunks}, "
                  f"{plan.ring_chunks - plan.prefetch_chunks - 2}>")
     else:
