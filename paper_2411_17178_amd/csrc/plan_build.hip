@@ -176,25 +176,104 @@ __global__ void k_window_table(Geom g, int16_t* win) {
   win[2 * idx] = (int16_t)iv.lo; win[2 * idx + 1] = (int16_t)iv.hi;
 }
 
-// K2a: one thread per (group, wave): number of steps and kept pairs; wave 0 also
+// Wave-cooperative form of walk_patch(): the 64 lanes of a wave take 64 consecutive key
+// columns of one key row at a time.  The kept keys of a pass get consecutive places in the
+// patch's key list; a pass is cut where a step fills up (32 keys) or where the next key's
+// 2^logS-key block lies more than A blocks after the block of the step's first key, exactly
+// as in the serial walk, so both produce the same steps.  Sink receives
+//   keys(step, idx, upos, token, qmask, take)   per pass segment: lanes with take set hold
+//                                               the key that becomes entry idx of the step
+//   close(step, n_keys, last_upos)              when a step is complete (wave-uniform)
+template <class Sink>
+__device__ int wave_walk_patch(const Geom& g, const GroupExtent& e, const PatchExtent& p, Sink& sink, int lane) {
+  if (p.ny == 0) return 0;
+  const int logS = g.logS, A = g.A;
+  const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int step = 0, cnt = 0, first_block = 0, last_upos = 0, ubase = 0;
+  for (int j = 0; j <= e.k; ++j) {
+    const Box gb = window_box(g, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+    const int gw = gb.xhi - gb.xlo + 1;
+    const Box pb = window_box(g, e.k, j, p.y0, p.y0 + p.ny - 1, p.x0, p.x0 + p.nx - 1);
+    const int sj = g.s[j], offj = g.off[j];
+    const Interval none = {1, 0};
+    Interval rw[kPatch], cw[kPatch];
+#pragma unroll
+    for (int d = 0; d < kPatch; ++d) {
+      rw[d] = d < p.ny ? win_interval(g, e.k, j, p.y0 + d) : none;
+      cw[d] = d < p.nx ? win_interval(g, e.k, j, p.x0 + d) : none;
+    }
+    for (int y = pb.ylo; y <= pb.yhi; ++y) {
+      unsigned rb = 0;
+#pragma unroll
+      for (int d = 0; d < kPatch; ++d) rb |= (unsigned)(y >= rw[d].lo && y <= rw[d].hi) << d;
+      if (!rb) continue;
+      const unsigned rowmask = ((rb & 1) ? 0x000fu : 0u) | ((rb & 2) ? 0x00f0u : 0u) |
+                               ((rb & 4) ? 0x0f00u : 0u) | ((rb & 8) ? 0xf000u : 0u);
+      const int urow = ubase + (y - gb.ylo) * gw - gb.xlo, trow = offj + y * sj;
+      for (int x0 = pb.xlo; x0 <= pb.xhi; x0 += 64) {
+        const int x = x0 + lane;
+        unsigned cb = 0;
+        if (x <= pb.xhi) {
+#pragma unroll
+          for (int d = 0; d < kPatch; ++d) cb |= (unsigned)(x >= cw[d].lo && x <= cw[d].hi) << d;
+        }
+        const unsigned qmask = (cb * 0x1111u) & rowmask;
+        const int upos = urow + x, blk = upos >> logS;
+        uint64_t km = __ballot(cb != 0);                // kept keys of this pass not yet placed
+        while (km) {
+          const int fl = __builtin_ctzll(km);
+          const int fblk = __shfl(blk, fl);
+          if (cnt > 0 && fblk - first_block > A) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
+          if (cnt == 0) first_block = fblk;
+          const bool mine = (km >> lane) & 1;
+          // lanes whose key still fits the step's span (blocks grow with the lane), ranked
+          const uint64_t fit = __ballot(mine && blk - first_block <= A);
+          const int rank = __builtin_popcountll(fit & lt_mask);
+          const bool take = ((fit >> lane) & 1) && rank < kStepKeys - cnt;
+          const uint64_t tm = __ballot(take);
+          sink.keys(step, cnt + rank, upos, trow + x, qmask, take);
+          last_upos = __shfl(upos, 63 - __builtin_clzll(tm));
+          cnt += __builtin_popcountll(tm);
+          km &= ~tm;
+          if (cnt == kStepKeys) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
+        }
+      }
+    }
+    ubase += (gb.yhi - gb.ylo + 1) * gw;
+  }
+  if (cnt > 0) { sink.close(step, cnt, last_upos); ++step; }
+  return step;
+}
+
+struct WaveCountSink {
+  int pairs = 0;                                         // this lane's share
+  __device__ void keys(int, int, int, int, unsigned qmask, bool take) { if (take) pairs += __builtin_popcount(qmask); }
+  __device__ void close(int, int, int) {}
+};
+
+// K2a: one wave per (group, patch): number of steps and kept pairs; patch 0 also
 // sizes the group's union list
-__global__ void k_count(Geom g, BlobPtrs p) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= g.n_groups * g.NW) return;
+__global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
+  const int idx = blockIdx.x, lane = threadIdx.x;
   const int grp = idx / g.NW, w = idx % g.NW;
   int k, gy, gx;
   group_coords(g, grp, k, gy, gx);
   const GroupExtent e = group_extent(g, k, gy, gx);
   const PatchExtent pe = patch_extent(g, k, gy, gx, w);
-  CountSink sink;
-  const int ns = walk_patch(g, e, pe, sink);
-  WaveDesc wd;
-  wd.step_begin = 0; wd.n_steps = ns;
-  wd.q_base = g.off[k] - g.q0 + pe.y0 * g.s[k] + pe.x0;
-  wd.sk = (int16_t)g.s[k]; wd.ny = (int16_t)pe.ny; wd.nx = (int16_t)pe.nx; wd.kq = (int16_t)k;
-  wd.pairs = (int32_t)sink.pairs; wd.pad[0] = wd.pad[1] = 0;
-  p.waves[idx] = wd;
-  if (w == 0) {
+  WaveCountSink sink;
+  const int ns = wave_walk_patch(g, e, pe, sink, lane);
+  int pairs = sink.pairs;
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) pairs += __shfl_xor(pairs, d);
+  if (lane == 0) {
+    WaveDesc wd;
+    wd.step_begin = 0; wd.n_steps = ns;
+    wd.q_base = g.off[k] - g.q0 + pe.y0 * g.s[k] + pe.x0;
+    wd.sk = (int16_t)g.s[k]; wd.ny = (int16_t)pe.ny; wd.nx = (int16_t)pe.nx; wd.kq = (int16_t)k;
+    wd.pairs = pairs; wd.pad[0] = wd.pad[1] = 0;
+    p.waves[idx] = wd;
+  }
+  if (w == 0 && lane == 0) {
     GroupDesc gd;
     gd.union_base = 0; gd.n_union = group_union_keys(g, e);
     gd.n_phases = (gd.n_union + g.C - 1) / g.C;
@@ -284,16 +363,19 @@ __global__ void k_fill_union(Geom g, BlobPtrs p, Caps caps) {
   for (int i = gd.n_union + threadIdx.x; i < gd.n_phases * g.C; i += blockDim.x) out[i] = last_tok;
 }
 
-// Per-lane view of the step being filled: all 64 lanes of a wave walk the patch in
-// lock-step, each keeping only what it will need in the attention kernel in registers;
-// a finished step is written with coalesced stores.  Lane (n, g4) = (lane % 16, lane / 16):
+// Step under construction: the wave's lanes deposit the keys they place (ring slot, token,
+// query mask) in a 32-entry LDS buffer; when the step closes every lane picks the entries
+// of its role in the attention kernel and the step is written with coalesced stores.
+// Lane (n, g4) = (lane % 16, lane / 16):
 //   K operand  rows of keys n and 16 + n          -> byte offset of its first 16-byte piece
 //   V operand  rows of keys 4*g4 + n/4 (+16)      -> byte offset of its d-tile-0 8-byte read
 //   mask bits  element e = 4*t + i  <->  key 16*t + 4*g4 + i against query n
+struct StepBuf { uint32_t slot[kStepKeys]; int32_t tok[kStepKeys]; uint32_t qmask[kStepKeys]; };
+
 struct FillSink {
   uint2* addr; uint64_t* mask; int32_t* toks; int32_t* phase_cnt;
+  StepBuf* buf;
   int R, logC, lane;
-  uint32_t k0, k1, v0, v1, bits; int32_t tok;
   __device__ static uint32_t k_off(uint32_t slot, int g4) {
     return slot * kRingRowBytes + (((2u * g4) ^ ring_swizzle(slot)) << 4);
   }
@@ -301,38 +383,36 @@ struct FillSink {
     const uint32_t sw = ring_swizzle(slot), b = (n >> 1) & 1, half = n & 1;
     return slot * kRingRowBytes + 8u * half + 16u * ((b ^ sw) & 1u) + ((sw >> 1) << 5);
   }
-  __device__ void place(int idx, uint32_t slot) {
+  __device__ void keys(int, int idx, int upos, int t, unsigned qmask, bool take) {
+    if (take) { buf->slot[idx] = (uint32_t)(upos % R); buf->tok[idx] = t; buf->qmask[idx] = qmask; }
+  }
+  __device__ void close(int step, int n_keys, int last_upos) {
+    __syncthreads();                                   // (one wave per block) deposits are visible
     const int n = lane & 15, g4 = lane >> 4;
-    if (idx == n) k0 = k_off(slot, g4);
-    if (idx == 16 + n) k1 = k_off(slot, g4);
-    if (idx == 4 * g4 + (n >> 2)) v0 = v_off(slot, n);
-    if (idx == 16 + 4 * g4 + (n >> 2)) v1 = v_off(slot, n);
-  }
-  __device__ void key(int, int idx, int upos, int t, unsigned qmask) {
-    if (idx == 0) { bits = 0; tok = -1; }
-    if (lane == idx) tok = t;
-    place(idx, (uint32_t)(upos % R));
-    const int r = idx & 15;
-    if ((r >> 2) == (lane >> 4) && (qmask >> (lane & 15) & 1)) bits |= 1u << (4 * (idx >> 4) + (r & 3));
-  }
-  __device__ void close(int step, int n, int last_upos) {
-    for (int idx = n; idx < kStepKeys; ++idx) place(idx, (uint32_t)(last_upos % R));  // padding keys
+    const uint32_t pad = (uint32_t)(last_upos % R);    // padding keys read the step's last row
+    auto slot_of = [&](int idx) { return idx < n_keys ? buf->slot[idx] : pad; };
+    const uint32_t k0 = k_off(slot_of(n), g4), k1 = k_off(slot_of(16 + n), g4);
+    const uint32_t v0 = v_off(slot_of(4 * g4 + (n >> 2)), n), v1 = v_off(slot_of(16 + 4 * g4 + (n >> 2)), n);
     addr[(int64_t)step * 64 + lane] = make_uint2(k0 | (k1 << 16), v0 | (v1 << 16));
     uint64_t mine = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const uint64_t bal = __ballot((bits >> e) & 1u);
+      const int idx = 16 * (e >> 2) + 4 * g4 + (e & 3);
+      const bool bit = idx < n_keys && ((buf->qmask[idx] >> n) & 1u);
+      const uint64_t bal = __ballot(bit);
       if (lane == e) mine = bal;
     }
     if (lane < 8) mask[(int64_t)step * 8 + lane] = mine;
-    if (lane < kStepKeys) toks[(int64_t)step * kStepKeys + lane] = tok;
+    if (lane < kStepKeys) toks[(int64_t)step * kStepKeys + lane] = lane < n_keys ? buf->tok[lane] : -1;
     if (lane == 0) phase_cnt[last_upos >> logC] += 1;
+    __syncthreads();                                   // the buffer may be refilled
   }
 };
 
-// K2d: one wave per (group, wave): steps (ring addresses, lane masks, tokens) and the
+// K2d: one wave per (group, patch): steps (ring addresses, lane masks, tokens) and the
 // cumulative number of steps that are runnable after each phase
 __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps) {
+  __shared__ StepBuf buf;
   const int idx = blockIdx.x, lane = threadIdx.x;
   if (p.hdr->error) return;
   const int grp = idx / g.NW, w = idx % g.NW;
@@ -348,9 +428,8 @@ __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps
   sink.addr = p.step_addr + (int64_t)wd.step_begin * 64;
   sink.mask = p.step_mask + (int64_t)wd.step_begin * 8;
   sink.toks = p.step_tok + (int64_t)wd.step_begin * kStepKeys;
-  sink.phase_cnt = pe; sink.R = g.R; sink.logC = g.logC; sink.lane = lane;
-  sink.k0 = sink.k1 = sink.v0 = sink.v1 = sink.bits = 0; sink.tok = -1;
-  walk_patch(g, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink);
+  sink.phase_cnt = pe; sink.buf = &buf; sink.R = g.R; sink.logC = g.logC; sink.lane = lane;
+  wave_walk_patch(g, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink, lane);
   __syncthreads();
   if (lane == 0) {
     int acc = 0;
@@ -364,7 +443,7 @@ litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipSt
   const int nwin = g.K * g.K * g.smax;
   hipLaunchKernelGGL(k_window_table, dim3((nwin + 255) / 256), dim3(256), 0, st, g, p.win);
   const int nw = g.n_groups * g.NW;
-  hipLaunchKernelGGL(k_count, dim3((nw + 63) / 64), dim3(64), 0, st, g, p);
+  hipLaunchKernelGGL(k_count, dim3(nw), dim3(64), 0, st, g, p);
   hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, st, g, p, caps);
   hipLaunchKernelGGL(k_fill_union, dim3(g.n_groups), dim3(256), 0, st, g, p, caps);
   hipLaunchKernelGGL(k_fill_steps, dim3(nw), dim3(64), 0, st, g, p, caps);
