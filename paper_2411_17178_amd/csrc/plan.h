@@ -98,7 +98,9 @@ LV_HD Interval win_interval(const Geom& g, int k, int j, int c) {
   const int sj = g.s[j];
   Interval iv;
   if (j < g.n_sink || g.rad[j] < 0) { iv.lo = 0; iv.hi = sj - 1; return iv; }
-  const int ctr = (int)(((2 * (int64_t)c + 1) * sj) / (2 * (int64_t)g.s[k]));
+  // (sides are at most kMaxSide = 1024, so the product fits 32 bits: a 64-bit division would
+  // cost an order of magnitude more on the device)
+  const int ctr = (int)((unsigned)((2 * c + 1) * sj) / (unsigned)(2 * g.s[k]));
   iv.lo = ctr - g.rad[j] < 0 ? 0 : ctr - g.rad[j];
   iv.hi = ctr + g.rad[j] > sj - 1 ? sj - 1 : ctr + g.rad[j];
   return iv;

@@ -176,8 +176,9 @@ __global__ void k_window_table(Geom g, int16_t* win) {
   win[2 * idx] = (int16_t)iv.lo; win[2 * idx + 1] = (int16_t)iv.hi;
 }
 
-// Wave-cooperative form of walk_patch(): the 64 lanes of a wave take 64 consecutive key
-// columns of one key row at a time.  The kept keys of a pass get consecutive places in the
+// Wave-cooperative form of walk_patch(): the 64 lanes of a wave take 64 consecutive keys of
+// the patch's box in a key scale at a time (several rows of a narrow box, or 64 columns of
+// one row).  The kept keys of a pass get consecutive places in the
 // patch's key list; a pass is cut where a step fills up (32 keys) or where the next key's
 // 2^logS-key block lies more than A blocks after the block of the step's first key, exactly
 // as in the serial walk, so both produce the same steps.  Sink receives
@@ -191,29 +192,48 @@ __device__ int wave_walk_patch(const Geom& g, const GroupExtent& e, const PatchE
   const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
   int step = 0, cnt = 0, first_block = 0, last_upos = 0, ubase = 0;
   for (int j = 0; j <= e.k; ++j) {
-    const Box gb = window_box(g, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
-    const int gw = gb.xhi - gb.xlo + 1;
-    const Box pb = window_box(g, e.k, j, p.y0, p.y0 + p.ny - 1, p.x0, p.x0 + p.nx - 1);
-    const int sj = g.s[j], offj = g.off[j];
+    // The twelve window intervals of this key scale (four patch rows, four patch columns, the
+    // group's first and last row and column) are computed by twelve lanes at once -- each
+    // costs an integer division -- and handed round with v_readlane.
+    const int sk = g.s[e.k];
+    int cq = lane < 4 ? p.y0 + lane : lane < 8 ? p.x0 + lane - 4 : lane == 8 ? e.qy0 : lane == 9 ? e.qy1 : lane == 10 ? e.qx0 : e.qx1;
+    cq = cq < sk ? cq : sk - 1;
+    const Interval mine_iv = win_interval(g, e.k, j, cq);
     const Interval none = {1, 0};
     Interval rw[kPatch], cw[kPatch];
 #pragma unroll
     for (int d = 0; d < kPatch; ++d) {
-      rw[d] = d < p.ny ? win_interval(g, e.k, j, p.y0 + d) : none;
-      cw[d] = d < p.nx ? win_interval(g, e.k, j, p.x0 + d) : none;
+      const Interval r = {__shfl(mine_iv.lo, d), __shfl(mine_iv.hi, d)};
+      const Interval cc = {__shfl(mine_iv.lo, 4 + d), __shfl(mine_iv.hi, 4 + d)};
+      rw[d] = d < p.ny ? r : none;
+      cw[d] = d < p.nx ? cc : none;
     }
-    for (int y = pb.ylo; y <= pb.yhi; ++y) {
+    Box gb, pb;
+    gb.ylo = __shfl(mine_iv.lo, 8); gb.yhi = __shfl(mine_iv.hi, 9);
+    gb.xlo = __shfl(mine_iv.lo, 10); gb.xhi = __shfl(mine_iv.hi, 11);
+    pb.ylo = rw[0].lo; pb.yhi = __shfl(mine_iv.hi, p.ny - 1);
+    pb.xlo = cw[0].lo; pb.xhi = __shfl(mine_iv.hi, 4 + p.nx - 1);
+    const int gw = gb.xhi - gb.xlo + 1;
+    const int sj = g.s[j], offj = g.off[j];
+    // lanes of a pass in key order: RP rows of the patch's box (W columns each) when the box
+    // is narrower than a wave, else 64 columns of one row
+    const int W = pb.xhi - pb.xlo + 1;
+    const int WL = W < 64 ? W : 64, RP = 64 / WL;
+    const int ry = lane / WL, xx = lane - ry * WL;
+    for (int y0 = pb.ylo; y0 <= pb.yhi; y0 += RP) {
+      const int y = y0 + ry;
       unsigned rb = 0;
+      if (ry < RP && y <= pb.yhi) {
 #pragma unroll
-      for (int d = 0; d < kPatch; ++d) rb |= (unsigned)(y >= rw[d].lo && y <= rw[d].hi) << d;
-      if (!rb) continue;
+        for (int d = 0; d < kPatch; ++d) rb |= (unsigned)(y >= rw[d].lo && y <= rw[d].hi) << d;
+      }
       const unsigned rowmask = ((rb & 1) ? 0x000fu : 0u) | ((rb & 2) ? 0x00f0u : 0u) |
                                ((rb & 4) ? 0x0f00u : 0u) | ((rb & 8) ? 0xf000u : 0u);
       const int urow = ubase + (y - gb.ylo) * gw - gb.xlo, trow = offj + y * sj;
-      for (int x0 = pb.xlo; x0 <= pb.xhi; x0 += 64) {
-        const int x = x0 + lane;
+      for (int x0 = pb.xlo; x0 <= pb.xhi; x0 += WL) {
+        const int x = x0 + xx;
         unsigned cb = 0;
-        if (x <= pb.xhi) {
+        if (rb && x <= pb.xhi) {
 #pragma unroll
           for (int d = 0; d < kPatch; ++d) cb |= (unsigned)(x >= cw[d].lo && x <= cw[d].hi) << d;
         }
@@ -294,34 +314,31 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
   }
 }
 
-// K2b: exclusive scans over groups (union keys, phase entries) and waves (steps) by one
-// 1024-thread block: per-thread partial sums over a contiguous slice, a serial scan of the
-// 1024 partials, then the slice is revisited
+// K2b: exclusive scans over groups (union keys, phase entries) and patches (steps) by one
+// 1024-thread block: per-thread partial sums over a contiguous slice of groups, a block-wide
+// scan of the partials (Hillis-Steele in LDS), then the slice is revisited
 __global__ __launch_bounds__(1024) void k_scan(Geom g, BlobPtrs p, Caps caps) {
-  __shared__ int64_t part[3][1024];
+  __shared__ int64_t part[2][4][1024];
   const int t = threadIdx.x;
   const int per = (g.n_groups + 1023) / 1024;
   const int g0 = t * per < g.n_groups ? t * per : g.n_groups;
   const int g1 = g0 + per < g.n_groups ? g0 + per : g.n_groups;
-  int64_t steps = 0, uni = 0, phe = 0, pairs = 0;
+  int64_t v[4] = {0, 0, 0, 0};                          // steps, union keys, phase entries, pairs
   for (int grp = g0; grp < g1; ++grp) {
-    uni += (int64_t)p.groups[grp].n_phases * g.C; phe += (int64_t)p.groups[grp].n_phases * g.NW;
-    for (int w = 0; w < g.NW; ++w) { steps += p.waves[grp * g.NW + w].n_steps; pairs += p.waves[grp * g.NW + w].pairs; }
+    v[1] += (int64_t)p.groups[grp].n_phases * g.C; v[2] += (int64_t)p.groups[grp].n_phases * g.NW;
+    for (int w = 0; w < g.NW; ++w) { v[0] += p.waves[grp * g.NW + w].n_steps; v[3] += p.waves[grp * g.NW + w].pairs; }
   }
-  part[0][t] = steps; part[1][t] = uni; part[2][t] = phe;
-  // total of the kept pairs: a plain tree reduction through LDS
-  __shared__ int64_t psum[1024];
-  __shared__ int64_t tot[3];
-  psum[t] = pairs;
+  int cur = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) part[0][i][t] = v[i];
   __syncthreads();
-  for (int d = 512; d > 0; d >>= 1) { if (t < d) psum[t] += psum[t + d]; __syncthreads(); }
-  if (t < 3) {
-    int64_t acc = 0;
-    for (int i = 0; i < 1024; ++i) { const int64_t v = part[t][i]; part[t][i] = acc; acc += v; }
-    tot[t] = acc;                              // total steps, union keys, phase entries
+  for (int d = 1; d < 1024; d <<= 1) {                  // inclusive scan
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[cur ^ 1][i][t] = part[cur][i][t] + (t >= d ? part[cur][i][t - d] : 0);
+    cur ^= 1;
+    __syncthreads();
   }
-  __syncthreads();
-  steps = part[0][t]; uni = part[1][t]; phe = part[2][t];
+  int64_t steps = part[cur][0][t] - v[0], uni = part[cur][1][t] - v[1], phe = part[cur][2][t] - v[2];
   for (int grp = g0; grp < g1; ++grp) {
     GroupDesc& gd = p.groups[grp];
     gd.union_base = (int32_t)uni; gd.phase_base = (int32_t)phe;
@@ -331,12 +348,13 @@ __global__ __launch_bounds__(1024) void k_scan(Geom g, BlobPtrs p, Caps caps) {
       wd.step_begin = (int32_t)steps; steps += wd.n_steps;
     }
   }
-  if (t == 0) {
+  if (t == 1023) {
     Header h;
     memset(&h, 0, sizeof h);
     h.magic = kMagic; h.blob_bytes = caps.bytes;
     h.n_groups = g.n_groups; h.n_waves = g.n_groups * g.NW;
-    h.n_steps = tot[0]; h.n_union = tot[1]; h.n_phase_entries = tot[2]; h.retained_pairs = psum[0];
+    h.n_steps = part[cur][0][t]; h.n_union = part[cur][1][t]; h.n_phase_entries = part[cur][2][t];
+    h.retained_pairs = part[cur][3][t];
     h.error = (h.n_steps != caps.n_steps || h.n_union != caps.n_union ||
                h.n_phase_entries != caps.n_phase_entries || h.retained_pairs != caps.retained_pairs) ? 1 : 0;
     *p.hdr = h;
