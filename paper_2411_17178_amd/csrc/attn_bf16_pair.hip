@@ -44,6 +44,8 @@ constexpr int kPairWaves = 8;         // waves per workgroup
 constexpr int kDmaKeys = 64;          // keys per chunk (the unit of loading and of ring slot reuse)
 constexpr int kPhaseChunks = 2;       // chunks per phase
 constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two landing
+constexpr int kBufferFlags = 0x00020000;   // word 3 of a raw buffer resource on gfx9: 32-bit data format
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 constexpr int kLater = 2;             // descriptors per patch, beyond the first step of a phase, that are
                                       // fetched at the start of the phase
 
@@ -121,17 +123,25 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const unsigned row_bytes = (unsigned)a.ks[2] * 2u;   // a (batch, head) slab spans < 2 GiB (checked by the API)
   const int32_t* utok = a.union_tok + gd.union_base;
   const int ident = __builtin_amdgcn_readfirstlane(gd.ident);   // union entries [0, ident) are token i at position i
-  const int row = 8 * wave + (lane >> 3), pos = lane & 7;
+  const int row = 8 * wave + (lane >> 3);
+  // A lane's row of chunk t goes to slot (t % 5) * 64 + row.  Chunks start at multiples of 64
+  // slots, so the slot's swizzle -- and with it the 16-byte piece of the source row that
+  // this lane fetches -- does not depend on t.
+  const unsigned piece_off = (((unsigned)lane & 7u) ^ ring_swizzle((unsigned)row)) << 4;
+  static_assert((kDmaKeys & 63) == 0, "the swizzle folds slot bits 0..5 only");
   auto issue_chunk = [&](int t, int tok) {             // chunk t -> ring slots (t % 5) * 64 ...
     const int slot0 = (t % kRingChunks) * C + 8 * wave;
-    const unsigned slot = (unsigned)(slot0 + (lane >> 3));
-    const unsigned src = (unsigned)tok * row_bytes + (((unsigned)pos ^ ring_swizzle(slot)) << 4);
+    const unsigned src = (unsigned)tok * row_bytes + piece_off;
     __builtin_amdgcn_global_load_lds((global_void*)(Kp + src), (lds_void*)(Kring + slot0 * kRingRowBytes), 16, 0, 0);
     __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
   };
+  // (tokens and descriptors through buffer loads: a scalar resource and a scalar offset plus a
+  // lane offset register, where a flat address costs 64-bit vector arithmetic per load)
+  const __amdgpu_buffer_rsrc_t tok_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)utok, 0, NC * C * 4, kBufferFlags);
   auto load_tok = [&](int t) -> int {                  // this lane's row of chunk t (clamped to the last chunk)
-    const int i = min(t, NC - 1) * C + row;
-    const int v = utok[i];
+    const int tc = min(t, NC - 1);
+    const int v = (int)__builtin_amdgcn_raw_buffer_load_b32(tok_rsrc, row * 4, tc * C * 4, 0);
+    const int i = tc * C + row;
     return i < ident ? i : v;
   };
 
@@ -168,8 +178,14 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   }
 
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
-  const uint2* addrA = a.step_addr + sbA * 64 + lane;
-  const uint2* addrB = a.step_addr + sbB * 64 + lane;
+  const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
+  const __amdgpu_buffer_rsrc_t descA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.step_addr + sbA * 64), 0, (lastA + 1) * 512, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t descB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.step_addr + sbB * 64), 0, (lastB + 1) * 512, kBufferFlags);
+  const int lane8 = lane * 8;
+  auto load_desc = [&](const __amdgpu_buffer_rsrc_t& rsrc, int s) -> uint2 {
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane8, s * 512, 0);
+    return make_uint2(v.x, v.y);
+  };
   const uint64_t* maskA = a.step_mask + sbA * 8;
   const uint64_t* maskB = a.step_mask + sbB * 8;
 
@@ -210,13 +226,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // (all loads of a phase are unconditional, from clamped indices, so that their number is
   // static and the compiler's waits stay exact: a conditional load would make it wait for
   // everything, the chunks in flight included, before each later use of a loaded register)
-  const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
-  auto load_later = [&](uint2 (&d)[kLater], const uint2* addrs, int first, int last) {
+  auto load_later = [&](uint2 (&d)[kLater], const __amdgpu_buffer_rsrc_t& rsrc, int first, int last) {
 #pragma unroll
-    for (int i = 0; i < kLater; ++i) d[i] = addrs[(int64_t)min(first + 1 + i, last) * 64];
+    for (int i = 0; i < kLater; ++i) d[i] = load_desc(rsrc, min(first + 1 + i, last));
   };
-  dA0 = addrA[0];
-  dB0 = addrB[0];
+  dA0 = load_desc(descA, 0);
+  dB0 = load_desc(descB, 0);
   int tokn0 = load_tok(2), tokn1 = load_tok(3);         // tokens of the chunks issued in phase 0
   // All workgroups walk the same plan in lock-step, so each phase's first access to its part
   // of the plan would be an HBM miss on every workgroup's critical path.  The workgroups of
@@ -297,8 +312,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     constexpr bool NEXT = decltype(has_next)::value;
     // (scalar loads, two phases ahead of their use)
     const int end2A = peA[min(ph + 2, P - 1)], end2B = peB[min(ph + 2, P - 1)];
-    load_later(dAl, addrA, doneA, lastA);
-    load_later(dBl, addrB, doneB, lastB);
+    load_later(dAl, descA, doneA, lastA);
+    load_later(dBl, descB, doneB, lastB);
     if (doneA < endA) run_step(A, dA0, maskA, doneA);
     if (doneB < endB) run_step(B, dB0, maskB, doneB);
     if constexpr (NEXT) {
@@ -308,19 +323,19 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       wait_vmcnt<0>();
       issue_chunk(2 * ph + 2, tokn0); issue_chunk(2 * ph + 3, tokn1);
       // first descriptors and tokens of the next phase: in place, their users are done
-      dA0 = addrA[(int64_t)min(endA, lastA) * 64];
-      dB0 = addrB[(int64_t)min(endB, lastB) * 64];
+      dA0 = load_desc(descA, min(endA, lastA));
+      dB0 = load_desc(descB, min(endB, lastB));
       tokn0 = load_tok(2 * ph + 4); tokn1 = load_tok(2 * ph + 5);
     }
 #pragma unroll
     for (int i = 0; i < kLater; ++i)
       if (doneA + 1 + i < endA) run_step(A, dAl[i], maskA, doneA + 1 + i);
     // (a patch rarely has more steps in a phase; their descriptors are loaded on the spot)
-    for (int s = doneA + 1 + kLater; s < endA; ++s) run_step(A, addrA[(int64_t)s * 64], maskA, s);
+    for (int s = doneA + 1 + kLater; s < endA; ++s) run_step(A, load_desc(descA, s), maskA, s);
 #pragma unroll
     for (int i = 0; i < kLater; ++i)
       if (doneB + 1 + i < endB) run_step(B, dBl[i], maskB, doneB + 1 + i);
-    for (int s = doneB + 1 + kLater; s < endB; ++s) run_step(B, addrB[(int64_t)s * 64], maskB, s);
+    for (int s = doneB + 1 + kLater; s < endB; ++s) run_step(B, load_desc(descB, s), maskB, s);
     doneA = endA; doneB = endB;
     endA = end1A; endB = end1B; end1A = end2A; end1B = end2B;
     // Chunks 2 ph + 2 and 2 ph + 3, the next descriptors and tokens are in once nothing of
