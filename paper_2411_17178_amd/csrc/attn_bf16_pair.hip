@@ -216,6 +216,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   bf16x8 ones;
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+  asm volatile("" : "+v"(ones));     // kept in four registers (the compiler would rebuild it in every step)
   const float slack = kSlack / c;
 
   // Step descriptors of a patch for one phase: the first step's is fetched during the phase
@@ -286,8 +287,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       for (int dt = 0; dt < 4; ++dt) ps.O[dt] *= alpha;
     }
     const float negmc = ps.negmc;
-    // V^T operands: issued here rather than before the softmax, where sixteen more live
-    // registers would not fit
+    // V^T operands: issued here, consumed after the exponentials
     uint2 va[4][2];
     lds_read_v<VOFF>(lds_addr(Kring + (cur.y & 0xffffu)), lds_addr(Kring + (cur.y >> 16)), va);
     float p[8];
