@@ -106,9 +106,9 @@ typedef struct litevar_plan_opts {
   int32_t chunk_keys;       /* keys per phase of the key stream: 0 = choose; else 32, 64 or 128 */
   int32_t prefetch_chunks;  /* chunks kept in flight: 0 = choose */
   int32_t spare_chunks;     /* extra ring chunks that let waves drift apart: -1 = choose.
-                               Supported (chunk, prefetch, spare): (32,2,0) (32,2,2) (32,3,2) (32,4,3)
-                               (64,2,0) (64,2,1); 16 patches per group take (128,2,0) only: phases
-                               of 128 keys, ring and prefetch depth counted in 64-key chunks */
+                               Supported (chunk, prefetch, spare) for 4 and 8 patches per group:
+                               (32,2,2) and (64,2,1).  16 patches per group take (128,2,0) only:
+                               phases of 128 keys, ring and prefetch depth counted in 64-key chunks */
   int32_t reserved[4];
 } litevar_plan_opts;
 

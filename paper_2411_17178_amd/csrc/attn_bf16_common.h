@@ -19,8 +19,6 @@ typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
 
 constexpr float kFloor = -1.0e30f;   // initial softmax reference: keeps exp2 arguments finite
 constexpr float kSlack = 6.0f;       // base-2 exponent by which a score may exceed the reference
-constexpr int kTokBatchChunks = 8;   // chunks covered by one token batch
-constexpr int kAhead = 4;            // step descriptors fetched ahead by a compute wave
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 

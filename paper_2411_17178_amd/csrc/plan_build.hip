@@ -73,7 +73,7 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
   if (spare < 0) spare = waves == 16 ? 0 : chunk == 32 ? 2 : 1;
   if (waves == 16 && (chunk != 128 || depth != 2 || spare != 0))
     return fail(LITEVAR_E_INVALID_ARG, "16 patches per group need (chunk_keys, prefetch_chunks, spare_chunks) = (128, 2, 0)");
-  static const int ok[][3] = {{32, 2, 0}, {32, 2, 2}, {32, 3, 2}, {32, 4, 3}, {64, 2, 0}, {64, 2, 1}};
+  static const int ok[][3] = {{32, 2, 2}, {64, 2, 1}};
   bool found = false;
   for (const auto& t : ok) found |= (t[0] == chunk && t[1] == depth && t[2] == spare);
   found |= waves == 16;

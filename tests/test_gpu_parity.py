@@ -131,6 +131,9 @@ MASK_CASES = [
     ((1, 2, 3, 4, 6, 9, 13, 18, 24, 32), -1, 0, (8, 10)),   # dense block-causal
     ((5, 21, 33), 2, 0, None),
     ((2, 40), 7, 0, (1, 2)),
+    ((1, 3, 70), 40, 0, (2, 3)),                 # window boxes wider than a wave (84 columns, clipped to 70)
+    ((1, 3, 70), -1, 0, (2, 3)),                 # dense rows of 70 keys
+    ((2, 100), [-1, 45], 0, (1, 2)),             # 94-column boxes inside a 100-column scale
 ]
 
 
@@ -186,7 +189,7 @@ def test_var_d16(lv, waves):
     assert torch.equal(o[:, :, 0].cpu(), v[:, :, 0])
 
 
-@pytest.mark.parametrize("waves", [0, 4, 8, 16])
+@pytest.mark.parametrize("waves", [0, 4, 8, 16, (4, 64, 2, 1), (8, 64, 2, 1)])
 def test_var_d30_kv_step(lv, waves):
     w = workloads.get("var_d30_kvstep")
     q, k, v = workloads.make_workload_qkv(w)
@@ -265,6 +268,7 @@ ATTN_CASES = [
     ((1, 2, 3, 4, 6, 9, 13, 18, 24, 32), 0, 0, None, 1, 2),
     ((2, 40), 7, 0, (1, 2), 2, 1),
     ((5, 21, 33), 2, 0, None, 1, 3),
+    ((1, 3, 70), 40, 0, (2, 3), 1, 1),           # window boxes wider than a wave
 ]
 
 
