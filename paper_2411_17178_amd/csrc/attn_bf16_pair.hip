@@ -36,6 +36,32 @@
 
 #include "attn_bf16_common.h"
 
+// Per-wave timing records for profiling builds (-DLITEVAR_TIMELINE): 16 x uint64 per wave.
+//   [0] start  [1] first chunks issued  [2] prologue loads issued  [3] prologue loads landed
+//   [4] first barrier passed  [5] phases done  [6] stored          (100 MHz wall clock)
+//   [8] cycles in steps  [9] in issuing chunks and loads  [10] in barriers  [11] in the phase
+//   loop  [12] hardware id (HW_ID | XCC_ID << 32)  [13] waiting for memory at phase ends
+//   (shader clock).  Empty in normal builds.
+#ifdef LITEVAR_TIMELINE
+#define LV_TL_DECL unsigned long long tl_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
+#define LV_TL_WALL(i) tl_[i] = wall_clock64()
+#define LV_TL_BEGIN(v) const long long v = clock64()
+#define LV_TL_ADD(i, v) tl_[i] += clock64() - (v)
+#define LV_TL_FLUSH(args, wave_index, lane)                                                       \
+  do {                                                                                            \
+    tl_[12] = (unsigned long long)__builtin_amdgcn_s_getreg(4 | (31 << 11)) |                      \
+              ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32);              \
+    if ((args).timeline && (lane) == 0)                                                            \
+      for (int i_ = 0; i_ < 16; ++i_) (args).timeline[(size_t)(wave_index) * 16 + i_] = tl_[i_];   \
+  } while (0)
+#else
+#define LV_TL_DECL
+#define LV_TL_WALL(i)
+#define LV_TL_BEGIN(v)
+#define LV_TL_ADD(i, v)
+#define LV_TL_FLUSH(args, wave_index, lane)
+#endif
+
 namespace lv {
 
 namespace {
@@ -46,6 +72,7 @@ constexpr int kPhaseChunks = 2;       // chunks per phase
 constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two landing
 constexpr int kBufferFlags = 0x00020000;   // word 3 of a raw buffer resource on gfx9: 32-bit data format
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 constexpr int kLater = 2;             // descriptors per patch, beyond the first step of a phase, that are
                                       // fetched at the start of the phase
 
@@ -53,27 +80,31 @@ __device__ inline unsigned lds_addr(const void* p) {
   return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 
-// four 16-byte K pieces (two keys x two halves of the head dimension); waits for them
-__device__ inline void lds_read_k(unsigned a0, unsigned a1, uint4& k00, uint4& k01, uint4& k10, uint4& k11) {
+// four 16-byte K pieces (two keys x two halves of the head dimension): issued only,
+// lds_wait_k() must precede the first use
+__device__ inline void lds_read_k_issue(unsigned a0, unsigned a1, u32x4& k00, u32x4& k01, u32x4& k10, u32x4& k11) {
   asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\t"
-               "ds_read_b128 %2, %6\n\tds_read_b128 %3, %7\n\t"
-               "s_waitcnt lgkmcnt(0)"
+               "ds_read_b128 %2, %6\n\tds_read_b128 %3, %7"
                : "=&v"(k00), "=&v"(k01), "=&v"(k10), "=&v"(k11)
                : "v"(a0), "v"(a0 ^ 16u), "v"(a1), "v"(a1 ^ 16u) : "memory");
+}
+
+__device__ inline void lds_wait_k(u32x4& k00, u32x4& k01, u32x4& k10, u32x4& k11) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(k00), "+v"(k01), "+v"(k10), "+v"(k11) : : "memory");
 }
 
 // transposing reads of the V^T operands of one step (4 head-dim tiles x 2 key halves);
 // issued only: lds_wait() must precede the first use
 template <int VOFF>
-__device__ inline void lds_read_v(unsigned v0, unsigned v1, uint2 (&va)[4][2]) {
+__device__ inline void lds_read_v(unsigned v0, unsigned v1, const unsigned (&x)[3][2], uint2 (&va)[4][2]) {
   asm volatile("ds_read_b64_tr_b16 %0, %8 offset:%16\n\tds_read_b64_tr_b16 %1, %9 offset:%16\n\t"
                "ds_read_b64_tr_b16 %2, %10 offset:%16\n\tds_read_b64_tr_b16 %3, %11 offset:%16\n\t"
                "ds_read_b64_tr_b16 %4, %12 offset:%16\n\tds_read_b64_tr_b16 %5, %13 offset:%16\n\t"
                "ds_read_b64_tr_b16 %6, %14 offset:%16\n\tds_read_b64_tr_b16 %7, %15 offset:%16"
                : "=&v"(va[0][0]), "=&v"(va[0][1]), "=&v"(va[1][0]), "=&v"(va[1][1]),
                  "=&v"(va[2][0]), "=&v"(va[2][1]), "=&v"(va[3][0]), "=&v"(va[3][1])
-               : "v"(v0), "v"(v1), "v"(v0 ^ 32u), "v"(v1 ^ 32u), "v"(v0 ^ 64u), "v"(v1 ^ 64u),
-                 "v"(v0 ^ 96u), "v"(v1 ^ 96u), "i"(VOFF) : "memory");
+               : "v"(v0), "v"(v1), "v"(x[0][0]), "v"(x[0][1]), "v"(x[1][0]), "v"(x[1][1]),
+                 "v"(x[2][0]), "v"(x[2][1]), "i"(VOFF) : "memory");
 }
 
 // waits for the reads issued by lds_read_v; the operands are tied so that no use is
@@ -110,6 +141,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
   if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
 
+  LV_TL_DECL;
+  LV_TL_WALL(0);
+#ifdef LITEVAR_TIMELINE
+  // experiment: delay the first (tune[0] = 1) or the later (2) workgroups of a CU by tune[1] x 64 cycles
+  if ((a.tune[0] == 1 && seq < a.tune[2]) || (a.tune[0] == 2 && seq >= a.tune[2]))
+    for (int i = 0; i < a.tune[1]; ++i) __builtin_amdgcn_s_sleep(1);
+#endif
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -177,6 +215,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     issue_chunk(1, t1);
   }
 
+  LV_TL_WALL(1);
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
   const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
   const __amdgpu_buffer_rsrc_t descA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.step_addr + sbA * 64), 0, (lastA + 1) * 512, kBufferFlags);
@@ -251,21 +290,43 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     const char* src = l < lines_d ? da + (int64_t)l * 128 : ma + (int64_t)(l - lines_d) * 128;
     warm = *(const int*)src;
   }
+  LV_TL_WALL(2);
   wait_vmcnt<0>();
+  LV_TL_WALL(3);
   asm volatile("" : : "v"(warm));                        // the only use of the plan-touching load: keeps it
   asm volatile("s_barrier" ::: "memory");
+  LV_TL_WALL(4);
 
   // One step: 32 keys against the 16 queries of patch ps.
   auto run_step = [&](PatchState& ps, const uint2 cur, const uint64_t* masks, int s) {
-    const const_u64_ptr mk = (const_u64_ptr)(masks + (int64_t)s * 8);
-    uint4 k00, k01, k10, k11;
-    lds_read_k(lds_addr(Kring + (cur.x & 0xffffu)), lds_addr(Kring + (cur.x >> 16)), k00, k01, k10, k11);
+    // lane masks of the step (a scalar load): requested ahead of the K pieces so that the
+    // two latencies overlap
+    const const_u64_ptr mkp = (const_u64_ptr)((const char*)masks + (unsigned)s * 64u);
+    uint64_t mk[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mk[e] = mkp[e];
+    u32x4 k00, k01, k10, k11;
+    lds_read_k_issue(lds_addr(Kring + (cur.x & 0xffffu)), lds_addr(Kring + (cur.x >> 16)), k00, k01, k10, k11);
+    // addresses of the V^T pieces: computed while the K pieces are on their way
+    unsigned v0 = lds_addr(Kring + (cur.y & 0xffffu)), v1 = lds_addr(Kring + (cur.y >> 16));
+    unsigned va_addr[3][2];
+#pragma unroll
+    for (int dt = 1; dt < 4; ++dt) { va_addr[dt - 1][0] = v0 ^ (32u * dt); va_addr[dt - 1][1] = v1 ^ (32u * dt); }
+    asm volatile("" : "+v"(v0), "+v"(v1), "+v"(va_addr[0][0]), "+v"(va_addr[0][1]), "+v"(va_addr[1][0]),
+                 "+v"(va_addr[1][1]), "+v"(va_addr[2][0]), "+v"(va_addr[2][1]));
+    lds_wait_k(k00, k01, k10, k11);
+    // (the masks were requested before the K pieces and share their counter: they are in,
+    // and the compiler should know before the V^T reads go out, or it waits for those too)
+    asm volatile("" : : "s"(mk[0]), "s"(mk[1]), "s"(mk[2]), "s"(mk[3]), "s"(mk[4]), "s"(mk[5]), "s"(mk[6]), "s"(mk[7]));
     f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
-    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k00), ps.qb0, S0, 0, 0, 0);
-    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k10), ps.qb0, S1, 0, 0, 0);
-    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k01), ps.qb1, S0, 0, 0, 0);
-    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k11), ps.qb1, S1, 0, 0, 0);
+    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k00), ps.qb0, S0, 0, 0, 0);
+    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k10), ps.qb0, S1, 0, 0, 0);
+    S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k01), ps.qb1, S0, 0, 0, 0);
+    S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k11), ps.qb1, S1, 0, 0, 0);
 
+    // V^T operands: issued behind the score MFMAs, consumed after the exponentials
+    uint2 va[4][2];
+    lds_read_v<VOFF>(v0, v1, va_addr, va);
     float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
 #pragma unroll
     for (int e = 0; e < 8; ++e) sv[e] = mask_select(sv[e], mk[e]);
@@ -275,7 +336,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     // wave has crossed its threshold.
     const float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                            fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-    if (__builtin_amdgcn_ballot_w64(mx > ps.thr) != 0) {   // rare after the first steps
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > ps.thr) != 0, 0)) {   // rare after the first steps
       const float mxr = max_across_rows(mx);
       const bool grow = mxr > ps.thr;
       const float negmc_new = grow ? -mxr * c : ps.negmc;
@@ -287,9 +348,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       for (int dt = 0; dt < 4; ++dt) ps.O[dt] *= alpha;
     }
     const float negmc = ps.negmc;
-    // V^T operands: issued here, consumed after the exponentials
-    uint2 va[4][2];
-    lds_read_v<VOFF>(lds_addr(Kring + (cur.y & 0xffffu)), lds_addr(Kring + (cur.y >> 16)), va);
     float p[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c, negmc));
@@ -308,14 +366,20 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   // ---- phases ----
   int doneA = 0, doneB = 0;                             // steps finished so far
+  LV_TL_BEGIN(tl_loop);
   auto run_phase = [&](int ph, auto has_next) {
     constexpr bool NEXT = decltype(has_next)::value;
     // (scalar loads, two phases ahead of their use)
     const int end2A = peA[min(ph + 2, P - 1)], end2B = peB[min(ph + 2, P - 1)];
+    LV_TL_BEGIN(tl_later);
     load_later(dAl, descA, doneA, lastA);
     load_later(dBl, descB, doneB, lastB);
+    LV_TL_ADD(9, tl_later);
+    LV_TL_BEGIN(tl_first);
     if (doneA < endA) run_step(A, dA0, maskA, doneA);
     if (doneB < endB) run_step(B, dB0, maskB, doneB);
+    LV_TL_ADD(8, tl_first);
+    LV_TL_BEGIN(tl_issue);
     if constexpr (NEXT) {
       // The later descriptors have had two steps to arrive; with nothing else outstanding
       // when the chunks go out, no later use of a loaded register has to wait for them
@@ -327,6 +391,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       dB0 = load_desc(descB, min(endB, lastB));
       tokn0 = load_tok(2 * ph + 4); tokn1 = load_tok(2 * ph + 5);
     }
+    LV_TL_ADD(9, tl_issue);
+    LV_TL_BEGIN(tl_rest);
 #pragma unroll
     for (int i = 0; i < kLater; ++i)
       if (doneA + 1 + i < endA) run_step(A, dAl[i], maskA, doneA + 1 + i);
@@ -336,19 +402,27 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     for (int i = 0; i < kLater; ++i)
       if (doneB + 1 + i < endB) run_step(B, dBl[i], maskB, doneB + 1 + i);
     for (int s = doneB + 1 + kLater; s < endB; ++s) run_step(B, load_desc(descB, s), maskB, s);
+    LV_TL_ADD(8, tl_rest);
     doneA = endA; doneB = endB;
     endA = end1A; endB = end1B; end1A = end2A; end1B = end2B;
     // Chunks 2 ph + 2 and 2 ph + 3, the next descriptors and tokens are in once nothing of
     // this wave is outstanding.  All LDS reads of the phase have returned (each step waits
     // for its own), so after the barrier the slots of chunks 2 ph - 1 and 2 ph are free.
+    LV_TL_BEGIN(tl_wait);
     wait_vmcnt<0>();
+    LV_TL_ADD(13, tl_wait);
+    LV_TL_BEGIN(tl_bar);
     if constexpr (NEXT) asm volatile("s_barrier" ::: "memory");
+    LV_TL_ADD(10, tl_bar);
   };
   {
     int ph = 0;
     for (; ph + 1 < P; ++ph) run_phase(ph, std::true_type{});
     run_phase(ph, std::false_type{});
   }
+
+  LV_TL_ADD(11, tl_loop);
+  LV_TL_WALL(5);
 
   // ---- epilogue ----
   auto store_patch = [&](const PatchState& ps, const PatchWords& w) {
@@ -369,6 +443,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   };
   store_patch(A, pwA);
   store_patch(B, pwB);
+  LV_TL_WALL(6);
+  LV_TL_FLUSH(a, blockIdx.x * kPairWaves + wave, lane);
 }
 
 litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
