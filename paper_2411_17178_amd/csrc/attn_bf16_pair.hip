@@ -176,11 +176,17 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // (tokens and descriptors through buffer loads: a scalar resource and a scalar offset plus a
   // lane offset register, where a flat address costs 64-bit vector arithmetic per load)
   const __amdgpu_buffer_rsrc_t tok_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)utok, 0, NC * C * 4, kBufferFlags);
-  auto load_tok = [&](int t) -> int {                  // this lane's row of chunk t (clamped to the last chunk)
+  // this lane's row of chunk t (clamped to the last chunk): load_tok() fetches the list entry
+  // unless the whole chunk lies in the identity prefix, tok_of() applied to its result at the
+  // time of use (when the load has been waited for) gives the token
+  auto load_tok = [&](int t) -> int {
     const int tc = min(t, NC - 1);
-    const int v = (int)__builtin_amdgcn_raw_buffer_load_b32(tok_rsrc, row * 4, tc * C * 4, 0);
-    const int i = tc * C + row;
-    return i < ident ? i : v;
+    if ((tc + 1) * C <= ident) return 0;               // (uniform)
+    return (int)__builtin_amdgcn_raw_buffer_load_b32(tok_rsrc, row * 4, tc * C * 4, 0);
+  };
+  auto tok_of = [&](int t, int loaded) -> int {
+    const int i = min(t, NC - 1) * C + row;
+    return i < ident ? i : loaded;
   };
 
   // ---- prologue, scalar part.  Everything that comes through scalar loads (patch
@@ -211,8 +217,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     issue_chunk(1, C + row);
   } else {
     const int t0 = load_tok(0), t1 = load_tok(1);
-    issue_chunk(0, t0);
-    issue_chunk(1, t1);
+    issue_chunk(0, tok_of(0, t0));
+    issue_chunk(1, tok_of(1, t1));
   }
 
   LV_TL_WALL(1);
@@ -263,12 +269,14 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   uint2 dA0 = make_uint2(0u, 0u), dB0 = dA0, dAl[kLater], dBl[kLater];
 #pragma unroll
   for (int i = 0; i < kLater; ++i) { dAl[i] = dA0; dBl[i] = dA0; }
-  // (all loads of a phase are unconditional, from clamped indices, so that their number is
-  // static and the compiler's waits stay exact: a conditional load would make it wait for
-  // everything, the chunks in flight included, before each later use of a loaded register)
-  auto load_later = [&](uint2 (&d)[kLater], const __amdgpu_buffer_rsrc_t& rsrc, int first, int last) {
+  // (Every register that a vector load fills is used only behind an explicit wait for all
+  // of the wave's loads: with chunks in flight the compiler would otherwise place such a wait,
+  // the chunks included, before the use.  That also allows loads under uniform conditions,
+  // whose number the compiler cannot know: only the descriptors that the phase needs.)
+  auto load_later = [&](uint2 (&d)[kLater], const __amdgpu_buffer_rsrc_t& rsrc, int first, int end) {
 #pragma unroll
-    for (int i = 0; i < kLater; ++i) d[i] = load_desc(rsrc, min(first + 1 + i, last));
+    for (int i = 0; i < kLater; ++i)
+      if (first + 1 + i < end) d[i] = load_desc(rsrc, first + 1 + i);
   };
   dA0 = load_desc(descA, 0);
   dB0 = load_desc(descB, 0);
@@ -372,8 +380,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     // (scalar loads, two phases ahead of their use)
     const int end2A = peA[min(ph + 2, P - 1)], end2B = peB[min(ph + 2, P - 1)];
     LV_TL_BEGIN(tl_later);
-    load_later(dAl, descA, doneA, lastA);
-    load_later(dBl, descB, doneB, lastB);
+    load_later(dAl, descA, doneA, endA);
+    load_later(dBl, descB, doneB, endB);
     LV_TL_ADD(9, tl_later);
     LV_TL_BEGIN(tl_first);
     if (doneA < endA) run_step(A, dA0, maskA, doneA);
@@ -385,7 +393,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       // when the chunks go out, no later use of a loaded register has to wait for them
       // (the compiler would otherwise wait for everything, the chunks included).
       wait_vmcnt<0>();
-      issue_chunk(2 * ph + 2, tokn0); issue_chunk(2 * ph + 3, tokn1);
+      issue_chunk(2 * ph + 2, tok_of(2 * ph + 2, tokn0)); issue_chunk(2 * ph + 3, tok_of(2 * ph + 3, tokn1));
       // first descriptors and tokens of the next phase: in place, their users are done
       dA0 = load_desc(descA, min(endA, lastA));
       dB0 = load_desc(descB, min(endB, lastB));
