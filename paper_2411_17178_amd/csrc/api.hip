@@ -211,6 +211,10 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   const int64_t esize = dt == LITEVAR_BF16 ? 2 : 4;
   if ((int64_t)plan->kv_len * a.ks[2] * esize >= ((int64_t)1 << 31))
     return fail(LITEVAR_E_UNSUPPORTED, "one (batch, head) slab of k/v spans 2 GiB or more");
+  // (the kernels form token x stride with 24-bit multiplies: tokens are below 2^24 by the
+  // line above, since a token's row is at least 128 bytes from the next)
+  if (a.ks[2] * esize >= ((int64_t)1 << 24))
+    return fail(LITEVAR_E_UNSUPPORTED, "k/v token stride of 16 MiB or more");
   a.q = d_q; a.k = d_k; a.v = d_v; a.o = d_o;
   a.B = B; a.H = H; a.sm_scale = sm_scale;
   a.cfg_share = (flags & LITEVAR_FLAG_CFG_SHARE) ? d_cfg_share : nullptr;

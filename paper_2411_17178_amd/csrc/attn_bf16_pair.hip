@@ -68,7 +68,7 @@ namespace {
 
 constexpr int kPairWaves = 8;         // waves per workgroup
 constexpr int kDmaKeys = 64;          // keys per chunk (the unit of loading and of ring slot reuse)
-constexpr int kPhaseChunks = 2;       // chunks per phase
+constexpr int kPhaseChunks = 2;       // chunks per phase (the first phase has one)
 constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two landing
 constexpr int kBufferFlags = 0x00020000;   // word 3 of a raw buffer resource on gfx9: 32-bit data format
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
@@ -152,8 +152,10 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int n = lane & 15, g4 = lane >> 4;
-  const int P = __builtin_amdgcn_readfirstlane(gd.n_phases);
-  const int NC = kPhaseChunks * P;                 // chunks of the (padded) key list
+  // The plan counts 64-key chunks.  Phase 0 is chunk 0 alone, so that the first steps start
+  // on the smallest possible amount of data; phase p >= 1 is chunks 2 p - 1 and 2 p.
+  const int NC = __builtin_amdgcn_readfirstlane(gd.n_phases);   // chunks of the (padded) key list
+  const int P = NC / 2 + 1;                                     // phases
 
   // ---- loading duty: rows [8 wave, 8 wave + 8) of every chunk ----
   const unsigned char* Kp = (const unsigned char*)((const __bf16*)a.k + b * a.ks[0] + h * a.ks[1]);
@@ -169,7 +171,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   static_assert((kDmaKeys & 63) == 0, "the swizzle folds slot bits 0..5 only");
   auto issue_chunk = [&](int t, int tok) {             // chunk t -> ring slots (t % 5) * 64 ...
     const int slot0 = (t % kRingChunks) * C + 8 * wave;
-    const unsigned src = (unsigned)tok * row_bytes + piece_off;
+    const unsigned src = __umul24((unsigned)tok, row_bytes) + piece_off;   // (both below 2^24, checked by the API)
     __builtin_amdgcn_global_load_lds((global_void*)(Kp + src), (lds_void*)(Kring + slot0 * kRingRowBytes), 16, 0, 0);
     __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
   };
@@ -197,29 +199,26 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int pa = wave, pb_ = ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1);   // p and its partner two patch rows below, columns swapped
   const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp * 16 + pa), wB = (const_i32_ptr)(a.waves + grp * 16 + pb_);
   const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
-  const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * P);
-  const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * P);
+  const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * NC);
+  const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * NC);
+  auto last_chunk = [&](int ph) -> int { return min(2 * ph, NC - 1); };   // of phase ph (clamped)
   struct PatchWords { int step_begin, q_base, sk_ny, nx_kq; };
   const PatchWords pwA = {wA[0], wA[2], wA[3], wA[4]}, pwB = {wB[0], wB[2], wB[3], wB[4]};
   const int first_step = wF[0], n_group_steps = wL[0] + wL[1] - first_step;
   // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
   // phase p + 2 is fetched during phase p
   int endA = peA[0], endB = peB[0];
-  int end1A = peA[P > 1 ? 1 : 0], end1B = peB[P > 1 ? 1 : 0];
+  int end1A = peA[last_chunk(1)], end1B = peB[last_chunk(1)];
   asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.nx_kq),
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.nx_kq),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
 
-  // ---- prologue, vector part: chunks 0 and 1 first.  The key list usually starts with
-  // whole key scales (token = position), which needs no token load.
-  if (ident >= 2 * C || ident >= NC * C) {
-    issue_chunk(0, row);
-    issue_chunk(1, C + row);
-  } else {
-    const int t0 = load_tok(0), t1 = load_tok(1);
-    issue_chunk(0, tok_of(0, t0));
-    issue_chunk(1, tok_of(1, t1));
-  }
+  // ---- prologue, vector part: chunk 0 first.  The key list usually starts with whole key
+  // scales (token = position), which needs no token load; otherwise the tokens of the first
+  // three chunks are fetched (and waited for) before anything else is in flight.
+  int tok0 = load_tok(0), tok1 = load_tok(1), tok2 = load_tok(2);
+  tok0 = tok_of(0, tok0); tok1 = tok_of(1, tok1); tok2 = tok_of(2, tok2);
+  asm volatile("" : "+v"(tok0), "+v"(tok1), "+v"(tok2));   // (here: waits for the three, if they were loaded at all)
 
   LV_TL_WALL(1);
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
@@ -280,7 +279,10 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   };
   dA0 = load_desc(descA, 0);
   dB0 = load_desc(descB, 0);
-  int tokn0 = load_tok(2), tokn1 = load_tok(3);         // tokens of the chunks issued in phase 0
+  int tokn0 = load_tok(3), tokn1 = load_tok(4);         // tokens of the chunks issued in phase 1
+  // the later descriptors of phase 0, which has no wait of its own before their use
+  load_later(dAl, descA, 0, endA);
+  load_later(dBl, descB, 0, endB);
   // All workgroups walk the same plan in lock-step, so each phase's first access to its part
   // of the plan would be an HBM miss on every workgroup's critical path.  The workgroups of
   // one XCD (they share an L2) therefore touch the group's step descriptors and lane masks
@@ -298,10 +300,14 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     const char* src = l < lines_d ? da + (int64_t)l * 128 : ma + (int64_t)(l - lines_d) * 128;
     warm = *(const int*)src;
   }
+  // The chunks go out behind the small loads (a load issued behind a chunk is held up until
+  // the chunk's data is in), chunks 1 and 2 (phase 1) last: phase 0 waits for everything but them.
+  issue_chunk(0, tok0);
+  issue_chunk(1, tok1);
+  issue_chunk(2, tok2);
   LV_TL_WALL(2);
-  wait_vmcnt<0>();
+  wait_vmcnt<4>();
   LV_TL_WALL(3);
-  asm volatile("" : : "v"(warm));                        // the only use of the plan-touching load: keeps it
   asm volatile("s_barrier" ::: "memory");
   LV_TL_WALL(4);
 
@@ -375,13 +381,15 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // ---- phases ----
   int doneA = 0, doneB = 0;                             // steps finished so far
   LV_TL_BEGIN(tl_loop);
-  auto run_phase = [&](int ph, auto has_next) {
-    constexpr bool NEXT = decltype(has_next)::value;
+  auto run_phase = [&](int ph, auto is_first, auto has_next) {
+    constexpr bool FIRST = decltype(is_first)::value, NEXT = decltype(has_next)::value;
     // (scalar loads, two phases ahead of their use)
-    const int end2A = peA[min(ph + 2, P - 1)], end2B = peB[min(ph + 2, P - 1)];
+    const int end2A = peA[last_chunk(ph + 2)], end2B = peB[last_chunk(ph + 2)];
     LV_TL_BEGIN(tl_later);
-    load_later(dAl, descA, doneA, endA);
-    load_later(dBl, descB, doneB, endB);
+    if constexpr (!FIRST) {            // (phase 0: fetched in the prologue)
+      load_later(dAl, descA, doneA, endA);
+      load_later(dBl, descB, doneB, endB);
+    }
     LV_TL_ADD(9, tl_later);
     LV_TL_BEGIN(tl_first);
     if (doneA < endA) run_step(A, dA0, maskA, doneA);
@@ -389,15 +397,22 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     LV_TL_ADD(8, tl_first);
     LV_TL_BEGIN(tl_issue);
     if constexpr (NEXT) {
-      // The later descriptors have had two steps to arrive; with nothing else outstanding
-      // when the chunks go out, no later use of a loaded register has to wait for them
-      // (the compiler would otherwise wait for everything, the chunks included).
-      wait_vmcnt<0>();
-      issue_chunk(2 * ph + 2, tok_of(2 * ph + 2, tokn0)); issue_chunk(2 * ph + 3, tok_of(2 * ph + 3, tokn1));
+      if constexpr (!FIRST) {
+        // The later descriptors have had two steps to arrive; with nothing else outstanding
+        // when the chunks go out, no later use of a loaded register has to wait for them
+        // (the compiler would otherwise wait for everything, the chunks included).
+        wait_vmcnt<0>();
+      }
       // first descriptors and tokens of the next phase: in place, their users are done
+      // (ahead of the chunks: a load issued behind a chunk is held up until its data is in)
       dA0 = load_desc(descA, min(endA, lastA));
       dB0 = load_desc(descB, min(endB, lastB));
-      tokn0 = load_tok(2 * ph + 4); tokn1 = load_tok(2 * ph + 5);
+      if constexpr (!FIRST) {
+        const int t0 = tok_of(2 * ph + 1, tokn0), t1 = tok_of(2 * ph + 2, tokn1);
+        tokn0 = load_tok(2 * ph + 3); tokn1 = load_tok(2 * ph + 4);
+        // the chunks of phase ph + 1, into the slots of chunks 2 ph - 4 and 2 ph - 3
+        issue_chunk(2 * ph + 1, t0); issue_chunk(2 * ph + 2, t1);
+      }
     }
     LV_TL_ADD(9, tl_issue);
     LV_TL_BEGIN(tl_rest);
@@ -413,9 +428,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     LV_TL_ADD(8, tl_rest);
     doneA = endA; doneB = endB;
     endA = end1A; endB = end1B; end1A = end2A; end1B = end2B;
-    // Chunks 2 ph + 2 and 2 ph + 3, the next descriptors and tokens are in once nothing of
+    // The chunks of phase ph + 1, the next descriptors and tokens are in once nothing of
     // this wave is outstanding.  All LDS reads of the phase have returned (each step waits
-    // for its own), so after the barrier the slots of chunks 2 ph - 1 and 2 ph are free.
+    // for its own), so after the barrier the slots of chunks 2 ph - 3 and 2 ph - 2 are free.
     LV_TL_BEGIN(tl_wait);
     wait_vmcnt<0>();
     LV_TL_ADD(13, tl_wait);
@@ -424,13 +439,16 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     LV_TL_ADD(10, tl_bar);
   };
   {
-    int ph = 0;
-    for (; ph + 1 < P; ++ph) run_phase(ph, std::true_type{});
-    run_phase(ph, std::false_type{});
+    run_phase(0, std::true_type{}, std::true_type{});
+    int ph = 1;
+    for (; ph + 1 < P; ++ph) run_phase(ph, std::false_type{}, std::true_type{});
+    run_phase(ph, std::false_type{}, std::false_type{});    // (no steps left when the list is one chunk)
   }
 
   LV_TL_ADD(11, tl_loop);
   LV_TL_WALL(5);
+
+  asm volatile("" : : "v"(warm));      // the only use of the plan-touching load: keeps it
 
   // ---- epilogue ----
   auto store_patch = [&](const PatchState& ps, const PatchWords& w) {
@@ -456,7 +474,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 }
 
 litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
-  if (pl->waves_per_group != 16 || pl->chunk_keys != kPhaseChunks * kDmaKeys || pl->ring_chunks != kRingChunks)
+  if (pl->waves_per_group != 16 || pl->chunk_keys != kDmaKeys || pl->ring_chunks != kRingChunks)
     return fail(LITEVAR_E_PLAN_CORRUPT, "no 16-patch kernel for chunk=%d ring=%d", pl->chunk_keys, pl->ring_chunks);
   const int64_t bh8 = ((int64_t)a.B * a.H + 7) / 8 * 8;
   const int64_t blocks = bh8 * a.n_groups;

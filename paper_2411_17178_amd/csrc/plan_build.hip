@@ -20,9 +20,10 @@ static void choose_tiling(Geom& g, int waves, int chunk, int depth, int spare) {
   while ((1 << g.logC) < g.C) ++g.logC;
   g.logS = g.logC; g.R = g.NR * g.C;
   if (waves == 16) {
-    // phases of 128 keys over a ring of five 64-key chunks: one chunk of look-back, the two
-    // of the phase and the two that are landing; ring and prefetch depth count 64-key chunks
-    g.logS = 6; g.NR = 5; g.R = 320;
+    // The 16-patch kernel runs phases of two 64-key chunks (`chunk` = 128 keys) over a ring
+    // of five: one chunk of look-back, the two of the phase and the two that are landing.
+    // The plan counts in 64-key chunks (phase tables, list padding, ring depth).
+    g.C = 64; g.logC = 6; g.logS = 6; g.NR = 5; g.R = 320;
   }
 }
 
