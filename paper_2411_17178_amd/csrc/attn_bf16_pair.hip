@@ -73,6 +73,7 @@ constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two
 constexpr int kBufferFlags = 0x00020000;   // word 3 of a raw buffer resource on gfx9: 32-bit data format
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+constexpr int kBoostPhases = 3;       // phases that a later-arrived workgroup runs at raised priority
 constexpr int kLater = 2;             // descriptors per patch, beyond the first step of a phase, that are
                                       // fetched at the start of the phase
 
@@ -143,6 +144,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   LV_TL_DECL;
   LV_TL_WALL(0);
+  // Two workgroups share a CU, and the instruction arbiter prefers the older waves: left
+  // alone, the workgroup that arrived first runs as if it had the CU to itself and the other
+  // one finishes a quarter later, alone on a CU that it cannot fill.  The later arrival (it
+  // gets the higher wave slots of each SIMD) therefore runs at raised priority through its
+  // first phases, which evens out the two finishing times.
+  const bool later_arrival = (__builtin_amdgcn_s_getreg(4 | (3 << 11)) & 0xf) >= 2;   // HW_ID.WAVE_ID
+  if (later_arrival) __builtin_amdgcn_s_setprio(1);
 #ifdef LITEVAR_TIMELINE
   // experiment: delay the first (tune[0] = 1) or the later (2) workgroups of a CU by tune[1] x 64 cycles
   if ((a.tune[0] == 1 && seq < a.tune[2]) || (a.tune[0] == 2 && seq >= a.tune[2]))
@@ -383,6 +391,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   LV_TL_BEGIN(tl_loop);
   auto run_phase = [&](int ph, auto is_first, auto has_next) {
     constexpr bool FIRST = decltype(is_first)::value, NEXT = decltype(has_next)::value;
+    if (!FIRST && ph == kBoostPhases) __builtin_amdgcn_s_setprio(0);
     // (scalar loads, two phases ahead of their use)
     const int end2A = peA[last_chunk(ph + 2)], end2B = peB[last_chunk(ph + 2)];
     LV_TL_BEGIN(tl_later);
