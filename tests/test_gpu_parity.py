@@ -269,6 +269,16 @@ ATTN_CASES = [
     ((2, 40), 7, 0, (1, 2), 2, 1),
     ((5, 21, 33), 2, 0, None, 1, 3),
     ((1, 3, 70), 40, 0, (2, 3), 1, 1),           # window boxes wider than a wave
+    # dense key lists of 55, 91, 128, 140, 192, 204 and 285 keys: one to five 64-key chunks,
+    # with and without a ragged last chunk (the 16-patch kernel's first phase is one chunk,
+    # the others two)
+    ((1, 2, 3, 4, 5), -1, 0, (4, 5), 1, 2),
+    ((1, 2, 3, 4, 5, 6), -1, 0, (5, 6), 1, 2),
+    ((8, 8), -1, 0, (1, 2), 1, 2),
+    ((1, 2, 3, 4, 5, 6, 7), -1, 0, (6, 7), 1, 2),
+    ((8, 8, 8), -1, 0, (2, 3), 1, 1),
+    ((1, 2, 3, 4, 5, 6, 7, 8), -1, 0, (7, 8), 1, 1),
+    ((1, 2, 3, 4, 5, 6, 7, 8, 9), -1, 0, (8, 9), 1, 1),
 ]
 
 
