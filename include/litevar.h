@@ -85,7 +85,8 @@ typedef struct litevar_plan {
   int32_t q_token_begin;    /* index in the full sequence of query row 0 */
   int32_t side_max;         /* largest s_k */
   int32_t waves_per_group;  /* 4x4 query patches handled by one workgroup */
-  int32_t chunk_keys;       /* keys staged into LDS per phase */
+  int32_t chunk_keys;       /* keys per chunk of the key stream (the unit of loading and of LDS ring reuse;
+                               64 for 16 patches per group, whose kernel runs phases of two chunks) */
   int32_t ring_chunks;      /* LDS ring depth in chunks = look-back (1) + 1 + prefetch + spare */
   int32_t prefetch_chunks;  /* chunks the loader keeps in flight */
   int32_t n_groups;         /* workgroup tiles per (batch, head) */
