@@ -63,7 +63,7 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
   if (waves == 0) {
     int sq = 0;
     for (int k = g.qb; k < g.qe; ++k) if (g.s[k] > sq) sq = g.s[k];
-    waves = sq >= 8 ? 16 : 4;
+    waves = sq > 8 ? 16 : 4;    // (queries of side <= 8 are one group of 2 x 2 patches: the smaller kernel is quicker)
   }
   if (waves != 4 && waves != 8 && waves != 16)
     return fail(LITEVAR_E_INVALID_ARG, "waves_per_group must be 0, 4, 8 or 16 (got %d)", waves);
