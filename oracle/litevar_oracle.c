@@ -350,6 +350,60 @@ int lvo_cfg_share(int32_t K, const int32_t* scales, int32_t qb, int32_t qe,
   return LVO_OK;
 }
 
+/* ---- window calibration (Section 2: the metric R_w and the threshold R_0) ----
+ *
+ * For every head, query scale k and part j <= k of a post-softmax attention
+ * map: R_w = (sum of the map's values inside the window) / (sum of all values
+ * of the part); the window grows from zero until R_w reaches R_0.  The map
+ * p[N][H][L][L] holds N reference samples; reading taken here: their values
+ * are summed (one window per head, scale and part for the whole reference
+ * set), a part is one key scale, and "window size zero" is radius 0, the
+ * centre key alone (the same square window and centre map as above).
+ *
+ * radius[h][k][j] = smallest r >= 0 with R_w >= R_0 (0 for a part without
+ * mass; entries with j > k are set to -1).  mass[h][k][j][r], optional, is
+ * the in-window sum at radius r for r < smax (the whole part's sum once the
+ * window covers the part). */
+int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, int32_t H,
+                  double r0, int32_t* radius, double* mass, int32_t smax) {
+  if (K < 1 || !scales || !p || !radius || N < 1 || H < 1) return LVO_BAD_ARG;
+  for (int32_t k = 0; k < K; ++k) if (scales[k] < 1 || scales[k] > smax) return LVO_BAD_ARG;
+  const int64_t L = lvo_seq_len(K, scales);
+  int32_t* rad = (int32_t*)malloc((size_t)K * sizeof(int32_t));
+  if (!rad) return LVO_NO_MEM;
+  for (int32_t h = 0; h < H; ++h)
+    for (int32_t k = 0; k < K; ++k)
+      for (int32_t j = 0; j < K; ++j) {
+        int32_t* out = radius + ((int64_t)h * K + k) * K + j;
+        double* mout = mass ? mass + (((int64_t)h * K + k) * K + j) * smax : NULL;
+        if (mout) for (int32_t r = 0; r < smax; ++r) mout[r] = 0.0;
+        if (j > k) { *out = -1; continue; }
+        const int64_t oq = lvo_scale_offset(K, scales, k), ok = lvo_scale_offset(K, scales, j);
+        const int32_t sk = scales[k], sj = scales[j];
+        int32_t found = -1;
+        for (int32_t r = 0; r < smax; ++r) {          /* the window grows from zero */
+          for (int32_t i = 0; i < K; ++i) rad[i] = r;
+          double in = 0.0, all = 0.0;
+          for (int32_t n = 0; n < N; ++n)
+            for (int32_t qy = 0; qy < sk; ++qy)
+              for (int32_t qx = 0; qx < sk; ++qx)
+                for (int32_t ky = 0; ky < sj; ++ky)
+                  for (int32_t kx = 0; kx < sj; ++kx) {
+                    const int64_t q = oq + (int64_t)qy * sk + qx, t = ok + (int64_t)ky * sj + kx;
+                    const double v = p[(((int64_t)n * H + h) * L + q) * L + t];
+                    all += v;
+                    if (allowed_coords(scales, rad, 0, k, qy, qx, j, ky, kx)) in += v;
+                  }
+          if (mout) mout[r] = in;
+          if (found < 0 && (all == 0.0 || in / all >= r0)) found = r;
+          if (found >= 0 && !mout) break;
+        }
+        *out = found < 0 ? sj - 1 : found;
+      }
+  free(rad);
+  return LVO_OK;
+}
+
 int lvo_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -189,5 +189,24 @@ def cfg_share(scales, o, share, q_scales=None):
     return o
 
 
+def calibrate(scales, p, r0, with_mass=False):
+    """Window radii from a post-softmax attention map p[N][H][L][L] (float64): the smallest
+    radius per (head, query scale, key scale) whose window holds the fraction r0 of the
+    part's values.  Returns radius[H][K][K] (and mass[H][K][K][smax] when asked)."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    N, H, L, L2 = p.shape
+    K = len(scales)
+    assert L == L2 == seq_len(scales)
+    smax = int(max(scales))
+    radius = np.zeros((H, K, K), dtype=np.int32)
+    mass = np.zeros((H, K, K, smax), dtype=np.float64) if with_mass else None
+    sc = _i32(scales)
+    rc = _L().lvo_calibrate(C.c_int32(K), _p(sc), _p(p), C.c_int32(N), C.c_int32(H),
+                            C.c_double(float(r0)), _p(radius), _p(mass) if with_mass else None,
+                            C.c_int32(smax))
+    assert rc == 0, rc
+    return (radius, mass) if with_mass else radius
+
+
 def num_threads():
     return int(_L().lvo_num_threads())

@@ -44,6 +44,33 @@ def make_cfg_share(heads, n_scales, seed, p=0.5):
     return (torch.rand(heads, n_scales, generator=g) < p).to(torch.uint8)
 
 
+def make_attn_map(scales, n_samples, heads, seed, sigma=(0.05, 0.4), noise=0.3):
+    """Synthetic post-softmax attention maps [N, H, L, L] (float32), standing in for the
+    reference maps that the paper collects from training images: block-causal across
+    scales, each row a noisy bump around the query's own image position (positions taken as
+    cell centres in the unit square, so no part of the method's window arithmetic enters),
+    head h with its own width between sigma[0] and sigma[1], every row normalised to sum 1."""
+    g = np.random.default_rng(seed)
+    pos, scale_of = [], []
+    for k, s in enumerate(scales):
+        c = (np.arange(s) + 0.5) / s
+        yy, xx = np.meshgrid(c, c, indexing="ij")
+        pos.append(np.stack([yy.ravel(), xx.ravel()], axis=1))
+        scale_of.append(np.full(s * s, k))
+    pos, scale_of = np.concatenate(pos), np.concatenate(scale_of)
+    L = len(pos)
+    d2 = ((pos[:, None, :] - pos[None, :, :]) ** 2).sum(-1)
+    causal = scale_of[None, :] <= scale_of[:, None]
+    out = np.empty((n_samples, heads, L, L), dtype=np.float32)
+    for h in range(heads):
+        sg = sigma[0] + (sigma[1] - sigma[0]) * (h / max(heads - 1, 1))
+        base = np.exp(-d2 / (2 * sg * sg))
+        for n in range(n_samples):
+            w = base * np.exp(noise * g.standard_normal((L, L))) * causal
+            out[n, h] = (w / w.sum(axis=1, keepdims=True)).astype(np.float32)
+    return torch.from_numpy(out)
+
+
 def bf16_bits(t):
     """numpy uint16 view of a CPU bf16 tensor's bit patterns (no copy of values)."""
     assert t.dtype == torch.bfloat16 and t.device.type == "cpu"
