@@ -206,6 +206,35 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
                                          const uint8_t* d_cfg_share, uint32_t flags,
                                          void* stream);
 
+/*
+ * Window calibration (paper Section 2: the metric R_w and the threshold R_0).  From
+ * post-softmax attention maps of N reference samples, for every head, query scale k and
+ * key scale j <= k: the smallest radius r >= 0 such that the values inside the radius-r
+ * windows of the part (query scale k, key scale j), summed over the part's queries and the
+ * samples, reach the fraction r0 of all of the part's values ("the window grows from zero
+ * until R_w reaches R_0"; r0 = 1 keeps every non-zero value).  Windows and centres are those
+ * of litevar_mask_build; a part without mass gets radius 0.
+ *
+ *   scales, n_scales  HOST, as in litevar_mask_desc
+ *   d_attn       DEVICE float32 [N][H][L][L], contiguous, L = sum of s_k^2: row q holds
+ *                query q's weights over all keys (entries of later scales are not read)
+ *   r0           in (0, 1]
+ *   d_workspace  DEVICE, 8-byte aligned, at least
+ *                litevar_window_calibrate_workspace_bytes() bytes; contents undefined
+ *                before and after; calls that share a workspace must not overlap
+ *   d_radius     DEVICE int32 [H][K][K], written: [h][k][j] as above, -1 where j > k
+ *   d_mass       DEVICE float64 [H][K][K][smax] or NULL (smax = largest side): the sum
+ *                inside the window of radius r, for the parity tests
+ * Sums are formed in fp64 in a fixed order (repeatable bit for bit).  Host arrays are read
+ * during the call only; the library allocates nothing; asynchronous on `stream`.
+ */
+litevar_status litevar_window_calibrate_workspace_bytes(const int32_t* scales, int32_t n_scales,
+                                                        int32_t H, size_t* out_bytes);
+litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
+                                        const float* d_attn, int32_t N, int32_t H, float r0,
+                                        void* d_workspace, size_t workspace_bytes,
+                                        int32_t* d_radius, double* d_mass, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

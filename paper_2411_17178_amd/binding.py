@@ -67,7 +67,8 @@ def load_library():
     lib.litevar_version.restype = C.c_int32
     for name in ("litevar_mask_plan_bytes", "litevar_mask_plan_stats", "litevar_mask_build", "litevar_plan_check",
                  "litevar_window_table_export", "litevar_mask_export_dense",
-                 "litevar_mask_export_csr", "litevar_windowed_attn_fwd"):
+                 "litevar_mask_export_csr", "litevar_windowed_attn_fwd",
+                 "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate"):
         getattr(lib, name).restype = C.c_int32
     _lib = lib
     return lib
@@ -232,6 +233,31 @@ def litevar_windowed_attn_fwd(plan, q, k, v, sm_scale, out=None, cfg_share=None,
         C.c_int32(D), C.c_int32(dt), _strides(q), _strides(k), _strides(out),
         C.c_float(sm_scale), share_ptr, C.c_uint32(flags), _stream_handle(stream)))
     return out
+
+
+def litevar_window_calibrate(scales, attn_map, r0, with_mass=False, stream=None):
+    """Window radii [H, K, K] (int32, -1 above the diagonal) from post-softmax attention maps
+    `attn_map` [N, H, L, L] (float32 CUDA tensor); with_mass also returns the in-window sums
+    [H, K, K, smax] (float64)."""
+    lib = load_library()
+    assert attn_map.is_cuda and attn_map.dtype == torch.float32 and attn_map.is_contiguous()
+    N, H, L, L2 = attn_map.shape
+    K = len(scales)
+    sc = (C.c_int32 * K)(*[int(s) for s in scales])
+    n = C.c_size_t(0)
+    _check(lib.litevar_window_calibrate_workspace_bytes(sc, C.c_int32(K), C.c_int32(H), C.byref(n)))
+    assert L == L2 == sum(int(s) * int(s) for s in scales)
+    dev = attn_map.device
+    work = torch.empty(max(1, (n.value + 7) // 8), dtype=torch.float64, device=dev)
+    radius = torch.empty((H, K, K), dtype=torch.int32, device=dev)
+    mass = torch.empty((H, K, K, max(int(s) for s in scales)), dtype=torch.float64, device=dev) \
+        if with_mass else None
+    _check(lib.litevar_window_calibrate(
+        sc, C.c_int32(K), C.c_void_p(attn_map.data_ptr()), C.c_int32(N), C.c_int32(H),
+        C.c_float(r0), C.c_void_p(work.data_ptr()), C.c_size_t(work.numel() * 8),
+        C.c_void_p(radius.data_ptr()), C.c_void_p(mass.data_ptr()) if with_mass else None,
+        _stream_handle(stream)))
+    return (radius, mass) if with_mass else radius
 
 
 def prepare_attn_call(plan, q, k, v, sm_scale, out, cfg_share=None, stream=None):

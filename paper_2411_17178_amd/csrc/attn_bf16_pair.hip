@@ -68,7 +68,6 @@ namespace {
 
 constexpr int kPairWaves = 8;         // waves per workgroup
 constexpr int kDmaKeys = 64;          // keys per chunk (the unit of loading and of ring slot reuse)
-constexpr int kPhaseChunks = 2;       // chunks per phase (the first phase has one)
 constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two landing
 constexpr int kBufferFlags = 0x00020000;   // word 3 of a raw buffer resource on gfx9: 32-bit data format
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;

@@ -1,0 +1,181 @@
+// Window calibration (paper Section 2: the metric R_w and the threshold R_0): from a
+// post-softmax attention map, the smallest window radius per (head, query scale, key scale)
+// whose window holds the fraction R_0 of the part's values.
+//
+// Layout of the work.  In a part (query scale k, key scale j) a key's distance from the
+// window centre depends only on its offset (oy, ox) from that centre, and so does every
+// window it belongs to: radius r holds the offsets with max(|oy|, |ox|) <= r.  One thread
+// owns one offset and walks all queries of the part, adding the map's value at
+// (query, centre + offset) where that key exists: consecutive lanes own consecutive ox, so a
+// wave reads runs of consecutive keys of one map row; every value of the map is read exactly
+// once per launch, by exactly one thread, and summed in a fixed order in fp64 (no atomics:
+// two launches give identical bits).  A workgroup folds its 256 offsets into per-distance
+// sums (fixed order again) and writes them to the workspace; a second, small kernel adds the
+// workgroups of a part, forms the in-window sums by prefix and picks the radius.
+#include "internal.h"
+
+namespace lv {
+
+namespace {
+
+constexpr int kCalibThreads = 256;
+
+struct CalibArgs {
+  int K, N, H, smax, max_tiles;
+  int s[kMaxScales], off[kMaxScales + 1];
+  int64_t L;
+  const float* p;       // [N][H][L][L]
+  double* partial;      // [H][K][K][max_tiles][smax]: per-distance sums of one workgroup
+  int32_t* radius;      // [H][K][K]
+  double* mass;         // [H][K][K][smax] or nullptr
+  double r0;
+};
+
+__device__ inline int tiles_of(int sj) {
+  const int w = 2 * sj - 1;
+  return (w * w + kCalibThreads - 1) / kCalibThreads;
+}
+
+// grid (max_tiles, K * K, H)
+__global__ __launch_bounds__(kCalibThreads) void k_calib_mass(CalibArgs a) {
+  const int k = blockIdx.y / a.K, j = blockIdx.y % a.K, h = blockIdx.z, tile = blockIdx.x;
+  if (j > k) return;
+  const int sk = a.s[k], sj = a.s[j];
+  if (tile >= tiles_of(sj)) return;
+  __shared__ short cen[kMaxSide];          // centre of query coordinate c in key scale j
+  __shared__ double sum_of[kCalibThreads];
+  __shared__ short dist_of[kCalibThreads];
+  for (int c = threadIdx.x; c < sk; c += kCalibThreads)
+    cen[c] = (short)(((2 * c + 1) * sj) / (2 * sk));
+  __syncthreads();
+
+  const int w = 2 * sj - 1, o = tile * kCalibThreads + threadIdx.x;
+  const bool live = o < w * w;
+  const int oy = live ? o / w - (sj - 1) : 0, ox = live ? o % w - (sj - 1) : 0;
+  double acc = 0.0;
+  if (live) {
+    for (int n = 0; n < a.N; ++n) {
+      const float* base = a.p + ((int64_t)n * a.H + h) * a.L * a.L + (int64_t)a.off[k] * a.L + a.off[j];
+      for (int qy = 0; qy < sk; ++qy) {
+        const int ky = cen[qy] + oy;
+        if (ky < 0 || ky >= sj) continue;
+        const float* row = base + (int64_t)qy * sk * a.L + ky * sj;
+        for (int qx = 0; qx < sk; ++qx) {
+          const int kx = cen[qx] + ox;
+          if (kx >= 0 && kx < sj) acc += (double)row[(int64_t)qx * a.L + kx];
+        }
+      }
+    }
+  }
+  sum_of[threadIdx.x] = acc;
+  dist_of[threadIdx.x] = live ? (short)max(abs(oy), abs(ox)) : (short)-1;
+  __syncthreads();
+  double* out = a.partial + ((((int64_t)h * a.K + k) * a.K + j) * a.max_tiles + tile) * a.smax;
+  for (int d = threadIdx.x; d < sj; d += kCalibThreads) {
+    double s = 0.0;
+    for (int i = 0; i < kCalibThreads; ++i)
+      if (dist_of[i] == d) s += sum_of[i];
+    out[d] = s;
+  }
+}
+
+// grid (K * K, H), one wave
+__global__ __launch_bounds__(64) void k_calib_pick(CalibArgs a) {
+  const int k = blockIdx.x / a.K, j = blockIdx.x % a.K, h = blockIdx.y;
+  const int64_t part = ((int64_t)h * a.K + k) * a.K + j;
+  double* mass = a.mass ? a.mass + part * a.smax : nullptr;
+  if (j > k) {
+    if (threadIdx.x == 0) a.radius[part] = -1;
+    if (mass) for (int r = threadIdx.x; r < a.smax; r += 64) mass[r] = 0.0;
+    return;
+  }
+  const int sj = a.s[j], nt = tiles_of(sj);
+  __shared__ double ring[kMaxSide];          // values at distance exactly d
+  const double* in = a.partial + part * a.max_tiles * a.smax;
+  for (int d = threadIdx.x; d < sj; d += 64) {
+    double s = 0.0;
+    for (int t = 0; t < nt; ++t) s += in[(int64_t)t * a.smax + d];
+    ring[d] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  double total = 0.0;
+  for (int d = 0; d < sj; ++d) total += ring[d];
+  // the window grows from zero until the ratio reaches the threshold
+  double inside = 0.0;
+  int found = -1;
+  for (int r = 0; r < a.smax; ++r) {
+    if (r < sj) inside += ring[r];
+    if (mass) mass[r] = inside;
+    if (found < 0 && r < sj && (total == 0.0 || inside / total >= a.r0)) found = r;
+  }
+  a.radius[part] = found < 0 ? sj - 1 : found;
+}
+
+litevar_status calib_geom(const int32_t* scales, int32_t K, CalibArgs& a) {
+  if (!scales) return fail(LITEVAR_E_INVALID_ARG, "scales is NULL");
+  if (K < 1 || K > kMaxScales)
+    return fail(LITEVAR_E_INVALID_ARG, "n_scales must be in 1..%d (got %d)", kMaxScales, K);
+  a.K = K; a.smax = 0; a.L = 0;
+  for (int k = 0; k < K; ++k) {
+    if (scales[k] < 1 || scales[k] > kMaxSide)
+      return fail(LITEVAR_E_INVALID_ARG, "scales[%d] = %d outside 1..%d", k, scales[k], kMaxSide);
+    a.s[k] = scales[k]; a.off[k] = (int)a.L; a.L += (int64_t)scales[k] * scales[k];
+    if (a.L > ((int64_t)1 << 30)) return fail(LITEVAR_E_UNSUPPORTED, "sequence longer than 2^30 tokens");
+    if (scales[k] > a.smax) a.smax = scales[k];
+  }
+  a.off[K] = (int)a.L;
+  const int w = 2 * a.smax - 1;
+  a.max_tiles = (w * w + kCalibThreads - 1) / kCalibThreads;
+  return LITEVAR_OK;
+}
+
+size_t calib_workspace(const CalibArgs& a, int H) {
+  return (size_t)H * a.K * a.K * a.max_tiles * a.smax * sizeof(double);
+}
+
+}  // namespace
+
+}  // namespace lv
+
+using namespace lv;
+
+extern "C" {
+
+litevar_status litevar_window_calibrate_workspace_bytes(const int32_t* scales, int32_t n_scales,
+                                                        int32_t H, size_t* out_bytes) {
+  if (!out_bytes) return fail(LITEVAR_E_INVALID_ARG, "out_bytes is NULL");
+  if (H < 1) return fail(LITEVAR_E_INVALID_ARG, "H must be positive");
+  CalibArgs a;
+  if (litevar_status s = calib_geom(scales, n_scales, a)) return s;
+  *out_bytes = calib_workspace(a, H);
+  return LITEVAR_OK;
+}
+
+litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales, const float* d_attn,
+                                        int32_t N, int32_t H, float r0, void* d_workspace,
+                                        size_t workspace_bytes, int32_t* d_radius, double* d_mass,
+                                        void* stream) {
+  CalibArgs a;
+  if (litevar_status s = calib_geom(scales, n_scales, a)) return s;
+  if (N < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "N and H must be positive");
+  if (!(r0 > 0.f) || r0 > 1.f) return fail(LITEVAR_E_INVALID_ARG, "r0 must be in (0, 1] (got %g)", r0);
+  if (!d_attn || !d_radius || !d_workspace)
+    return fail(LITEVAR_E_INVALID_ARG, "d_attn, d_radius or d_workspace is NULL");
+  if (((uintptr_t)d_workspace & 7) || (d_mass && ((uintptr_t)d_mass & 7)))
+    return fail(LITEVAR_E_INVALID_ARG, "d_workspace and d_mass must be 8-byte aligned");
+  if (workspace_bytes < calib_workspace(a, H))
+    return fail(LITEVAR_E_INVALID_ARG, "workspace of %zu bytes, %zu needed", workspace_bytes,
+                calib_workspace(a, H));
+  if ((int64_t)a.K * a.K > 65535 || H > 65535)
+    return fail(LITEVAR_E_UNSUPPORTED, "grid too large");
+  a.N = N; a.H = H; a.p = d_attn; a.partial = (double*)d_workspace;
+  a.radius = d_radius; a.mass = d_mass; a.r0 = (double)r0;
+  hipStream_t st = (hipStream_t)stream;
+  hipLaunchKernelGGL(k_calib_mass, dim3(a.max_tiles, a.K * a.K, H), dim3(kCalibThreads), 0, st, a);
+  if (litevar_status s = hip_check(hipGetLastError(), "calibration mass launch")) return s;
+  hipLaunchKernelGGL(k_calib_pick, dim3(a.K * a.K, H), dim3(64), 0, st, a);
+  return hip_check(hipGetLastError(), "calibration pick launch");
+}
+
+}  // extern "C"

@@ -143,3 +143,27 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu(lv):
     assert f(q=C.c_void_p(4100)) == -1
     assert f(qs=(C.c_int64 * 3)(640, 640, 60)) == -1
     assert f(qs=(C.c_int64 * 3)(641, 640, 64)) == -1
+
+
+def test_calibrate_validation_needs_no_gpu(lv):
+    """Argument errors of the window calibration are found before any HIP call."""
+    lib = lv.load_library()
+    sc = (C.c_int32 * 3)(1, 2, 3)
+    n = C.c_size_t(0)
+    assert lib.litevar_window_calibrate_workspace_bytes(sc, 3, 2, C.byref(n)) == 0
+    # [H][K][K][tiles][smax] doubles: side 3 -> 25 offsets -> one tile of 256
+    assert n.value == 2 * 3 * 3 * 1 * 3 * 8
+    assert lib.litevar_window_calibrate_workspace_bytes(sc, 3, 0, C.byref(n)) == -1
+    assert lib.litevar_window_calibrate_workspace_bytes(None, 3, 2, C.byref(n)) == -1
+    bad = (C.c_int32 * 2)(4, 0)
+    assert lib.litevar_window_calibrate_workspace_bytes(bad, 2, 1, C.byref(n)) == -1
+    call = lib.litevar_window_calibrate
+    ptr = C.c_void_p(4096)
+    assert call(sc, 3, ptr, 1, 2, C.c_float(1.5), ptr, C.c_size_t(1 << 20), ptr, None, None) == -1
+    assert b"r0" in lib.litevar_last_error()
+    assert call(sc, 3, ptr, 1, 2, C.c_float(0.0), ptr, C.c_size_t(1 << 20), ptr, None, None) == -1
+    assert call(sc, 3, None, 1, 2, C.c_float(0.9), ptr, C.c_size_t(1 << 20), ptr, None, None) == -1
+    assert call(sc, 3, ptr, 0, 2, C.c_float(0.9), ptr, C.c_size_t(1 << 20), ptr, None, None) == -1
+    assert call(sc, 3, ptr, 1, 2, C.c_float(0.9), ptr, C.c_size_t(8), ptr, None, None) == -1
+    assert b"workspace" in lib.litevar_last_error()
+    assert call(sc, 3, ptr, 1, 2, C.c_float(0.9), C.c_void_p(4097), C.c_size_t(1 << 20), ptr, None, None) == -1

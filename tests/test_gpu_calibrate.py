@@ -1,0 +1,94 @@
+"""Window calibration (paper Section 2: metric R_w, threshold R_0) through the C ABI against
+the oracle: radii are integers decided by a floating-point comparison, so they must match
+the oracle's except where the oracle's own ratio lies within summation rounding of the
+threshold (there the neighbouring radius is valid too); the in-window sums match to the
+rounding of fp64 sums taken in different orders."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+VAR_SCALES = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+
+
+@pytest.fixture(scope="module")
+def lv():
+    import paper_2411_17178_amd as m
+    m.load_library()
+    return m
+
+
+def _compare(lv, scales, p32, r0):
+    print(f"  calibrate: scales={scales} map{tuple(p32.shape)} r0={r0}", flush=True)
+    rad, mass = lv.litevar_window_calibrate(scales, p32.cuda(), r0, with_mass=True)
+    torch.cuda.synchronize()
+    rad, mass = rad.cpu().numpy(), mass.cpu().numpy()
+    r0_used = float(np.float32(r0))                      # the ABI takes a float
+    want, wmass = oracle.calibrate(scales, p32.numpy().astype(np.float64), r0_used, with_mass=True)
+    # both sides sum in fp64, in different orders: the error of a sum of n non-negative terms
+    # is below n 2^-53 of the sum (n <= 2.6e6 values per part here)
+    assert np.allclose(mass, wmass, rtol=1e-9, atol=1e-13), float(np.abs(mass / np.maximum(wmass, 1e-300) - 1).max())
+    K = len(scales)
+    differ = 0
+    for h in range(p32.shape[1]):
+        for k in range(K):
+            for j in range(K):
+                g, w = rad[h, k, j], want[h, k, j]
+                if g == w:
+                    continue
+                differ += 1
+                total = wmass[h, k, j, scales[j] - 1]
+                assert j <= k and abs(g - w) == 1 and total > 0
+                assert abs(wmass[h, k, j, min(g, w)] / total - r0_used) < 1e-9, (h, k, j, g, w)
+    return rad, differ
+
+
+@pytest.mark.parametrize("r0", [0.6, 0.95, 1.0])
+def test_calibrate_var_scales(lv, r0):
+    p = workloads.make_attn_map(VAR_SCALES, 2, 3, 31)
+    rad, differ = _compare(lv, VAR_SCALES, p, r0)
+    # (at threshold 1 far-away values below the rounding of the part's sum decide: a tie)
+    assert differ == 0 or r0 == 1.0
+    assert (rad[:, np.triu_indices(10, 1)[0], np.triu_indices(10, 1)[1]] == -1).all()
+    if r0 < 1.0:    # narrow heads get narrow windows
+        assert rad[0, 9, 9] < rad[2, 9, 9]
+
+
+@pytest.mark.parametrize("scales", [(1,), (3,), (7, 2, 9, 4), (2, 17), (5, 21, 33), (40,)])
+def test_calibrate_edge_scale_lists(lv, scales):
+    """one-token scales, non-monotone sides, sides whose offsets need several 256-offset tiles"""
+    p = workloads.make_attn_map(scales, 1, 2, 7, sigma=(0.08, 0.3))
+    _compare(lv, scales, p, 0.9)
+
+
+def test_calibrate_hand_placed_mass(lv):
+    """All of a part's mass one row below the centre key: radius 1; empty parts: radius 0."""
+    scales = (1, 2, 3, 4)
+    off = (0, 1, 5, 14)
+    centre_4_to_3 = (0, 1, 1, 2)       # from the worked example (tests/golden/tiny_r1_rows.txt)
+    p = torch.zeros((1, 1, 30, 30))
+    for qy in range(4):
+        for qx in range(4):
+            cy, cx = centre_4_to_3[qy], centre_4_to_3[qx]
+            if cy + 1 < 3:
+                p[0, 0, off[3] + qy * 4 + qx, off[2] + (cy + 1) * 3 + cx] = 0.5
+    rad, _ = _compare(lv, scales, p, 0.95)
+    assert rad[0, 3, 2] == 1 and rad[0, 3, 1] == 0 and rad[0, 2, 2] == 0
+
+
+def test_calibrate_repeats_bit_for_bit_and_feeds_the_plan(lv):
+    p = workloads.make_attn_map(VAR_SCALES, 1, 2, 3).cuda()
+    a, ma = lv.litevar_window_calibrate(VAR_SCALES, p, 0.9, with_mass=True)
+    b, mb = lv.litevar_window_calibrate(VAR_SCALES, p, 0.9, with_mass=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(ma, mb)
+    # one radius per key scale for a plan: the widest window any head or query scale asked for
+    per_key_scale = a.clamp(min=0).amax(dim=(0, 1)).cpu().tolist()
+    plan = lv.litevar_mask_build(VAR_SCALES, 0, per_key_scale, 3)
+    mask, _ = lv.litevar_mask_export_dense(plan)
+    want = oracle.mask_dense(VAR_SCALES, per_key_scale, 3)
+    assert np.array_equal(mask.cpu().numpy().astype(bool), want.astype(bool))
