@@ -7,11 +7,15 @@
 // window it belongs to: radius r holds the offsets with max(|oy|, |ox|) <= r.  One thread
 // owns one offset and walks all queries of the part, adding the map's value at
 // (query, centre + offset) where that key exists: consecutive lanes own consecutive ox, so a
-// wave reads runs of consecutive keys of one map row; every value of the map is read exactly
-// once per launch, by exactly one thread, and summed in a fixed order in fp64 (no atomics:
-// two launches give identical bits).  A workgroup folds its 256 offsets into per-distance
-// sums (fixed order again) and writes them to the workspace; a second, small kernel adds the
-// workgroups of a part, forms the in-window sums by prefix and picks the radius.
+// wave reads runs of consecutive keys of one map row; every value of the map is added exactly
+// once per launch, by exactly one thread, in a fixed order in fp64 (no atomics: two launches
+// give identical bits).  (Copying the reachable key rows to LDS with coalesced loads and
+// picking from there was measured: its two barriers per batch of queries make it 2.4 times
+// slower than the direct loads.)  The (sample, query row) pairs of a part are dealt to
+// `splits` workgroups per 256 offsets, so that small maps still fill the GPU.  A workgroup
+// folds its 256 offsets into per-distance sums (fixed order again) and writes them to the
+// workspace; a second, small kernel adds the workgroups of a part, forms the in-window sums
+// by prefix and picks the radius.
 #include "internal.h"
 
 namespace lv {
@@ -21,11 +25,11 @@ namespace {
 constexpr int kCalibThreads = 256;
 
 struct CalibArgs {
-  int K, N, H, smax, max_tiles;
+  int K, N, H, smax, max_tiles, splits;
   int s[kMaxScales], off[kMaxScales + 1];
   int64_t L;
   const float* p;       // [N][H][L][L]
-  double* partial;      // [H][K][K][max_tiles][smax]: per-distance sums of one workgroup
+  double* partial;      // [H][K][K][splits][max_tiles][smax]: per-distance sums of one workgroup
   int32_t* radius;      // [H][K][K]
   double* mass;         // [H][K][K][smax] or nullptr
   double r0;
@@ -36,15 +40,17 @@ __device__ inline int tiles_of(int sj) {
   return (w * w + kCalibThreads - 1) / kCalibThreads;
 }
 
-// grid (max_tiles, K * K, H)
+// grid (max_tiles * splits, K * K, H)
 __global__ __launch_bounds__(kCalibThreads) void k_calib_mass(CalibArgs a) {
-  const int k = blockIdx.y / a.K, j = blockIdx.y % a.K, h = blockIdx.z, tile = blockIdx.x;
+  const int k = blockIdx.y / a.K, j = blockIdx.y % a.K, h = blockIdx.z;
+  const int tile = blockIdx.x % a.max_tiles, split = blockIdx.x / a.max_tiles;
   if (j > k) return;
   const int sk = a.s[k], sj = a.s[j];
   if (tile >= tiles_of(sj)) return;
   __shared__ short cen[kMaxSide];          // centre of query coordinate c in key scale j
   __shared__ double sum_of[kCalibThreads];
   __shared__ short dist_of[kCalibThreads];
+  __shared__ double sub_of[16][17];        // fold, first level: 16 distances x 16 runs of 16 threads
   for (int c = threadIdx.x; c < sk; c += kCalibThreads)
     cen[c] = (short)(((2 * c + 1) * sj) / (2 * sk));
   __syncthreads();
@@ -52,30 +58,58 @@ __global__ __launch_bounds__(kCalibThreads) void k_calib_mass(CalibArgs a) {
   const int w = 2 * sj - 1, o = tile * kCalibThreads + threadIdx.x;
   const bool live = o < w * w;
   const int oy = live ? o / w - (sj - 1) : 0, ox = live ? o % w - (sj - 1) : 0;
-  double acc = 0.0;
+  // Eight loads in flight per thread: every load is unconditional, from the key column
+  // clamped into the row (a value outside the row's keys is read and then not added), and
+  // feeds its own running sum; the order of the additions is fixed.
+  constexpr int U = 8;
+  double acc[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) acc[u] = 0.0;
   if (live) {
-    for (int n = 0; n < a.N; ++n) {
-      const float* base = a.p + ((int64_t)n * a.H + h) * a.L * a.L + (int64_t)a.off[k] * a.L + a.off[j];
-      for (int qy = 0; qy < sk; ++qy) {
-        const int ky = cen[qy] + oy;
-        if (ky < 0 || ky >= sj) continue;
-        const float* row = base + (int64_t)qy * sk * a.L + ky * sj;
-        for (int qx = 0; qx < sk; ++qx) {
-          const int kx = cen[qx] + ox;
-          if (kx >= 0 && kx < sj) acc += (double)row[(int64_t)qx * a.L + kx];
+    const float* part = a.p + (int64_t)h * a.L * a.L + (int64_t)a.off[k] * a.L + a.off[j];
+    for (int r = split; r < a.N * sk; r += a.splits) {     // (sample, query row) pairs of this split
+      const int n = r / sk, qy = r % sk;
+      const int ky = cen[qy] + oy;
+      if (ky < 0 || ky >= sj) continue;
+      const float* row = part + (int64_t)n * a.H * a.L * a.L + (int64_t)qy * sk * a.L + ky * sj;
+      for (int qx = 0; qx < sk; qx += U) {
+        float v[U];
+        bool in[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int q = min(qx + u, sk - 1);               // (past the last query: re-read it, not added)
+          const int kx = cen[q] + ox;
+          in[u] = qx + u < sk && kx >= 0 && kx < sj;
+          v[u] = row[(int64_t)q * a.L + min(max(kx, 0), sj - 1)];
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] += in[u] ? (double)v[u] : 0.0;
       }
     }
   }
-  sum_of[threadIdx.x] = acc;
+  double total = 0.0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) total += acc[u];
+  sum_of[threadIdx.x] = total;
   dist_of[threadIdx.x] = live ? (short)max(abs(oy), abs(ox)) : (short)-1;
   __syncthreads();
-  double* out = a.partial + ((((int64_t)h * a.K + k) * a.K + j) * a.max_tiles + tile) * a.smax;
-  for (int d = threadIdx.x; d < sj; d += kCalibThreads) {
+  double* out = a.partial +
+      (((((int64_t)h * a.K + k) * a.K + j) * a.splits + split) * a.max_tiles + tile) * a.smax;
+  // per-distance sums over the 256 threads, in a fixed order: 16 distances at a time, thread
+  // (d, c) adds run c (16 consecutive threads), then thread (d, 0) adds the 16 runs
+  const int dl = threadIdx.x >> 4, c = threadIdx.x & 15;
+  for (int d0 = 0; d0 < sj; d0 += 16) {
     double s = 0.0;
-    for (int i = 0; i < kCalibThreads; ++i)
-      if (dist_of[i] == d) s += sum_of[i];
-    out[d] = s;
+    for (int i = 16 * c; i < 16 * c + 16; ++i)
+      if (dist_of[i] == d0 + dl) s += sum_of[i];
+    sub_of[dl][c] = s;
+    __syncthreads();
+    if (c == 0 && d0 + dl < sj) {
+      double t = 0.0;
+      for (int i = 0; i < 16; ++i) t += sub_of[dl][i];
+      out[d0 + dl] = t;
+    }
+    __syncthreads();
   }
 }
 
@@ -91,10 +125,11 @@ __global__ __launch_bounds__(64) void k_calib_pick(CalibArgs a) {
   }
   const int sj = a.s[j], nt = tiles_of(sj);
   __shared__ double ring[kMaxSide];          // values at distance exactly d
-  const double* in = a.partial + part * a.max_tiles * a.smax;
+  const double* in = a.partial + part * a.splits * a.max_tiles * a.smax;
   for (int d = threadIdx.x; d < sj; d += 64) {
     double s = 0.0;
-    for (int t = 0; t < nt; ++t) s += in[(int64_t)t * a.smax + d];
+    for (int sp = 0; sp < a.splits; ++sp)
+      for (int t = 0; t < nt; ++t) s += in[((int64_t)sp * a.max_tiles + t) * a.smax + d];
     ring[d] = s;
   }
   __syncthreads();
@@ -127,11 +162,12 @@ litevar_status calib_geom(const int32_t* scales, int32_t K, CalibArgs& a) {
   a.off[K] = (int)a.L;
   const int w = 2 * a.smax - 1;
   a.max_tiles = (w * w + kCalibThreads - 1) / kCalibThreads;
+  a.splits = 64 / a.max_tiles < 1 ? 1 : (64 / a.max_tiles > 4 ? 4 : 64 / a.max_tiles);
   return LITEVAR_OK;
 }
 
 size_t calib_workspace(const CalibArgs& a, int H) {
-  return (size_t)H * a.K * a.K * a.max_tiles * a.smax * sizeof(double);
+  return (size_t)H * a.K * a.K * a.splits * a.max_tiles * a.smax * sizeof(double);
 }
 
 }  // namespace
@@ -172,7 +208,7 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
   a.N = N; a.H = H; a.p = d_attn; a.partial = (double*)d_workspace;
   a.radius = d_radius; a.mass = d_mass; a.r0 = (double)r0;
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(k_calib_mass, dim3(a.max_tiles, a.K * a.K, H), dim3(kCalibThreads), 0, st, a);
+  hipLaunchKernelGGL(k_calib_mass, dim3(a.max_tiles * a.splits, a.K * a.K, H), dim3(kCalibThreads), 0, st, a);
   if (litevar_status s = hip_check(hipGetLastError(), "calibration mass launch")) return s;
   hipLaunchKernelGGL(k_calib_pick, dim3(a.K * a.K, H), dim3(64), 0, st, a);
   return hip_check(hipGetLastError(), "calibration pick launch");

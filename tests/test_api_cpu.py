@@ -151,8 +151,8 @@ def test_calibrate_validation_needs_no_gpu(lv):
     sc = (C.c_int32 * 3)(1, 2, 3)
     n = C.c_size_t(0)
     assert lib.litevar_window_calibrate_workspace_bytes(sc, 3, 2, C.byref(n)) == 0
-    # [H][K][K][tiles][smax] doubles: side 3 -> 25 offsets -> one tile of 256
-    assert n.value == 2 * 3 * 3 * 1 * 3 * 8
+    # [H][K][K][splits][tiles][smax] doubles: side 3 -> 25 offsets -> one tile of 256, 16 splits
+    assert n.value == 2 * 3 * 3 * 4 * 1 * 3 * 8
     assert lib.litevar_window_calibrate_workspace_bytes(sc, 3, 0, C.byref(n)) == -1
     assert lib.litevar_window_calibrate_workspace_bytes(None, 3, 2, C.byref(n)) == -1
     bad = (C.c_int32 * 2)(4, 0)
