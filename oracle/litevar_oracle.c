@@ -81,13 +81,16 @@ int lvo_token_coords(int32_t K, const int32_t* scales, int64_t t,
   return LVO_BAD_ARG;
 }
 
-/* The predicate, on coordinates.  radii[j] < 0 means "no window in part j". */
-static int allowed_coords(const int32_t* scales, const int32_t* radii,
+/* The predicate, on coordinates.  radii is a [K][K] table: radii[k*K + j] is the
+ * radius of part j of query scale k's attention map (Section 2, step (3): the
+ * window size is determined for each scale and part); < 0 means "no window in
+ * that part". */
+static int allowed_coords(int32_t K, const int32_t* scales, const int32_t* radii,
                           int32_t n_sink, int32_t qk, int32_t qy, int32_t qx,
                           int32_t kj, int32_t ky, int32_t kx) {
   if (kj > qk) return 0;                 /* block-causal across scales */
   if (kj < n_sink) return 1;             /* leading parts kept dense */
-  int32_t r = radii[kj];
+  int32_t r = radii[(int64_t)qk * K + kj];
   if (r < 0) return 1;                   /* dense part */
   int64_t sj = scales[kj], sk = scales[qk];
   int64_t cy = ((2 * (int64_t)qy + 1) * sj) / (2 * sk);
@@ -104,7 +107,7 @@ int lvo_allowed(int32_t K, const int32_t* scales, const int32_t* radii,
   int32_t qk, qy, qx, kj, ky, kx;
   if (lvo_token_coords(K, scales, tq, &qk, &qy, &qx) != LVO_OK) return LVO_BAD_ARG;
   if (lvo_token_coords(K, scales, tk, &kj, &ky, &kx) != LVO_OK) return LVO_BAD_ARG;
-  return allowed_coords(scales, radii, n_sink, qk, qy, qx, kj, ky, kx);
+  return allowed_coords(K, scales, radii, n_sink, qk, qy, qx, kj, ky, kx);
 }
 
 typedef struct { int32_t k, y, x; } coord_t;
@@ -139,7 +142,7 @@ int lvo_mask_dense(int32_t K, const int32_t* scales, const int32_t* radii,
   for (int64_t q = q0; q < q1; ++q)
     for (int64_t t = 0; t < L; ++t)
       mask[(q - q0) * L + t] = (uint8_t)allowed_coords(
-          scales, radii, n_sink, c[q].k, c[q].y, c[q].x, c[t].k, c[t].y, c[t].x);
+          K, scales, radii, n_sink, c[q].k, c[q].y, c[q].x, c[t].k, c[t].y, c[t].x);
   free(c);
   return LVO_OK;
 }
@@ -156,7 +159,7 @@ int lvo_row_counts(int32_t K, const int32_t* scales, const int32_t* radii,
   for (int64_t q = q0; q < q1; ++q) {
     int64_t n = 0;
     for (int64_t t = 0; t < L; ++t)
-      n += allowed_coords(scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
+      n += allowed_coords(K, scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
                           c[t].k, c[t].y, c[t].x);
     counts[q - q0] = n;
   }
@@ -180,7 +183,7 @@ int lvo_index_sets(int32_t K, const int32_t* scales, const int32_t* radii,
   for (int64_t q = q0; q < q1; ++q) {
     int64_t w = rowptr[q - q0];
     for (int64_t t = 0; t < L; ++t)
-      if (allowed_coords(scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
+      if (allowed_coords(K, scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
                          c[t].k, c[t].y, c[t].x)) {
         if (w < rowptr[q - q0 + 1]) cols[w] = (int32_t)t;
         ++w;
@@ -211,13 +214,13 @@ static double load_elem(const void* p, int32_t dtype, int64_t i) {
  * maximum, exponentiate, normalise, weight V.  probs (optional, length L)
  * receives the normalised weights, 0 for masked keys.
  */
-static int attn_row(const int32_t* scales, const int32_t* radii, int32_t n_sink,
+static int attn_row(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
                     const coord_t* c, int64_t L, int64_t tq,
                     const double* qrow, const double* Kd, const double* Vd,
                     int32_t D, double sm_scale, double* z, double* out, double* probs) {
   double m = -INFINITY;
   for (int64_t t = 0; t < L; ++t) {
-    if (!allowed_coords(scales, radii, n_sink, c[tq].k, c[tq].y, c[tq].x,
+    if (!allowed_coords(K, scales, radii, n_sink, c[tq].k, c[tq].y, c[tq].x,
                         c[t].k, c[t].y, c[t].x)) { z[t] = NAN; continue; }
     double s = 0.0;
     for (int32_t d = 0; d < D; ++d) s += qrow[d] * Kd[t * D + d];
@@ -284,7 +287,7 @@ int lvo_attn(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_s
           int64_t ql = rows ? rows[r] : r;
           for (int32_t d = 0; d < D; ++d)
             qrow[d] = load_elem(q, dtype, (bh * Lq + ql) * D + d);
-          attn_row(scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
+          attn_row(K, scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
                    z, out + (bh * n_rows + r) * D, NULL);
         }
       }
@@ -318,7 +321,7 @@ int lvo_attn_probs(int32_t K, const int32_t* scales, const int32_t* radii, int32
       Vd[i] = load_elem(v, dtype, bh * L * D + i);
     }
     for (int32_t d = 0; d < D; ++d) qrow[d] = load_elem(q, dtype, (bh * Lq + ql) * D + d);
-    rc = attn_row(scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
+    rc = attn_row(K, scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
                   z, out_row, probs);
   }
   free(c); free(Kd); free(Vd); free(z); free(qrow);
@@ -369,7 +372,7 @@ int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, 
   if (K < 1 || !scales || !p || !radius || N < 1 || H < 1) return LVO_BAD_ARG;
   for (int32_t k = 0; k < K; ++k) if (scales[k] < 1 || scales[k] > smax) return LVO_BAD_ARG;
   const int64_t L = lvo_seq_len(K, scales);
-  int32_t* rad = (int32_t*)malloc((size_t)K * sizeof(int32_t));
+  int32_t* rad = (int32_t*)malloc((size_t)K * K * sizeof(int32_t));
   if (!rad) return LVO_NO_MEM;
   for (int32_t h = 0; h < H; ++h)
     for (int32_t k = 0; k < K; ++k)
@@ -382,7 +385,7 @@ int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, 
         const int32_t sk = scales[k], sj = scales[j];
         int32_t found = -1;
         for (int32_t r = 0; r < smax; ++r) {          /* the window grows from zero */
-          for (int32_t i = 0; i < K; ++i) rad[i] = r;
+          for (int32_t i = 0; i < K * K; ++i) rad[i] = r;
           double in = 0.0, all = 0.0;
           for (int32_t n = 0; n < N; ++n)
             for (int32_t qy = 0; qy < sk; ++qy)
@@ -392,7 +395,7 @@ int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, 
                     const int64_t q = oq + (int64_t)qy * sk + qx, t = ok + (int64_t)ky * sj + kx;
                     const double v = p[(((int64_t)n * H + h) * L + q) * L + t];
                     all += v;
-                    if (allowed_coords(scales, rad, 0, k, qy, qx, j, ky, kx)) in += v;
+                    if (allowed_coords(K, scales, rad, 0, k, qy, qx, j, ky, kx)) in += v;
                   }
           if (mout) mout[r] = in;
           if (found < 0 && (all == 0.0 || in / all >= r0)) found = r;

@@ -31,6 +31,18 @@ def _p(a):
     return a.ctypes.data_as(C.c_void_p)
 
 
+def _rtab(scales, radii):
+    """The C side's [K][K] radius table ([query scale][key scale]) from either one radius
+    per key scale (the same for every query scale) or a full table."""
+    K = len(scales)
+    r = np.asarray(radii, dtype=np.int32)
+    if r.ndim == 1:
+        assert r.shape == (K,)
+        r = np.tile(r, (K, 1))
+    assert r.shape == (K, K)
+    return np.ascontiguousarray(r)
+
+
 def expand_radii(scales, radius, radius_per_key_scale=None):
     """One radius per key scale; a negative radius means a dense part."""
     K = len(scales)
@@ -63,7 +75,7 @@ def token_coords(scales, t):
 
 
 def allowed(scales, radii, n_sink, tq, tk):
-    s, r = _i32(scales), _i32(radii)
+    s, r = _i32(scales), _rtab(scales, radii)
     rc = _L().lvo_allowed(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
                           C.c_int64(tq), C.c_int64(tk))
     if rc < 0:
@@ -79,7 +91,7 @@ def _qrange(scales, q_scales):
 
 
 def mask_dense(scales, radii, n_sink=0, q_scales=None):
-    s, r = _i32(scales), _i32(radii)
+    s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     m = np.empty((Lq, seq_len(scales)), dtype=np.uint8)
     rc = _L().lvo_mask_dense(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
@@ -90,7 +102,7 @@ def mask_dense(scales, radii, n_sink=0, q_scales=None):
 
 
 def row_counts(scales, radii, n_sink=0, q_scales=None):
-    s, r = _i32(scales), _i32(radii)
+    s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     cnt = np.empty(Lq, dtype=np.int64)
     rc = _L().lvo_row_counts(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
@@ -102,7 +114,7 @@ def row_counts(scales, radii, n_sink=0, q_scales=None):
 
 def index_sets(scales, radii, n_sink=0, q_scales=None):
     """(rowptr[Lq+1] int64, cols int32): ascending allowed keys of every query."""
-    s, r = _i32(scales), _i32(radii)
+    s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     cnt = row_counts(scales, radii, n_sink, q_scales)
     rowptr = np.zeros(Lq + 1, dtype=np.int64)
@@ -129,7 +141,7 @@ def _dtype_code(a):
 def attn(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, rows=None,
          bh_range=None):
     """fp64 windowed attention.  q [B,H,Lq,D]; k,v [B,H,L,D]; returns [B,H,n_rows,D]."""
-    s, r = _i32(scales), _i32(radii)
+    s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
     code = _dtype_code(q)
@@ -156,7 +168,7 @@ def attn(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, rows=None,
 
 def attn_probs(scales, radii, q, k, v, sm_scale, bh, ql, n_sink=0, q_scales=None):
     """(probs[L], out[D]) of one (b*H+h, local query) pair, fp64."""
-    s, r = _i32(scales), _i32(radii)
+    s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
     code = _dtype_code(q)

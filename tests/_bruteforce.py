@@ -34,11 +34,13 @@ def dense_mask(scales, radii, n_sink=0, q_scales=None):
         for t, (j, yy, xx) in enumerate(toks):
             if j > k:
                 continue
-            if j < n_sink or radii[j] < 0:
+            # one radius per key scale, or a table [query scale][key scale]
+            rad = radii[k][j] if hasattr(radii[0], "__len__") else radii[j]
+            if j < n_sink or rad < 0:
                 m[r, t] = True
                 continue
             cy, cx = centre(y, scales[k], scales[j]), centre(x, scales[k], scales[j])
-            m[r, t] = max(abs(yy - cy), abs(xx - cx)) <= radii[j]
+            m[r, t] = max(abs(yy - cy), abs(xx - cx)) <= rad
     return m
 
 

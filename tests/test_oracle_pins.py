@@ -179,6 +179,50 @@ def test_bruteforce_random_scale_lists(scales, radius, n_sink, D, seed, kv_step)
         np.testing.assert_allclose(got[b, 0], ref, rtol=0, atol=1e-11)
 
 
+# ---- one radius per (query scale, part) (Section 2, step (3)) ------------------------
+
+def test_pair_radii_hand_derived():
+    """Scales (1,2,3,4): query scale 3 (side 4) keeps radius 0 in part 2 (side 3) and radius 1
+    in its own part; query scale 2 (side 3) keeps radius 1 in part 1.  Counted by hand from the
+    worked example's centres (side 4 -> side 3: 0,1,1,2): radius 0 keeps one key per query."""
+    scales = (1, 2, 3, 4)
+    tab = [[5, 5, 5, 5], [5, 5, 5, 5], [5, 1, 5, 5], [5, 5, 0, 1]]
+    m = oracle.mask_dense(scales, tab).astype(bool)
+    off = (0, 1, 5, 14, 30)
+    blk = lambda k, j: m[off[k]:off[k + 1], off[j]:off[j + 1]]
+    assert blk(3, 2).sum() == 16 and (blk(3, 2).sum(axis=1) == 1).all()
+    centre = (0, 1, 1, 2)
+    for qy in range(4):
+        for qx in range(4):
+            assert blk(3, 2)[qy * 4 + qx, centre[qy] * 3 + centre[qx]]
+    # same-scale part of side 4 at radius 1: (2 + 3 + 3 + 2)^2 kept pairs
+    assert blk(3, 3).sum() == 100
+    # side 3 -> side 2 centres 0,1,1 at radius 1 cover both cells: the part is full
+    assert blk(2, 1).all()
+    # radius 5 everywhere else: full parts; nothing above the diagonal
+    assert blk(3, 1).all() and blk(3, 0).all() and blk(2, 2).all() and not blk(2, 3).any()
+
+
+@settings(max_examples=25, deadline=None)
+@given(scales=st.lists(st.integers(1, 6), min_size=1, max_size=4), n_sink=st.integers(0, 2),
+       seed=st.integers(0, 2 ** 16), kv_step=st.booleans())
+def test_bruteforce_pair_radii(scales, n_sink, seed, kv_step):
+    K = len(scales)
+    rng = np.random.default_rng(seed)
+    tab = rng.integers(-1, 4, size=(K, K)).tolist()
+    q_scales = (K - 1, K) if kv_step else None
+    mask = dense_mask(scales, tab, n_sink, q_scales)
+    assert (oracle.mask_dense(scales, tab, n_sink, q_scales).astype(bool) == mask).all()
+    L, Lq = mask.shape[1], mask.shape[0]
+    q, k, v = (rng.standard_normal((1, 1, n, 8)) for n in (Lq, L, L))
+    got = oracle.attn(scales, tab, q, k, v, 0.5, n_sink, q_scales)
+    ref, _ = masked_attention(q[0, 0], k[0, 0], v[0, 0], mask, 0.5)
+    np.testing.assert_allclose(got[0, 0], ref, rtol=0, atol=1e-11)
+    # a table whose rows are equal is the per-key-scale case
+    per = rng.integers(-1, 4, size=K).tolist()
+    assert (oracle.mask_dense(scales, [per] * K, n_sink) == oracle.mask_dense(scales, per, n_sink)).all()
+
+
 # ---- invariants -------------------------------------------------------------------
 
 def _small_case(seed=7, scales=(1, 2, 3, 4, 6), B=2, H=3, D=16):
