@@ -66,6 +66,11 @@ typedef struct litevar_mask_desc {
   int32_t n_sink_scales;               /* leading key scales kept dense, 0..K (paper: 3) */
   int32_t q_scale_begin, q_scale_end;  /* query scales [begin, end): whole sequence = [0, K),
                                           last KV-cache step = [K-1, K) */
+  const int32_t* radius_per_scale_pair; /* optional [K][K], [query scale][key scale] (Section 2:
+                                          one window size per scale and part, e.g. from
+                                          litevar_window_calibrate); overrides both radius
+                                          fields when non-NULL; entries with key scale > query
+                                          scale are ignored */
 } litevar_mask_desc;
 
 /*
@@ -97,7 +102,7 @@ typedef struct litevar_plan {
   int64_t computed_pairs;   /* 16 * 32 * n_steps: pairs the MFMA tiles cover */
   uint64_t off[12];         /* byte offsets of the blob's sections (private) */
   int32_t scales[LITEVAR_MAX_SCALES];
-  int32_t radii[LITEVAR_MAX_SCALES];
+  int32_t radii[LITEVAR_MAX_SCALES];   /* per key scale: the widest radius over the plan's query scales */
   int32_t n_sink_scales;
 } litevar_plan;
 

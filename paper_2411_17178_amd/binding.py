@@ -27,7 +27,7 @@ class _MaskDesc(C.Structure):
     _fields_ = [("n_scales", C.c_int32), ("scales", C.POINTER(C.c_int32)),
                 ("radius", C.c_int32), ("radius_per_key_scale", C.POINTER(C.c_int32)),
                 ("n_sink_scales", C.c_int32), ("q_scale_begin", C.c_int32),
-                ("q_scale_end", C.c_int32)]
+                ("q_scale_end", C.c_int32), ("radius_per_scale_pair", C.POINTER(C.c_int32))]
 
 
 class _PlanOpts(C.Structure):
@@ -88,12 +88,20 @@ def _stream_handle(stream):
 def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
     K = len(scales)
     sc = (C.c_int32 * K)(*[int(s) for s in scales])
-    rp = None
+    # radius_per_key_scale: [K] (one radius per key scale) or a table [K][K]
+    # ([query scale][key scale], one window size per scale and part)
+    rp = pair = None
     if radius_per_key_scale is not None:
-        rp = (C.c_int32 * len(radius_per_key_scale))(*[int(r) for r in radius_per_key_scale])
+        rows = list(radius_per_key_scale)
+        if len(rows) and hasattr(rows[0], "__len__"):
+            assert len(rows) == K and all(len(r) == K for r in rows), "radius table must be [K][K]"
+            pair = (C.c_int32 * (K * K))(*[int(r) for row in rows for r in row])
+        else:
+            assert len(rows) == K, "one radius per key scale"
+            rp = (C.c_int32 * K)(*[int(r) for r in rows])
     qb, qe = (0, K) if q_scales is None else q_scales
-    d = _MaskDesc(K, sc, int(radius), rp, int(n_sink_scales), int(qb), int(qe))
-    d._keep = (sc, rp)
+    d = _MaskDesc(K, sc, int(radius), rp, int(n_sink_scales), int(qb), int(qe), pair)
+    d._keep = (sc, rp, pair)
     return d
 
 

@@ -81,7 +81,14 @@ static void fill_handle(const Geom& g, const PlanSizes& z, litevar_plan* plan) {
   plan->retained_pairs = z.retained_pairs;
   plan->computed_pairs = z.n_steps * 16 * kStepKeys;
   for (int i = 0; i < kNumSections; ++i) plan->off[i] = z.off[i];
-  for (int k = 0; k < g.K; ++k) { plan->scales[k] = g.s[k]; plan->radii[k] = g.rad[k]; }
+  for (int k = 0; k < g.K; ++k) {
+    plan->scales[k] = g.s[k];
+    // widest window of key scale k over the plan's query scales (-1 if one of them is dense)
+    int r = 0;
+    for (int q = (g.qb > k ? g.qb : k); q < g.qe; ++q)
+      r = (r < 0 || g.rad[q][k] < 0) ? -1 : (g.rad[q][k] > r ? g.rad[q][k] : r);
+    plan->radii[k] = r;
+  }
   plan->n_sink_scales = g.n_sink;
 }
 

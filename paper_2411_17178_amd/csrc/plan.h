@@ -40,7 +40,8 @@ struct Geom {
   int n_groups, n_patches;
   int s[kMaxScales];
   int off[kMaxScales + 1];
-  int rad[kMaxScales];          // < 0: dense part
+  short rad[kMaxScales][kMaxScales];   // [query scale][key scale] (Section 2, step (3): one
+                                       // window size per scale and part); < 0: dense part
   int grp_off[kMaxScales + 1];  // groups are ordered by DESCENDING query scale:
                                 // slot i holds scale qe-1-i; grp_off is its prefix sum
 };
@@ -97,12 +98,13 @@ struct Interval { int lo, hi; };   // empty when hi < lo
 LV_HD Interval win_interval(const Geom& g, int k, int j, int c) {
   const int sj = g.s[j];
   Interval iv;
-  if (j < g.n_sink || g.rad[j] < 0) { iv.lo = 0; iv.hi = sj - 1; return iv; }
+  const int rad = g.rad[k][j];
+  if (j < g.n_sink || rad < 0) { iv.lo = 0; iv.hi = sj - 1; return iv; }
   // (sides are at most kMaxSide = 1024, so the product fits 32 bits: a 64-bit division would
   // cost an order of magnitude more on the device)
   const int ctr = (int)((unsigned)((2 * c + 1) * sj) / (unsigned)(2 * g.s[k]));
-  iv.lo = ctr - g.rad[j] < 0 ? 0 : ctr - g.rad[j];
-  iv.hi = ctr + g.rad[j] > sj - 1 ? sj - 1 : ctr + g.rad[j];
+  iv.lo = ctr - rad < 0 ? 0 : ctr - rad;
+  iv.hi = ctr + rad > sj - 1 ? sj - 1 : ctr + rad;
   return iv;
 }
 

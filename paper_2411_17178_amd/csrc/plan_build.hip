@@ -44,12 +44,14 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
     if (s > g.smax) g.smax = s;
   }
   g.off[g.K] = (int)L; g.L = (int)L;
-  for (int k = 0; k < g.K; ++k) {
-    const int r = d->radius_per_key_scale ? d->radius_per_key_scale[k] : d->radius;
-    if (r < LITEVAR_RADIUS_DENSE)
-      return fail(LITEVAR_E_INVALID_ARG, "radius %d of key scale %d is below -1", r, k);
-    g.rad[k] = r > kMaxSide ? kMaxSide : r;
-  }
+  for (int k = 0; k < g.K; ++k)
+    for (int j = 0; j < g.K; ++j) {
+      const int r = d->radius_per_scale_pair ? d->radius_per_scale_pair[k * g.K + j]
+                  : d->radius_per_key_scale ? d->radius_per_key_scale[j] : d->radius;
+      if (r < LITEVAR_RADIUS_DENSE)
+        return fail(LITEVAR_E_INVALID_ARG, "radius %d of key scale %d (query scale %d) is below -1", r, j, k);
+      g.rad[k][j] = (short)(r > kMaxSide ? kMaxSide : r);
+    }
   if (d->n_sink_scales < 0 || d->n_sink_scales > g.K)
     return fail(LITEVAR_E_INVALID_ARG, "n_sink_scales %d outside 0..%d", d->n_sink_scales, g.K);
   g.n_sink = d->n_sink_scales;

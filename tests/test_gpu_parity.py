@@ -367,3 +367,49 @@ def test_repeat_launch_is_deterministic(lv):
     a = _gpu_attn(lv, plan, q, k, v, w.sm_scale)
     b = _gpu_attn(lv, plan, q, k, v, w.sm_scale)
     assert torch.equal(a, b)
+
+
+# ---- one radius per (query scale, part) (Section 2, step (3)) ------------------------
+
+PAIR_CASES = [
+    ((1, 2, 3, 4), 0, None),
+    ((1, 2, 3, 5, 7, 10), 1, None),
+    ((1, 2, 3, 4, 5, 6, 8, 10, 13, 16), 3, None),
+    ((1, 2, 3, 4, 5, 6, 8, 10, 13, 16), 0, (9, 10)),     # the KV-cache step
+    ((7, 2, 9, 4, 17), 0, (2, 5)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(PAIR_CASES)))
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_pair_radius_tables(lv, case, waves):
+    """masks bit-exact and attention within tolerance when every (query scale, key scale)
+    part has its own radius (some of them dense)"""
+    scales, n_sink, q_scales = PAIR_CASES[case]
+    K = len(scales)
+    rng = np.random.default_rng(500 + case)
+    tab = rng.integers(-1, 5, size=(K, K)).tolist()
+    print(f"  pair radii: scales={scales} waves={waves} q_scales={q_scales}", flush=True)
+    plan = lv.litevar_mask_build(scales, 0, tab, n_sink, q_scales, waves_per_group=waves)
+    lv.litevar_plan_check(plan)
+    mask, _ = lv.litevar_mask_export_dense(plan)
+    want = oracle.mask_dense(scales, tab, n_sink, q_scales)
+    assert np.array_equal(mask.cpu().numpy(), want)
+    assert plan.retained_pairs == int(want.sum())
+    for dtype in ("bf16", "f32"):
+        q, k, v = _rand_case(scales, 1, 2, dtype, 900 + case, q_scales)
+        o = _gpu_attn(lv, plan, q, k, v, 0.125)
+        ref = _oracle_attn(scales, tab, q, k, v, 0.125, n_sink, q_scales)
+        assert _maxerr(o, ref) <= TOL[dtype]
+
+
+def test_calibrated_table_feeds_the_plan(lv):
+    """calibration -> radius table of one head -> plan: the plan's mask is the oracle's mask
+    of that table"""
+    scales = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+    p = workloads.make_attn_map(scales, 1, 2, 19).cuda()
+    rad = lv.litevar_window_calibrate(scales, p, 0.9).cpu().numpy()
+    tab = np.maximum(rad[1], 0).tolist()          # head 1; the unused upper triangle as radius 0
+    plan = lv.litevar_mask_build(scales, 0, tab, 3)
+    mask, _ = lv.litevar_mask_export_dense(plan)
+    assert np.array_equal(mask.cpu().numpy(), oracle.mask_dense(scales, tab, 3))
