@@ -9,9 +9,10 @@
 // (query, centre + offset) where that key exists: consecutive lanes own consecutive ox, so a
 // wave reads runs of consecutive keys of one map row; every value of the map is added exactly
 // once per launch, by exactly one thread, in a fixed order in fp64 (no atomics: two launches
-// give identical bits).  (Copying the reachable key rows to LDS with coalesced loads and
-// picking from there was measured: its two barriers per batch of queries make it 2.4 times
-// slower than the direct loads.)  The (sample, query row) pairs of a part are dealt to
+// give identical bits).  (Measured alternatives, both slower: copying the reachable key rows
+// to LDS with coalesced loads and picking from there -- two barriers per batch of queries,
+// 2.4 times slower; one thread per key with a private LDS column of per-distance sums --
+// fully coalesced loads, but a dependent LDS read-add-write per value, 2 times slower.)  The (sample, query row) pairs of a part are dealt to
 // `splits` workgroups per 256 offsets, so that small maps still fill the GPU.  A workgroup
 // folds its 256 offsets into per-distance sums (fixed order again) and writes them to the
 // workspace; a second, small kernel adds the workgroups of a part, forms the in-window sums
