@@ -413,3 +413,37 @@ def test_calibrated_table_feeds_the_plan(lv):
     plan = lv.litevar_mask_build(scales, 0, tab, 3)
     mask, _ = lv.litevar_mask_export_dense(plan)
     assert np.array_equal(mask.cpu().numpy(), oracle.mask_dense(scales, tab, 3))
+
+
+def test_random_configurations_sweep(lv):
+    """forty seeded random problems (scale lists in any order, per-part radii with dense
+    parts, dense leading scales, query-scale ranges, all three kernels): masks bit-exact,
+    index sets through the CSR export, attention within tolerance"""
+    rng = np.random.default_rng(20241127)
+    for it in range(40):
+        K = int(rng.integers(1, 7))
+        scales = [int(x) for x in rng.integers(1, 20, size=K)]
+        if it % 4 == 0:
+            scales = sorted(scales)
+        tab = rng.integers(-1, 6, size=(K, K)).tolist()
+        radii = tab if it % 2 else [int(x) for x in rng.integers(-1, 6, size=K)]
+        n_sink = int(rng.integers(0, K + 1)) if it % 3 == 0 else 0
+        qb = int(rng.integers(0, K))
+        q_scales = (qb, int(rng.integers(qb + 1, K + 1))) if it % 5 else None
+        waves = (4, 8, 16)[it % 3]
+        dtype = "bf16" if it % 2 == 0 else "f32"
+        print(f"  sweep {it}: scales={scales} radii={radii} n_sink={n_sink} q_scales={q_scales} "
+              f"waves={waves} {dtype}", flush=True)
+        plan = lv.litevar_mask_build(scales, 0, radii, n_sink, q_scales, waves_per_group=waves)
+        lv.litevar_plan_check(plan)
+        want = oracle.mask_dense(scales, radii, n_sink, q_scales)
+        mask, _ = lv.litevar_mask_export_dense(plan)
+        assert np.array_equal(mask.cpu().numpy(), want), it
+        rowptr, cols = lv.litevar_mask_export_csr(plan)
+        rp = rowptr.cpu().numpy()
+        assert np.array_equal(np.diff(rp), want.sum(axis=1)), it
+        assert np.array_equal(cols.cpu().numpy(), np.nonzero(want)[1]), it
+        q, k, v = _rand_case(scales, 1, 2, dtype, 3000 + it, q_scales)
+        o = _gpu_attn(lv, plan, q, k, v, 0.125)
+        ref = _oracle_attn(scales, radii, q, k, v, 0.125, n_sink, q_scales)
+        assert _maxerr(o, ref) <= TOL[dtype], it
