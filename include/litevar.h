@@ -11,8 +11,9 @@
  *     the conditional rows' attention output.
  * Window geometry (the paper's figure is its only definition): query (k, y, x)
  * keeps key (j, y', x') of scale j <= k iff j < n_sink_scales, or
- * |y' - cy| <= r_j and |x' - cx| <= r_j with cy = floor((2y+1) s_j / (2 s_k)),
- * cx likewise.  Tokens of a scale are stored row-major.  Masking precedes the
+ * |y' - cy| <= r and |x' - cx| <= r with cy = floor((2y+1) s_j / (2 s_k)),
+ * cx likewise, and r the radius of part j (one per key scale, or one per
+ * (query scale, key scale): Section 2 determines it for each scale and part).  Tokens of a scale are stored row-major.  Masking precedes the
  * softmax, so the kept weights sum to 1.
  *
  * Conventions
