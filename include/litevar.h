@@ -105,6 +105,7 @@ typedef struct litevar_plan {
   int32_t scales[LITEVAR_MAX_SCALES];
   int32_t radii[LITEVAR_MAX_SCALES];   /* per key scale: the widest radius over the plan's query scales */
   int32_t n_sink_scales;
+  int32_t patches_per_wave; /* 16 patches per group only: 0 = chosen per launch, else 1 or 2 */
 } litevar_plan;
 
 /* Tuning knobs of the plan; zero-initialise for the defaults. */
@@ -116,7 +117,11 @@ typedef struct litevar_plan_opts {
                                Supported (chunk, prefetch, spare) for 4 and 8 patches per group:
                                (32,2,2) and (64,2,1).  16 patches per group take (128,2,0) only:
                                phases of 128 keys, ring and prefetch depth counted in 64-key chunks */
-  int32_t reserved[4];
+  int32_t patches_per_wave; /* 16 patches per group only: 0 = choose at each launch (one patch per
+                               wave, sixteen waves per workgroup, when the launch has no more
+                               working workgroups than the GPU has CUs; else two patches per wave,
+                               eight waves), else 1 or 2 */
+  int32_t reserved[3];
 } litevar_plan_opts;
 
 /*

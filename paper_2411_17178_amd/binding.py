@@ -33,7 +33,7 @@ class _MaskDesc(C.Structure):
 class _PlanOpts(C.Structure):
     _fields_ = [("waves_per_group", C.c_int32), ("chunk_keys", C.c_int32),
                 ("prefetch_chunks", C.c_int32), ("spare_chunks", C.c_int32),
-                ("reserved", C.c_int32 * 4)]
+                ("patches_per_wave", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 class _Plan(C.Structure):
@@ -46,7 +46,8 @@ class _Plan(C.Structure):
                 ("n_steps", C.c_int64), ("n_union_keys", C.c_int64),
                 ("retained_pairs", C.c_int64), ("computed_pairs", C.c_int64),
                 ("off", C.c_uint64 * 12), ("scales", C.c_int32 * MAX_SCALES),
-                ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32)]
+                ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32),
+                ("patches_per_wave", C.c_int32)]
 
 
 def lib_path():
@@ -106,14 +107,15 @@ def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
 
 
 def _make_opts(waves_per_group):
-    """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks, spare_chunks);
-    0 (spare: -1) = library default."""
+    """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks, spare_chunks,
+    patches_per_wave); 0 (spare: -1) = library default."""
     o = _PlanOpts()
     o.spare_chunks = -1
     if isinstance(waves_per_group, (tuple, list)):
         vals = [int(x) for x in waves_per_group] + [0, 0, -1]
         o.waves_per_group, o.chunk_keys, o.prefetch_chunks = vals[0], vals[1], vals[2]
         o.spare_chunks = vals[3] if len(waves_per_group) > 3 else -1
+        o.patches_per_wave = vals[4] if len(waves_per_group) > 4 else 0
     else:
         o.waves_per_group = int(waves_per_group)
     return o

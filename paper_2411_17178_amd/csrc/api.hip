@@ -67,8 +67,15 @@ litevar_status litevar_mask_plan_bytes(const litevar_mask_desc* desc, const lite
   return LITEVAR_OK;
 }
 
-static void fill_handle(const Geom& g, const PlanSizes& z, litevar_plan* plan) {
+static litevar_status check_patches_per_wave(const litevar_plan_opts* opts) {
+  const int pw = opts ? opts->patches_per_wave : 0;
+  if (pw < 0 || pw > 2) return fail(LITEVAR_E_INVALID_ARG, "patches_per_wave must be 0, 1 or 2 (got %d)", pw);
+  return LITEVAR_OK;
+}
+
+static void fill_handle(const Geom& g, const PlanSizes& z, const litevar_plan_opts* opts, litevar_plan* plan) {
   memset(plan, 0, sizeof *plan);
+  plan->patches_per_wave = (opts && g.NW == 16) ? opts->patches_per_wave : 0;
   plan->blob_bytes = z.bytes;
   plan->n_scales = g.K;
   plan->q_scale_begin = g.qb; plan->q_scale_end = g.qe;
@@ -101,7 +108,8 @@ litevar_status litevar_mask_plan_stats(const litevar_mask_desc* desc, const lite
   PlanSizes z;
   rc = size_plan(g, z);
   if (rc) return rc;
-  fill_handle(g, z, stats);
+  if (litevar_status s = check_patches_per_wave(opts)) return s;
+  fill_handle(g, z, opts, stats);
   return LITEVAR_OK;
 }
 
@@ -120,9 +128,10 @@ litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_p
   if (blob_bytes < z.bytes)
     return fail(LITEVAR_E_PLAN_TOO_SMALL, "plan needs %llu bytes, buffer has %llu",
                 (unsigned long long)z.bytes, (unsigned long long)blob_bytes);
+  if (litevar_status s = check_patches_per_wave(opts)) return s;
   rc = build_plan(g, z, d_blob, (hipStream_t)stream);
   if (rc) return rc;
-  fill_handle(g, z, plan);
+  fill_handle(g, z, opts, plan);
   plan->magic = kMagic;
   plan->d_blob = d_blob;
   return LITEVAR_OK;

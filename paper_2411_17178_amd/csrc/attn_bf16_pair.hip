@@ -66,7 +66,7 @@ namespace lv {
 
 namespace {
 
-constexpr int kPairWaves = 8;         // waves per workgroup
+constexpr int kGroupPatches = 16;     // query patches per workgroup
 constexpr int kDmaKeys = 64;          // keys per chunk (the unit of loading and of ring slot reuse)
 constexpr int kRingChunks = 5;        // ring depth: look-back, two current, two landing
 constexpr int kBufferFlags = 0x00020000;   // word 3 of a raw buffer resource on gfx9: 32-bit data format
@@ -123,8 +123,14 @@ struct PatchState {       // one query patch of a wave
 
 }  // namespace
 
-__global__ __launch_bounds__(kPairWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
+// PW = query patches per wave: 2 (8 waves per workgroup, two workgroups per CU: the form for
+// launches that fill the GPU) or 1 (16 waves per workgroup, one workgroup per CU: a launch with
+// no more workgroups than CUs then still has four waves on every SIMD).  Same plan, same
+// phases; with 16 waves the loading duty of a chunk is one K or one V transfer per wave.
+template <int PW>
+__global__ __launch_bounds__((kGroupPatches / PW) * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void k_attn_bf16_pair(AttnArgs a, float c) {
+  [[maybe_unused]] constexpr int NWV = kGroupPatches / PW;   // waves per workgroup
   constexpr int C = kDmaKeys;
   constexpr int R = kRingChunks * C;               // ring slots
   constexpr int VOFF = R * kRingRowBytes;          // V ring follows the K ring
@@ -148,7 +154,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // one finishes a quarter later, alone on a CU that it cannot fill.  The later arrival (it
   // gets the higher wave slots of each SIMD) therefore runs at raised priority through its
   // first phases, which evens out the two finishing times.
-  const bool later_arrival = (__builtin_amdgcn_s_getreg(4 | (3 << 11)) & 0xf) >= 2;   // HW_ID.WAVE_ID
+  const bool later_arrival = PW == 2 && (__builtin_amdgcn_s_getreg(4 | (3 << 11)) & 0xf) >= 2;   // HW_ID.WAVE_ID
   if (later_arrival) __builtin_amdgcn_s_setprio(1);
 #ifdef LITEVAR_TIMELINE
   // experiment: delay the first (tune[0] = 1) or the later (2) workgroups of a CU by tune[1] x 64 cycles
@@ -164,24 +170,28 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int NC = __builtin_amdgcn_readfirstlane(gd.n_phases);   // chunks of the (padded) key list
   const int P = NC / 2 + 1;                                     // phases
 
-  // ---- loading duty: rows [8 wave, 8 wave + 8) of every chunk ----
+  // ---- loading duty: rows [8 w, 8 w + 8) of every chunk, w = wave mod 8: K and V rows with
+  // eight waves, K rows (waves 0-7) or V rows (waves 8-15) with sixteen ----
   const unsigned char* Kp = (const unsigned char*)((const __bf16*)a.k + b * a.ks[0] + h * a.ks[1]);
   const unsigned char* Vp = (const unsigned char*)((const __bf16*)a.v + b * a.ks[0] + h * a.ks[1]);
   const unsigned row_bytes = (unsigned)a.ks[2] * 2u;   // a (batch, head) slab spans < 2 GiB (checked by the API)
   const int32_t* utok = a.union_tok + gd.union_base;
   const int ident = __builtin_amdgcn_readfirstlane(gd.ident);   // union entries [0, ident) are token i at position i
-  const int row = 8 * wave + (lane >> 3);
+  const int row = 8 * (wave & 7) + (lane >> 3);
   // A lane's row of chunk t goes to slot (t % 5) * 64 + row.  Chunks start at multiples of 64
   // slots, so the slot's swizzle -- and with it the 16-byte piece of the source row that
   // this lane fetches -- does not depend on t.
   const unsigned piece_off = (((unsigned)lane & 7u) ^ ring_swizzle((unsigned)row)) << 4;
   static_assert((kDmaKeys & 63) == 0, "the swizzle folds slot bits 0..5 only");
   auto issue_chunk = [&](int t, int tok) {             // chunk t -> ring slots (t % 5) * 64 ...
-    const int slot0 = (t % kRingChunks) * C + 8 * wave;
+    const int slot0 = (t % kRingChunks) * C + 8 * (wave & 7);
     const unsigned src = __umul24((unsigned)tok, row_bytes) + piece_off;   // (both below 2^24, checked by the API)
-    __builtin_amdgcn_global_load_lds((global_void*)(Kp + src), (lds_void*)(Kring + slot0 * kRingRowBytes), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
+    if (PW == 2 || wave < 8)
+      __builtin_amdgcn_global_load_lds((global_void*)(Kp + src), (lds_void*)(Kring + slot0 * kRingRowBytes), 16, 0, 0);
+    if (PW == 2 || wave >= 8)
+      __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
   };
+  constexpr int kDmaPerChunk = PW;                       // transfers that a wave issues per chunk
   // (tokens and descriptors through buffer loads: a scalar resource and a scalar offset plus a
   // lane offset register, where a flat address costs 64-bit vector arithmetic per load)
   const __amdgpu_buffer_rsrc_t tok_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)utok, 0, NC * C * 4, kBufferFlags);
@@ -203,7 +213,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // vector memory operation: behind the burst of first chunks of all workgroups a scalar
   // miss would take microseconds, and the vector loads below depend on these values.
   // Patch descriptor words: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16}
-  const int pa = wave, pb_ = ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1);   // p and its partner two patch rows below, columns swapped
+  // (two patches per wave: p and its partner two patch rows below, columns swapped)
+  const int pa = wave, pb_ = PW == 2 ? ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1) : wave;
   const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp * 16 + pa), wB = (const_i32_ptr)(a.waves + grp * 16 + pb_);
   const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
   const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * NC);
@@ -214,8 +225,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int first_step = wF[0], n_group_steps = wL[0] + wL[1] - first_step;
   // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
   // phase p + 2 is fetched during phase p
-  int endA = peA[0], endB = peB[0];
-  int end1A = peA[last_chunk(1)], end1B = peB[last_chunk(1)];
+  // (one patch per wave: the second patch's counts are the constant 0 and its code goes away)
+  int endA = peA[0], endB = PW == 2 ? peB[0] : 0;
+  int end1A = peA[last_chunk(1)], end1B = PW == 2 ? peB[last_chunk(1)] : 0;
   asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.nx_kq),
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.nx_kq),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
@@ -262,7 +274,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   };
   PatchState A, B;
   init_patch(A, pwA);
-  init_patch(B, pwB);
+  if constexpr (PW == 2) init_patch(B, pwB);
 
   bf16x8 ones;
 #pragma unroll
@@ -285,7 +297,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       if (first + 1 + i < end) d[i] = load_desc(rsrc, first + 1 + i);
   };
   dA0 = load_desc(descA, 0);
-  dB0 = load_desc(descB, 0);
+  if constexpr (PW == 2) dB0 = load_desc(descB, 0);
   int tokn0 = load_tok(3), tokn1 = load_tok(4);         // tokens of the chunks issued in phase 1
   // the later descriptors of phase 0, which has no wait of its own before their use
   load_later(dAl, descA, 0, endA);
@@ -313,7 +325,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   issue_chunk(1, tok1);
   issue_chunk(2, tok2);
   LV_TL_WALL(2);
-  wait_vmcnt<4>();
+  wait_vmcnt<2 * kDmaPerChunk>();
   LV_TL_WALL(3);
   asm volatile("s_barrier" ::: "memory");
   LV_TL_WALL(4);
@@ -392,7 +404,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     constexpr bool FIRST = decltype(is_first)::value, NEXT = decltype(has_next)::value;
     if (!FIRST && ph == kBoostPhases) __builtin_amdgcn_s_setprio(0);
     // (scalar loads, two phases ahead of their use)
-    const int end2A = peA[last_chunk(ph + 2)], end2B = peB[last_chunk(ph + 2)];
+    const int end2A = peA[last_chunk(ph + 2)], end2B = PW == 2 ? peB[last_chunk(ph + 2)] : 0;
     LV_TL_BEGIN(tl_later);
     if constexpr (!FIRST) {            // (phase 0: fetched in the prologue)
       load_later(dAl, descA, doneA, endA);
@@ -414,7 +426,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       // first descriptors and tokens of the next phase: in place, their users are done
       // (ahead of the chunks: a load issued behind a chunk is held up until its data is in)
       dA0 = load_desc(descA, min(endA, lastA));
-      dB0 = load_desc(descB, min(endB, lastB));
+      if constexpr (PW == 2) dB0 = load_desc(descB, min(endB, lastB));
       if constexpr (!FIRST) {
         const int t0 = tok_of(2 * ph + 1, tokn0), t1 = tok_of(2 * ph + 2, tokn1);
         tokn0 = load_tok(2 * ph + 3); tokn1 = load_tok(2 * ph + 4);
@@ -476,9 +488,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     }
   };
   store_patch(A, pwA);
-  store_patch(B, pwB);
+  if constexpr (PW == 2) store_patch(B, pwB);
   LV_TL_WALL(6);
-  LV_TL_FLUSH(a, blockIdx.x * kPairWaves + wave, lane);
+  LV_TL_FLUSH(a, blockIdx.x * NWV + wave, lane);
 }
 
 litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {
@@ -487,8 +499,26 @@ litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, 
   const int64_t bh8 = ((int64_t)a.B * a.H + 7) / 8 * 8;
   const int64_t blocks = bh8 * a.n_groups;
   if (blocks > 0x7fffffff) return fail(LITEVAR_E_UNSUPPORTED, "grid too large");
+  // One patch per wave when the launch has no more working workgroups than the GPU has CUs
+  // (with output sharing about half of them exit at once): sixteen waves then fill the CU that
+  // eight would leave half empty.
+  int pw = pl->patches_per_wave;
+  if (pw == 0) {
+    static thread_local int n_cu[64] = {0};
+    int dev = 0;
+    if (litevar_status s = hip_check(hipGetDevice(&dev), "hipGetDevice")) return s;
+    if (dev >= 0 && dev < 64 && n_cu[dev] == 0)
+      if (litevar_status s = hip_check(hipDeviceGetAttribute(&n_cu[dev], hipDeviceAttributeMultiprocessorCount, dev),
+                                       "hipDeviceGetAttribute")) return s;
+    const int cus = dev >= 0 && dev < 64 ? n_cu[dev] : 256;
+    const int64_t working = a.cfg_share ? ((int64_t)a.B * a.H * a.n_groups + 1) / 2 : (int64_t)a.B * a.H * a.n_groups;
+    pw = working <= cus ? 1 : 2;
+  }
   const float c = a.sm_scale * 1.4426950408889634f;
-  hipLaunchKernelGGL(k_attn_bf16_pair, dim3((unsigned)blocks), dim3(kPairWaves * 64), 0, st, a, c);
+  if (pw == 1)
+    hipLaunchKernelGGL(k_attn_bf16_pair<1>, dim3((unsigned)blocks), dim3(kGroupPatches * 64), 0, st, a, c);
+  else
+    hipLaunchKernelGGL(k_attn_bf16_pair<2>, dim3((unsigned)blocks), dim3(kGroupPatches / 2 * 64), 0, st, a, c);
   return hip_check(hipGetLastError(), "bf16 attention launch");
 }
 

@@ -189,7 +189,8 @@ def test_var_d16(lv, waves):
     assert torch.equal(o[:, :, 0].cpu(), v[:, :, 0])
 
 
-@pytest.mark.parametrize("waves", [0, 4, 8, 16, (4, 64, 2, 1), (8, 64, 2, 1)])
+@pytest.mark.parametrize("waves", [0, 4, 8, 16, (4, 64, 2, 1), (8, 64, 2, 1),
+                                   (16, 0, 0, -1, 1), (16, 0, 0, -1, 2)])   # (.., patches per wave)
 def test_var_d30_kv_step(lv, waves):
     w = workloads.get("var_d30_kvstep")
     q, k, v = workloads.make_workload_qkv(w)
@@ -284,7 +285,7 @@ ATTN_CASES = [
 
 @pytest.mark.parametrize("case", range(len(ATTN_CASES)))
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("waves", [4, 8, (16, 0, 0, -1, 1), (16, 0, 0, -1, 2)])   # 16 patches: one and two per wave
 def test_attn_edge_cases(lv, case, dtype, waves):
     scales, rad, n_sink, q_scales, B, H = ATTN_CASES[case]
     per = rad if isinstance(rad, list) else None
@@ -416,11 +417,11 @@ def test_calibrated_table_feeds_the_plan(lv):
 
 
 def test_random_configurations_sweep(lv):
-    """forty seeded random problems (scale lists in any order, per-part radii with dense
+    """forty-eight seeded random problems (scale lists in any order, per-part radii with dense
     parts, dense leading scales, query-scale ranges, all three kernels): masks bit-exact,
     index sets through the CSR export, attention within tolerance"""
     rng = np.random.default_rng(20241127)
-    for it in range(40):
+    for it in range(48):
         K = int(rng.integers(1, 7))
         scales = [int(x) for x in rng.integers(1, 20, size=K)]
         if it % 4 == 0:
@@ -430,7 +431,7 @@ def test_random_configurations_sweep(lv):
         n_sink = int(rng.integers(0, K + 1)) if it % 3 == 0 else 0
         qb = int(rng.integers(0, K))
         q_scales = (qb, int(rng.integers(qb + 1, K + 1))) if it % 5 else None
-        waves = (4, 8, 16)[it % 3]
+        waves = (4, 8, (16, 0, 0, -1, 1), (16, 0, 0, -1, 2))[it % 4]
         dtype = "bf16" if it % 2 == 0 else "f32"
         print(f"  sweep {it}: scales={scales} radii={radii} n_sink={n_sink} q_scales={q_scales} "
               f"waves={waves} {dtype}", flush=True)
