@@ -160,7 +160,13 @@ def main():
     achieved = bytes_layer / (kernel_us * 1e-6) / 1e9
 
     if w.dtype == "bf16" and plan.waves_per_group == 16:
-        kname = "k_attn_bf16_pair"
+        # the library's rule: one patch per wave when the working workgroups fit the CUs
+        working = BH * plan.n_groups
+        if share is not None:
+            working = (working + 1) // 2
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        pw = plan.patches_per_wave or (1 if working <= cus else 2)
+        kname = f"k_attn_bf16_pair<{pw}>"
     elif w.dtype == "bf16":
         kname = (f"k_attn_bf16<{plan.waves_per_group}, {plan.chunk_keys}, 1, {plan.prefetch_chunks}, "
                  f"{plan.ring_chunks - plan.prefetch_chunks - 2}>")
