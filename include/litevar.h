@@ -121,7 +121,10 @@ typedef struct litevar_plan_opts {
                                wave, sixteen waves per workgroup, when the launch has no more
                                working workgroups than the GPU has CUs; else two patches per wave,
                                eight waves), else 1 or 2 */
-  int32_t reserved[3];
+  int32_t batch_heads_hint; /* 0 = unknown, else the B * H of the launches this plan is for: when
+                               waves_per_group is left to the library, few (batch, head) pairs get
+                               smaller groups, so that the launch still fills the GPU */
+  int32_t reserved[2];
 } litevar_plan_opts;
 
 /*

@@ -24,6 +24,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--asc", action="store_true", help="share the conditional output everywhere")
     ap.add_argument("--graph", action="store_true", help="replay each layer's steps as one HIP graph")
+    ap.add_argument("--batch", type=int, default=0, help="batch size (0 = the workload's)")
+    ap.add_argument("--no-hint", action="store_true", help="do not tell the plans the batch size")
     args = ap.parse_args()
 
     import torch
@@ -39,8 +41,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
     w = workloads.get(args.workload)
-    gen = GenerationLayer(w.scales, w.radius, n_sink_scales=w.n_sink, device=dev)
-    B, H, L = w.batch, w.heads, gen.kv_len
+    B, H = args.batch or w.batch, w.heads
+    working = B * H // 2 if args.asc else B * H          # (batch, head) pairs that compute
+    gen = GenerationLayer(w.scales, w.radius, n_sink_scales=w.n_sink, device=dev,
+                          batch_heads=0 if args.no_hint else working)
+    L = gen.kv_len
     g = torch.Generator(device=dev).manual_seed(w.seed + 999)
 
     def draw():
@@ -100,6 +105,7 @@ def main():
         "dtype": "bf16", "data": "synthetic (seeded N(0,1), drawn on the device)",
         "config": {"workload": w.name + " (all steps)", "scales": list(w.scales), "batch": B,
                    "heads": H, "radius": w.radius, "asc_everywhere": bool(args.asc),
+                   "patches_per_group": [int(p.waves_per_group) for p in gen.plans],
                    "hip_graph": bool(args.graph)}}))
 
 

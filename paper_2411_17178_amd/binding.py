@@ -33,7 +33,8 @@ class _MaskDesc(C.Structure):
 class _PlanOpts(C.Structure):
     _fields_ = [("waves_per_group", C.c_int32), ("chunk_keys", C.c_int32),
                 ("prefetch_chunks", C.c_int32), ("spare_chunks", C.c_int32),
-                ("patches_per_wave", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("patches_per_wave", C.c_int32), ("batch_heads_hint", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class _Plan(C.Structure):
@@ -106,11 +107,12 @@ def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
     return d
 
 
-def _make_opts(waves_per_group):
+def _make_opts(waves_per_group, batch_heads=0):
     """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks, spare_chunks,
     patches_per_wave); 0 (spare: -1) = library default."""
     o = _PlanOpts()
     o.spare_chunks = -1
+    o.batch_heads_hint = int(batch_heads)
     if isinstance(waves_per_group, (tuple, list)):
         vals = [int(x) for x in waves_per_group] + [0, 0, -1]
         o.waves_per_group, o.chunk_keys, o.prefetch_chunks = vals[0], vals[1], vals[2]
@@ -137,31 +139,33 @@ class Plan:
 
 
 def litevar_mask_plan_bytes(scales, radius, radius_per_key_scale=None, n_sink_scales=0,
-                            q_scales=None, waves_per_group=0):
+                            q_scales=None, waves_per_group=0, batch_heads=0):
     d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
-    o = _make_opts(waves_per_group)
+    o = _make_opts(waves_per_group, batch_heads)
     n = C.c_size_t(0)
     _check(load_library().litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
     return int(n.value)
 
 
 def litevar_mask_plan_stats(scales, radius, radius_per_key_scale=None, n_sink_scales=0,
-                            q_scales=None, waves_per_group=0):
+                            q_scales=None, waves_per_group=0, batch_heads=0):
     """Host-only dry run: a Plan without a device blob (sizes and pair counts only)."""
     d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
-    o = _make_opts(waves_per_group)
+    o = _make_opts(waves_per_group, batch_heads)
     handle = _Plan()
     _check(load_library().litevar_mask_plan_stats(C.byref(d), C.byref(o), C.byref(handle)))
     return Plan(handle, None)
 
 
 def litevar_mask_build(scales, radius, radius_per_key_scale=None, n_sink_scales=0, q_scales=None,
-                       waves_per_group=0, device="cuda", stream=None, blob=None):
+                       waves_per_group=0, device="cuda", stream=None, blob=None, batch_heads=0):
     """Build a plan on the device.  `blob` (optional uint8 CUDA tensor, large enough and
-    256-byte aligned) is reused as the plan's storage instead of a fresh allocation."""
+    256-byte aligned) is reused as the plan's storage instead of a fresh allocation.
+    `batch_heads` (optional): B * H of the launches the plan is for, which lets the library
+    pick smaller groups for small batches."""
     lib = load_library()
     d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
-    o = _make_opts(waves_per_group)
+    o = _make_opts(waves_per_group, batch_heads)
     n = C.c_size_t(0)
     _check(lib.litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
     if blob is None:

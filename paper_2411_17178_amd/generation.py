@@ -19,7 +19,7 @@ from . import binding
 
 class GenerationLayer:
     def __init__(self, scales, radius, radius_per_key_scale=None, n_sink_scales=0,
-                 waves_per_group=0, device="cuda"):
+                 waves_per_group=0, device="cuda", batch_heads=0):
         self.scales = [int(s) for s in scales]
         self.offsets = [0]
         for s in self.scales:
@@ -27,7 +27,8 @@ class GenerationLayer:
         self.kv_len = self.offsets[-1]
         self.plans = [
             binding.litevar_mask_build(self.scales, radius, radius_per_key_scale, n_sink_scales,
-                                       (k, k + 1), waves_per_group=waves_per_group, device=device)
+                                       (k, k + 1), waves_per_group=waves_per_group, device=device,
+                                       batch_heads=batch_heads)
             for k in range(len(self.scales))
         ]
 

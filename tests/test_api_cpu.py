@@ -167,3 +167,22 @@ def test_calibrate_validation_needs_no_gpu(lv):
     assert call(sc, 3, ptr, 1, 2, C.c_float(0.9), ptr, C.c_size_t(8), ptr, None, None) == -1
     assert b"workspace" in lib.litevar_last_error()
     assert call(sc, 3, ptr, 1, 2, C.c_float(0.9), C.c_void_p(4097), C.c_size_t(1 << 20), ptr, None, None) == -1
+
+
+def test_batch_heads_hint_picks_smaller_groups(lv):
+    """KV step of the 10-scale list (one 16-patch group per (batch, head) pair): few pairs get
+    8 or 4 patches per group so that the launch has enough workgroups; no hint, many pairs or
+    an explicit group size leave the choice alone."""
+    sc, q = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16), (9, 10)
+    st = lambda **kw: lv.litevar_mask_plan_stats(sc, 3, None, 0, q, **kw)
+    assert st().waves_per_group == 16 and st().n_groups == 1
+    assert st(batch_heads=480).waves_per_group == 16
+    assert st(batch_heads=240).waves_per_group == 16
+    assert st(batch_heads=120).waves_per_group == 8 and st(batch_heads=120).n_groups == 2
+    assert st(batch_heads=60).waves_per_group == 4 and st(batch_heads=60).n_groups == 4
+    assert st(batch_heads=60, waves_per_group=16).waves_per_group == 16
+    assert st(batch_heads=60).retained_pairs == st().retained_pairs
+    with pytest.raises(lv.LitevarError):
+        st(batch_heads=-1)
+    # query scales of side <= 8 use 4 patches per group whatever the hint
+    assert lv.litevar_mask_plan_stats(sc, 3, None, 0, (6, 7), batch_heads=4).waves_per_group == 4
