@@ -250,12 +250,6 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   // profiling build: LITEVAR_TIMELINE_PTR holds the device address of a buffer of
   // 16 x uint64 per wave (see the LV_TL_* macros in the kernel)
   if (const char* e = getenv("LITEVAR_TIMELINE_PTR")) a.timeline = (unsigned long long*)strtoull(e, nullptr, 0);
-  for (int i = 0; i < 4; ++i) {
-    char name[32];
-    snprintf(name, sizeof name, "LITEVAR_TUNE%d", i);
-    const char* e = getenv(name);
-    a.tune[i] = e ? atoi(e) : 0;
-  }
 #endif
   if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);
   return launch_attn_bf16(plan, a, (hipStream_t)stream);

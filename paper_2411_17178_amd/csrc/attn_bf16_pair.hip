@@ -156,11 +156,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // first phases, which evens out the two finishing times.
   const bool later_arrival = PW == 2 && (__builtin_amdgcn_s_getreg(4 | (3 << 11)) & 0xf) >= 2;   // HW_ID.WAVE_ID
   if (later_arrival) __builtin_amdgcn_s_setprio(1);
-#ifdef LITEVAR_TIMELINE
-  // experiment: delay the first (tune[0] = 1) or the later (2) workgroups of a CU by tune[1] x 64 cycles
-  if ((a.tune[0] == 1 && seq < a.tune[2]) || (a.tune[0] == 2 && seq >= a.tune[2]))
-    for (int i = 0; i < a.tune[1]; ++i) __builtin_amdgcn_s_sleep(1);
-#endif
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;

@@ -41,9 +41,6 @@ struct AttnArgs {
   int n_groups;
   int q_len;                     // query rows per (batch, head)
   unsigned long long* timeline;  // per-wave timing records (builds with LITEVAR_TIMELINE only), else nullptr
-#ifdef LITEVAR_TIMELINE
-  int tune[4];                   // experiment knobs of profiling builds
-#endif
 };
 
 litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
