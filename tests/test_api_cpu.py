@@ -186,3 +186,14 @@ def test_batch_heads_hint_picks_smaller_groups(lv):
         st(batch_heads=-1)
     # query scales of side <= 8 use 4 patches per group whatever the hint
     assert lv.litevar_mask_plan_stats(sc, 3, None, 0, (6, 7), batch_heads=4).waves_per_group == 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N above 1 exits with a message that says why (one GPU only)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                         stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
