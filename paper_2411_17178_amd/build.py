@@ -2,28 +2,23 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblitevar.so")
-LIB_TIMELINE = os.path.join(HERE, "liblitevar_timeline.so")   # profiling build, see timeline.py
+OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "plan_build.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_pair.hip",
            "calibrate.hip"]
 # -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores are -inf
 # and the softmax reference starts at a finite floor), and it spares the canonicalising
 # v_max that IEEE maxNum semantics would need in front of every fmaxf.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-honor-nans",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-result", "-Wno-unknown-warning-option"]
 
 
-def build(verbose: bool = False, timeline: bool = False) -> str:
-    """timeline=True builds the profiling variant (-DLITEVAR_TIMELINE: the 16-patch kernel
-    records per-wave time stamps) next to the product library, which it does not replace."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    lib = LIB_TIMELINE if timeline else LIB
-    cmd = [hipcc] + FLAGS + (["-DLITEVAR_TIMELINE"] if timeline else []) + ["-o", lib] + \
-        [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -33,8 +28,21 @@ def build(verbose: bool = False, timeline: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return lib
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles every source (one hipcc per file, in parallel) and links the shared library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        jobs = [ex.submit(_run, [hipcc] + FLAGS + ["-c", "-o", o, os.path.join(CSRC, s)], verbose)
+                for s, o in zip(SOURCES, objs)]
+        for j in jobs:
+            j.result()
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, verbose)
+    return LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, timeline="--timeline" in sys.argv))
+    print(build(verbose=True))

@@ -4,7 +4,6 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 
 namespace lv {
@@ -245,12 +244,6 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
   a.n_groups = plan->n_groups;
   a.q_len = plan->q_len;
-  a.timeline = nullptr;
-#ifdef LITEVAR_TIMELINE
-  // profiling build: LITEVAR_TIMELINE_PTR holds the device address of a buffer of
-  // 16 x uint64 per wave (see the LV_TL_* macros in the kernel)
-  if (const char* e = getenv("LITEVAR_TIMELINE_PTR")) a.timeline = (unsigned long long*)strtoull(e, nullptr, 0);
-#endif
   if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);
   return launch_attn_bf16(plan, a, (hipStream_t)stream);
 }

@@ -36,32 +36,6 @@
 
 #include "attn_bf16_common.h"
 
-// Per-wave timing records for profiling builds (-DLITEVAR_TIMELINE): 16 x uint64 per wave.
-//   [0] start  [1] first chunks issued  [2] prologue loads issued  [3] prologue loads landed
-//   [4] first barrier passed  [5] phases done  [6] stored          (100 MHz wall clock)
-//   [8] cycles in steps  [9] in issuing chunks and loads  [10] in barriers  [11] in the phase
-//   loop  [12] hardware id (HW_ID | XCC_ID << 32)  [13] waiting for memory at phase ends
-//   (shader clock).  Empty in normal builds.
-#ifdef LITEVAR_TIMELINE
-#define LV_TL_DECL unsigned long long tl_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}
-#define LV_TL_WALL(i) tl_[i] = wall_clock64()
-#define LV_TL_BEGIN(v) const long long v = clock64()
-#define LV_TL_ADD(i, v) tl_[i] += clock64() - (v)
-#define LV_TL_FLUSH(args, wave_index, lane)                                                       \
-  do {                                                                                            \
-    tl_[12] = (unsigned long long)__builtin_amdgcn_s_getreg(4 | (31 << 11)) |                      \
-              ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32);              \
-    if ((args).timeline && (lane) == 0)                                                            \
-      for (int i_ = 0; i_ < 16; ++i_) (args).timeline[(size_t)(wave_index) * 16 + i_] = tl_[i_];   \
-  } while (0)
-#else
-#define LV_TL_DECL
-#define LV_TL_WALL(i)
-#define LV_TL_BEGIN(v)
-#define LV_TL_ADD(i, v)
-#define LV_TL_FLUSH(args, wave_index, lane)
-#endif
-
 namespace lv {
 
 namespace {
@@ -147,8 +121,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
   if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
 
-  LV_TL_DECL;
-  LV_TL_WALL(0);
   // Two workgroups share a CU, and the instruction arbiter prefers the older waves: left
   // alone, the workgroup that arrived first runs as if it had the CU to itself and the other
   // one finishes a quarter later, alone on a CU that it cannot fill.  The later arrival (it
@@ -234,7 +206,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   tok0 = tok_of(0, tok0); tok1 = tok_of(1, tok1); tok2 = tok_of(2, tok2);
   asm volatile("" : "+v"(tok0), "+v"(tok1), "+v"(tok2));   // (here: waits for the three, if they were loaded at all)
 
-  LV_TL_WALL(1);
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
   const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
   const __amdgpu_buffer_rsrc_t descA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.step_addr + sbA * 64), 0, (lastA + 1) * 512, kBufferFlags);
@@ -319,11 +290,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   issue_chunk(0, tok0);
   issue_chunk(1, tok1);
   issue_chunk(2, tok2);
-  LV_TL_WALL(2);
   wait_vmcnt<2 * kDmaPerChunk>();
-  LV_TL_WALL(3);
   asm volatile("s_barrier" ::: "memory");
-  LV_TL_WALL(4);
 
   // One step: 32 keys against the 16 queries of patch ps.
   auto run_step = [&](PatchState& ps, const uint2 cur, const uint64_t* masks, int s) {
@@ -394,23 +362,17 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   // ---- phases ----
   int doneA = 0, doneB = 0;                             // steps finished so far
-  LV_TL_BEGIN(tl_loop);
   auto run_phase = [&](int ph, auto is_first, auto has_next) {
     constexpr bool FIRST = decltype(is_first)::value, NEXT = decltype(has_next)::value;
     if (!FIRST && ph == kBoostPhases) __builtin_amdgcn_s_setprio(0);
     // (scalar loads, two phases ahead of their use)
     const int end2A = peA[last_chunk(ph + 2)], end2B = PW == 2 ? peB[last_chunk(ph + 2)] : 0;
-    LV_TL_BEGIN(tl_later);
     if constexpr (!FIRST) {            // (phase 0: fetched in the prologue)
       load_later(dAl, descA, doneA, endA);
       load_later(dBl, descB, doneB, endB);
     }
-    LV_TL_ADD(9, tl_later);
-    LV_TL_BEGIN(tl_first);
     if (doneA < endA) run_step(A, dA0, maskA, doneA);
     if (doneB < endB) run_step(B, dB0, maskB, doneB);
-    LV_TL_ADD(8, tl_first);
-    LV_TL_BEGIN(tl_issue);
     if constexpr (NEXT) {
       if constexpr (!FIRST) {
         // The later descriptors have had two steps to arrive; with nothing else outstanding
@@ -429,8 +391,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
         issue_chunk(2 * ph + 1, t0); issue_chunk(2 * ph + 2, t1);
       }
     }
-    LV_TL_ADD(9, tl_issue);
-    LV_TL_BEGIN(tl_rest);
 #pragma unroll
     for (int i = 0; i < kLater; ++i)
       if (doneA + 1 + i < endA) run_step(A, dAl[i], maskA, doneA + 1 + i);
@@ -440,18 +400,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     for (int i = 0; i < kLater; ++i)
       if (doneB + 1 + i < endB) run_step(B, dBl[i], maskB, doneB + 1 + i);
     for (int s = doneB + 1 + kLater; s < endB; ++s) run_step(B, load_desc(descB, s), maskB, s);
-    LV_TL_ADD(8, tl_rest);
     doneA = endA; doneB = endB;
     endA = end1A; endB = end1B; end1A = end2A; end1B = end2B;
     // The chunks of phase ph + 1, the next descriptors and tokens are in once nothing of
     // this wave is outstanding.  All LDS reads of the phase have returned (each step waits
     // for its own), so after the barrier the slots of chunks 2 ph - 3 and 2 ph - 2 are free.
-    LV_TL_BEGIN(tl_wait);
     wait_vmcnt<0>();
-    LV_TL_ADD(13, tl_wait);
-    LV_TL_BEGIN(tl_bar);
     if constexpr (NEXT) asm volatile("s_barrier" ::: "memory");
-    LV_TL_ADD(10, tl_bar);
   };
   {
     run_phase(0, std::true_type{}, std::true_type{});
@@ -460,8 +415,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     run_phase(ph, std::false_type{}, std::false_type{});    // (no steps left when the list is one chunk)
   }
 
-  LV_TL_ADD(11, tl_loop);
-  LV_TL_WALL(5);
 
   asm volatile("" : : "v"(warm));      // the only use of the plan-touching load: keeps it
 
@@ -484,8 +437,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   };
   store_patch(A, pwA);
   if constexpr (PW == 2) store_patch(B, pwB);
-  LV_TL_WALL(6);
-  LV_TL_FLUSH(a, blockIdx.x * NWV + wave, lane);
 }
 
 litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, hipStream_t st) {

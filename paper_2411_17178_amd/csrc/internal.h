@@ -40,7 +40,6 @@ struct AttnArgs {
   const int32_t* step_tok;
   int n_groups;
   int q_len;                     // query rows per (batch, head)
-  unsigned long long* timeline;  // per-wave timing records (builds with LITEVAR_TIMELINE only), else nullptr
 };
 
 litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
