@@ -224,7 +224,7 @@ def test_var_d36_windowed_and_dense(lv):
     assert float((o.float() - od.float()).abs().max()) > 0.05
 
 
-def test_var_2k_cfg_share_sampled(lv):
+def test_var_2k_cfg_share(lv):
     w = workloads.get("var_2k_cfg")
     q, k, v = workloads.make_workload_qkv(w)
     share = workloads.make_cfg_share(w.heads, len(w.scales), w.seed)
@@ -242,6 +242,22 @@ def test_var_2k_cfg_share_sampled(lv):
     err = float(np.abs(got - ref).max())
     print(f"  var_2k max-abs err on sampled rows {err:.3e}", flush=True)
     assert err <= TOL["bf16"]
+    # every query row of four heads, conditional and unconditional (8 of the 32 (batch, head)
+    # pairs, 273 920 rows): every group, patch and phase of the 2K plan goes through the float
+    # comparison, without sharing and, against the oracle's own cond -> uncond copy, with it
+    heads = [0, 5, 10, 15]
+    sub = [t[:, heads].contiguous() for t in (q, k, v)]
+    print(f"  oracle on all {off[-1]} rows of heads {heads}, cond and uncond", flush=True)
+    ref_full = _oracle_attn(w.scales, [w.radius] * 14, *sub, w.sm_scale)
+    got_full = o_plain[:, heads].float().cpu().numpy()
+    err_full = float(np.abs(got_full - ref_full).max())
+    ref_shared = ref_full.copy()
+    oracle.cfg_share(w.scales, ref_shared, share[heads].numpy())
+    assert not np.array_equal(ref_shared, ref_full)
+    err_shared = float(np.abs(o[:, heads].float().cpu().numpy() - ref_shared).max())
+    print(f"  var_2k compared rows: {ref_full.shape[0] * ref_full.shape[1] * ref_full.shape[2]} "
+          f"(all rows of 8 pairs); max-abs err {err_full:.3e} plain, {err_shared:.3e} shared", flush=True)
+    assert err_full <= TOL["bf16"] and err_shared <= TOL["bf16"]
     # CFG sharing, checked everywhere: shared uncond rows equal their cond rows bit for
     # bit, every other row equals the flag-off run bit for bit
     o, o_plain = o.cpu(), o_plain.cpu()

@@ -366,3 +366,14 @@ def test_cfg_share_copies_cond_to_uncond():
     for h in range(H):
         exp = o2[:2, h] if share[h, 3] else o2[2:, h]
         assert (out2[2:, h] == exp).all()
+
+
+def test_pair_counts_file_is_what_its_script_writes():
+    """tests/golden/pair_counts.txt is written by the closed-form script next to it (which
+    imports neither the oracle nor the library)"""
+    import subprocess
+    import sys
+    script = os.path.join(GOLDEN, "make_pair_counts.py")
+    src = open(script).read()
+    assert "import oracle" not in src and "paper_2411_17178_amd" not in src
+    assert subprocess.run([sys.executable, script, "--check"]).returncode == 0
