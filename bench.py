@@ -9,8 +9,11 @@ the VAR-d30 KV-cache step (256 queries of the 16x16 scale against all 680 keys, 
 30 heads, radius 3, 30 layers).
 
 Prints ONE JSON line: effective TFLOP/s on window-retained pairs, ms per step, the
-attention kernel's HIP-event duration and roofline fraction, and the fp64 oracle's
-throughput on the host cores as a reported baseline.
+attention kernel's HIP-event duration and roofline fraction, the fp64 oracle's throughput
+on the host cores as a reported baseline, what this GPU delivers on a streaming copy and a
+register-only MFMA loop (`measured_peaks`), and -- unless --no-extra -- a shorter
+measurement of the other workloads (`workloads`: VAR-d16, VAR-d36 windowed and dense
+block-causal, the 2K sequence with output sharing).
 """
 import argparse
 import json
@@ -25,6 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 LAYERS = {"tiny_f32": 1, "var_d16": 16, "var_d30_kvstep": 30, "var_d36_512": 36, "var_2k_cfg": 4}
+EXTRA = [("var_d16", False), ("var_d36_512", False), ("var_d36_512", True), ("var_2k_cfg", False)]
 
 
 def parse():
@@ -41,15 +45,17 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--dense", action="store_true", help="dense block-causal path (radius -1)")
+    ap.add_argument("--no-extra", action="store_true", help="headline workload only")
     return ap.parse_args()
 
 
-def measured_traffic(workload, kernel):
+def measured_traffic(workload, kernel, kernel_us):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload
-    (FETCH_SIZE and WRITE_SIZE runs, each scaled by a known-size copy kernel); None when
-    no summary exists for this kernel instance."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
-                        f"{kernel.split(chr(60))[0]}_{workload}_pmc.txt")
+    (FETCH_SIZE and WRITE_SIZE runs, each scaled by a known-size copy kernel).  None when no
+    summary exists for this kernel instance, or when the kernel time recorded with the
+    counters differs from this run's by more than 5 % (the summary then describes another
+    version of the kernel)."""
+    path = os.path.join(ROOT, "profiles", f"{kernel.split(chr(60))[0]}_{workload}_pmc.txt")
     if not os.path.exists(path):
         return None
     kv = {}
@@ -57,18 +63,27 @@ def measured_traffic(workload, kernel):
         if " = " in line:
             a, b = line.split(" = ", 1)
             kv[a.strip()] = b.strip()
-    if kv.get("kernel") != kernel or kv.get("workload") != workload:
+    if kv.get("kernel") != kernel or kv.get("workload") != workload or "kernel_us" not in kv:
+        return None
+    if abs(float(kv["kernel_us"]) - kernel_us) > 0.05 * kernel_us:
         return None
     return int(kv["traffic_bytes_per_launch"])
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def kernel_name(plan, w, working, cus):
+    if w.dtype == "bf16" and plan.waves_per_group == 16:
+        # the library's rule: one patch per wave when the working workgroups fit the CUs
+        pw = plan.patches_per_wave or (1 if working <= cus else 2)
+        return f"k_attn_bf16_pair<{pw}>"
+    if w.dtype == "bf16":
+        return (f"k_attn_bf16<{plan.waves_per_group}, {plan.chunk_keys}, 1, {plan.prefetch_chunks}, "
+                f"{plan.ring_chunks - plan.prefetch_chunks - 2}>")
+    return "k_attn_f32"
 
+
+def run_workload(name, dense, steps, warmup, layers, tiling, keep_layer0=False):
+    """Times `steps` steps (plan build + one attention launch per layer) of one workload;
+    returns (result dict, context for the oracle leg)."""
     import numpy as np
     import torch
 
@@ -76,17 +91,9 @@ def main():
     import workloads
     from paper_2411_17178_amd.binding import prepare_attn_call
 
-    lv.load_library()
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
-        sys.exit(3)
-    torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-
-    w = workloads.get(args.workload)
-    tiling = (args.waves, args.chunk, args.depth, args.spare)
-    layers = args.layers or LAYERS[w.name]
-    radius = -1 if args.dense else w.radius
+    w = workloads.get(name)
+    radius = -1 if dense else w.radius
     tdtype = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     esize = 2 if w.dtype == "bf16" else 4
 
@@ -115,30 +122,30 @@ def main():
              for l in range(layers)]
 
     def step(ev0=None, ev1=None):
-        p = build_plan()                      # a1-a3: tables and work-list, on the device
+        p = build_plan()                      # scale table, window tables and work-list, on the device
         assert p.n_steps == plan.n_steps
         if ev0 is not None:
             ev0.record()
-        for c in calls:                       # a5-a10: one fused attention launch per layer
+        for c in calls:                       # one fused attention launch per layer
             c()
         if ev1 is not None:
             ev1.record()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(args.steps)]
+          for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(*ev[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
-    ms_per_step = (t1 - t0) / args.steps * 1e3
-    attn_ms = sum(a.elapsed_time(b) for a, b in ev)            # all attention launches
-    kernel_us = attn_ms * 1e3 / (args.steps * layers)          # average per launch
+    ms_per_step = (t1 - t0) / steps * 1e3
+    attn_ms = sum(a.elapsed_time(b) for a, b in ev)       # all attention launches
+    kernel_us = attn_ms * 1e3 / (steps * layers)          # average per launch
 
     BH = w.batch * w.heads
     pairs = plan.retained_pairs * BH
@@ -158,47 +165,130 @@ def main():
     # K + V read once per (batch, head) (256 B per token)
     bytes_layer = BH * (2 * plan.q_len * 64 * esize + 2 * plan.kv_len * 64 * esize)
     achieved = bytes_layer / (kernel_us * 1e-6) / 1e9
+    t_mfma_us = flops_layer / (MFMA_BF16_PEAK_TFLOPS * 1e12) * 1e6
+    t_hbm_us = bytes_layer / (HBM_PEAK_GBS * 1e9) * 1e6
 
-    if w.dtype == "bf16" and plan.waves_per_group == 16:
-        # the library's rule: one patch per wave when the working workgroups fit the CUs
-        working = BH * plan.n_groups
-        if share is not None:
-            working = (working + 1) // 2
-        cus = torch.cuda.get_device_properties(0).multi_processor_count
-        pw = plan.patches_per_wave or (1 if working <= cus else 2)
-        kname = f"k_attn_bf16_pair<{pw}>"
-    elif w.dtype == "bf16":
-        kname = (f"k_attn_bf16<{plan.waves_per_group}, {plan.chunk_keys}, 1, {plan.prefetch_chunks}, "
-                 f"{plan.ring_chunks - plan.prefetch_chunks - 2}>")
-    else:
-        kname = "k_attn_f32"
-    traffic = None if args.dense else measured_traffic(w.name, kname)
+    working = BH * plan.n_groups
+    if share is not None:
+        working = (working + 1) // 2
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    kname = kernel_name(plan, w, working, cus)
+    res = {
+        "workload": w.name + ("_dense" if dense else ""), "kernel": kname,
+        "us_per_layer": round(kernel_us, 3), "ms_per_step": round(ms_per_step, 4),
+        "step_tflops_retained": round(value, 3),
+        "kernel_tflops_retained": round(kernel_tflops, 2),
+        "mfma_frac_retained": round(kernel_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "hbm_gbs": round(achieved, 1), "hbm_frac": round(achieved / HBM_PEAK_GBS, 4),
+        # the roofline that binds: the larger of the two floors against the measured time
+        "bound": "hbm" if t_hbm_us >= t_mfma_us else "mfma",
+        "floor_us": round(max(t_hbm_us, t_mfma_us), 2),
+        "binding_roofline_frac": round(max(t_hbm_us, t_mfma_us) / kernel_us, 4),
+        "tile_density": round(plan.retained_pairs / plan.computed_pairs, 4),
+        "retained_pairs_per_bh": int(plan.retained_pairs), "layers": layers, "steps": steps,
+        "bytes_per_launch": bytes_layer,
+    }
+    ctx = dict(w=w, plan=plan, radius=radius, q0=q0, k0=k0, v0=v0, o0=os_[0], share=share, BH=BH)
+    if not keep_layer0:
+        ctx = None
+    return res, ctx
+
+
+def measure_peaks():
+    """Streaming-copy GB/s (read + write) and register-only bf16 MFMA TFLOP/s of this GPU."""
+    import torch
+
+    import paper_2411_17178_amd as lv
+    dev = torch.device("cuda:0")
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev)
+    out = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    t_copy = timed(lambda: lv.litevar_peak_copy(src, dst), 10)
+    t_read = timed(lambda: lv.litevar_peak_read(src, out), 10)
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = lv.litevar_peak_mfma_bf16(2048, out)
+    t_mfma = timed(mfma, 5)
+    del src, dst
+    return {"copy_gbs": round(2 * n / t_copy / 1e9, 1), "copy_bytes": 2 * n,
+            "copy_frac_of_spec": round(2 * n / t_copy / 1e9 / HBM_PEAK_GBS, 4),
+            "read_gbs": round(n / t_read / 1e9, 1),
+            "read_frac_of_spec": round(n / t_read / 1e9 / HBM_PEAK_GBS, 4),
+            "mfma_bf16_tflops": round(flops[0] / t_mfma / 1e12, 1),
+            "mfma_frac_of_spec": round(flops[0] / t_mfma / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "spec": {"hbm_gbs": HBM_PEAK_GBS, "mfma_bf16_tflops": MFMA_BF16_PEAK_TFLOPS}}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2411_17178_amd as lv
+    import workloads
+
+    lv.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    tiling = (args.waves, args.chunk, args.depth, args.spare)
+    w = workloads.get(args.workload)
+    layers = args.layers or LAYERS[w.name]
+    res, ctx = run_workload(args.workload, args.dense, args.steps, args.warmup, layers, tiling,
+                            keep_layer0=True)
+    plan, radius = ctx["plan"], ctx["radius"]
+    traffic = None if args.dense else measured_traffic(w.name, res["kernel"], res["us_per_layer"])
 
     out = {
         "metric": "windowed-attn effective TFLOP/s (retained pairs)",
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "value": res["step_tflops_retained"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
         "data": "synthetic (seeded N(0,1); layer 0 from the CPU recipe, other layers drawn on the device)",
-        "config": {"workload": w.name + ("_dense" if args.dense else ""), "scales": list(w.scales),
+        "config": {"workload": res["workload"], "scales": list(w.scales),
                    "batch": w.batch, "heads": w.heads, "head_dim": w.head_dim, "radius": radius,
                    "q_len": plan.q_len, "kv_len": plan.kv_len, "layers_per_step": layers,
                    "cfg_share": bool(w.cfg_share), "waves_per_group": plan.waves_per_group,
                    "chunk_keys": plan.chunk_keys, "ring_chunks": plan.ring_chunks,
                    "prefetch_chunks": plan.prefetch_chunks,
                    "step": "plan build + one attention forward per layer"},
-        "us_per_layer": round(kernel_us, 3),
-        "kernel_tflops_retained": round(kernel_tflops, 2),
-        "mfma_frac_retained": round(kernel_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-        "tile_density": round(plan.retained_pairs / plan.computed_pairs, 4),
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": kname,
-                     "bytes_per_launch": bytes_layer, "kernel_us": round(kernel_us, 3)},
+        "us_per_layer": res["us_per_layer"],
+        "kernel_tflops_retained": res["kernel_tflops_retained"],
+        "mfma_frac_retained": res["mfma_frac_retained"],
+        "binding_roofline_frac": res["binding_roofline_frac"],
+        "tile_density": res["tile_density"],
+        "roofline": {"bound": "hbm", "achieved": res["hbm_gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": res["hbm_frac"], "traffic": traffic,
+                     "traffic_source": ("committed rocprofv3 --pmc summary under profiles/ (not measured by "
+                                        "this run); dropped when its kernel time is not this run's"),
+                     "kernel": res["kernel"],
+                     "bytes_per_launch": res["bytes_per_launch"], "kernel_us": res["us_per_layer"]},
     }
 
     if not args.no_cpu_baseline:
         import oracle
+        BH, q0, k0, v0, share = ctx["BH"], ctx["q0"], ctx["k0"], ctx["v0"], ctx["share"]
         radii = [radius] * len(w.scales)
         arrs = [workloads.to_oracle_array(t) for t in (q0, k0, v0)]
         # bounded sample: time a few (batch, head) pairs, then as many as fit the budget
@@ -214,7 +304,7 @@ def main():
             ref = oracle.attn(w.scales, radii, *arrs, w.sm_scale, w.n_sink, w.q_scales, bh_range=(0, n))
             dt += time.perf_counter() - ta
             reps += 1
-        got = os_[0].float().cpu().numpy().reshape(BH, plan.q_len, 64)[:n]
+        got = ctx["o0"].float().cpu().numpy().reshape(BH, plan.q_len, 64)[:n]
         if share is not None:
             got, ref_c = got[: min(n, BH // 2)], ref.reshape(BH, plan.q_len, 64)[: min(n, BH // 2)]
         else:
@@ -225,6 +315,22 @@ def main():
             "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{n} of {BH} (batch, head) pairs of one layer, {reps} time(s), {dt:.2f} s",
             "gpu_vs_oracle_max_abs_err": err}
+    del ctx
+    torch.cuda.empty_cache()
+
+    out["measured_peaks"] = measure_peaks()
+    if not args.no_extra and not args.dense and args.workload == "var_d30_kvstep":
+        extra = []
+        for name, dense in EXTRA:
+            torch.cuda.empty_cache()
+            r, _ = run_workload(name, dense, 4 if dense else 8, 2, min(LAYERS[name], 8), (0, 0, 0, -1))
+            extra.append(r)
+        win = next(r for r in extra if r["workload"] == "var_d36_512")
+        den = next(r for r in extra if r["workload"] == "var_d36_512_dense")
+        out["workloads"] = extra
+        out["d36_windowed_vs_dense"] = {
+            "speedup": round(den["us_per_layer"] / win["us_per_layer"], 3),
+            "flop_ratio": round(den["retained_pairs_per_bh"] / win["retained_pairs_per_bh"], 3)}
     print(json.dumps(out))
 
 

@@ -106,6 +106,8 @@ typedef struct litevar_plan {
   int32_t radii[LITEVAR_MAX_SCALES];   /* per key scale: the widest radius over the plan's query scales */
   int32_t n_sink_scales;
   int32_t patches_per_wave; /* 16 patches per group only: 0 = chosen per launch, else 1 or 2 */
+  int32_t spin_limit;       /* bound of the kernels' LDS-flag waits, in polls */
+  int32_t reserved;
 } litevar_plan;
 
 /* Tuning knobs of the plan; zero-initialise for the defaults. */
@@ -124,7 +126,11 @@ typedef struct litevar_plan_opts {
   int32_t batch_heads_hint; /* 0 = unknown, else the B * H of the launches this plan is for: when
                                waves_per_group is left to the library, few (batch, head) pairs get
                                smaller groups, so that the launch still fills the GPU */
-  int32_t reserved[2];
+  int32_t spin_limit;       /* 4 and 8 patches per group only: polls (of about 64 cycles) after which a
+                               wave's wait on another wave's LDS flag gives up, marks the plan's header
+                               (litevar_plan_check then fails) and runs to its end without waiting;
+                               0 = default (2^22).  Tests of that path pass 1. */
+  int32_t reserved[1];
 } litevar_plan_opts;
 
 /*
@@ -157,7 +163,10 @@ litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_p
 
 /*
  * Synchronises `stream`, reads the blob's header back and checks it against the
- * handle (magic, sizes, the builder's overflow flag).  For tests and debugging.
+ * handle: magic, sizes, the builder's overflow flag, and the mark that an attention
+ * kernel leaves when one of its bounded waits gave up.  (Every attention kernel checks
+ * magic and builder flag itself and does nothing when they are bad, so a zeroed or
+ * half-built blob yields an untouched output, never a hang.)  For tests and debugging.
  */
 litevar_status litevar_plan_check(const litevar_plan* plan, void* stream);
 
@@ -248,6 +257,20 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
                                         const float* d_attn, int32_t N, int32_t H, float r0,
                                         void* d_workspace, size_t workspace_bytes,
                                         int32_t* d_radius, double* d_mass, void* stream);
+
+/*
+ * Diagnostics for benchmark reports (measurement, Section 4's efficiency figures are quoted
+ * against what the hardware delivers): litevar_peak_copy enqueues a streaming copy of `bytes`
+ * bytes (DEVICE pointers, 16-byte aligned, size a multiple of 16; HBM traffic = 2 x bytes);
+ * litevar_peak_read enqueues a read-only pass over `bytes` bytes (HBM traffic = bytes);
+ * litevar_peak_mfma_bf16 enqueues a register-only loop of v_mfma_f32_16x16x32_bf16 (8 waves on
+ * every SIMD, `iters` x 8 independent MFMAs per wave) and returns the floating-point
+ * operations it performs in *flops (HOST, optional).  d_out: DEVICE, 4 bytes, never written
+ * in practice.  The caller times them with events on `stream`.
+ */
+litevar_status litevar_peak_copy(const void* d_src, void* d_dst, size_t bytes, void* stream);
+litevar_status litevar_peak_read(const void* d_src, size_t bytes, void* d_out, void* stream);
+litevar_status litevar_peak_mfma_bf16(int32_t iters, void* d_out, double* flops, void* stream);
 
 #ifdef __cplusplus
 }

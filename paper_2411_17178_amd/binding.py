@@ -34,7 +34,7 @@ class _PlanOpts(C.Structure):
     _fields_ = [("waves_per_group", C.c_int32), ("chunk_keys", C.c_int32),
                 ("prefetch_chunks", C.c_int32), ("spare_chunks", C.c_int32),
                 ("patches_per_wave", C.c_int32), ("batch_heads_hint", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("spin_limit", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class _Plan(C.Structure):
@@ -48,7 +48,7 @@ class _Plan(C.Structure):
                 ("retained_pairs", C.c_int64), ("computed_pairs", C.c_int64),
                 ("off", C.c_uint64 * 12), ("scales", C.c_int32 * MAX_SCALES),
                 ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32),
-                ("patches_per_wave", C.c_int32)]
+                ("patches_per_wave", C.c_int32), ("spin_limit", C.c_int32), ("reserved", C.c_int32)]
 
 
 def lib_path():
@@ -70,7 +70,8 @@ def load_library():
     for name in ("litevar_mask_plan_bytes", "litevar_mask_plan_stats", "litevar_mask_build", "litevar_plan_check",
                  "litevar_window_table_export", "litevar_mask_export_dense",
                  "litevar_mask_export_csr", "litevar_windowed_attn_fwd",
-                 "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate"):
+                 "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate",
+                 "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16"):
         getattr(lib, name).restype = C.c_int32
     _lib = lib
     return lib
@@ -107,12 +108,13 @@ def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
     return d
 
 
-def _make_opts(waves_per_group, batch_heads=0):
+def _make_opts(waves_per_group, batch_heads=0, spin_limit=0):
     """waves_per_group: an int, or a tuple (waves, chunk_keys, prefetch_chunks, spare_chunks,
     patches_per_wave); 0 (spare: -1) = library default."""
     o = _PlanOpts()
     o.spare_chunks = -1
     o.batch_heads_hint = int(batch_heads)
+    o.spin_limit = int(spin_limit)
     if isinstance(waves_per_group, (tuple, list)):
         vals = [int(x) for x in waves_per_group] + [0, 0, -1]
         o.waves_per_group, o.chunk_keys, o.prefetch_chunks = vals[0], vals[1], vals[2]
@@ -158,14 +160,15 @@ def litevar_mask_plan_stats(scales, radius, radius_per_key_scale=None, n_sink_sc
 
 
 def litevar_mask_build(scales, radius, radius_per_key_scale=None, n_sink_scales=0, q_scales=None,
-                       waves_per_group=0, device="cuda", stream=None, blob=None, batch_heads=0):
+                       waves_per_group=0, device="cuda", stream=None, blob=None, batch_heads=0,
+                       spin_limit=0):
     """Build a plan on the device.  `blob` (optional uint8 CUDA tensor, large enough and
     256-byte aligned) is reused as the plan's storage instead of a fresh allocation.
     `batch_heads` (optional): B * H of the launches the plan is for, which lets the library
     pick smaller groups for small batches."""
     lib = load_library()
     d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
-    o = _make_opts(waves_per_group, batch_heads)
+    o = _make_opts(waves_per_group, batch_heads, spin_limit)
     n = C.c_size_t(0)
     _check(lib.litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
     if blob is None:
@@ -272,6 +275,28 @@ def litevar_window_calibrate(scales, attn_map, r0, with_mass=False, stream=None)
         C.c_void_p(radius.data_ptr()), C.c_void_p(mass.data_ptr()) if with_mass else None,
         _stream_handle(stream)))
     return (radius, mass) if with_mass else radius
+
+
+def litevar_peak_copy(src, dst, stream=None):
+    """Enqueue the library's streaming copy of src into dst (uint8 CUDA tensors of one size)."""
+    assert src.is_cuda and dst.is_cuda and src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(load_library().litevar_peak_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()),
+                                            C.c_size_t(src.numel() * src.element_size()), _stream_handle(stream)))
+
+
+def litevar_peak_read(src, out, stream=None):
+    """Enqueue the library's read-only pass over src (a CUDA tensor); out: 4 bytes, CUDA."""
+    _check(load_library().litevar_peak_read(C.c_void_p(src.data_ptr()),
+                                            C.c_size_t(src.numel() * src.element_size()),
+                                            C.c_void_p(out.data_ptr()), _stream_handle(stream)))
+
+
+def litevar_peak_mfma_bf16(iters, out, stream=None):
+    """Enqueue the library's register-only bf16 MFMA loop; returns the flops it performs."""
+    flops = C.c_double(0.0)
+    _check(load_library().litevar_peak_mfma_bf16(C.c_int32(iters), C.c_void_p(out.data_ptr()),
+                                                 C.byref(flops), _stream_handle(stream)))
+    return flops.value
 
 
 def prepare_attn_call(plan, q, k, v, sm_scale, out, cfg_share=None, stream=None):

@@ -69,6 +69,7 @@ litevar_status litevar_mask_plan_bytes(const litevar_mask_desc* desc, const lite
 static litevar_status check_patches_per_wave(const litevar_plan_opts* opts) {
   const int pw = opts ? opts->patches_per_wave : 0;
   if (pw < 0 || pw > 2) return fail(LITEVAR_E_INVALID_ARG, "patches_per_wave must be 0, 1 or 2 (got %d)", pw);
+  if (opts && opts->spin_limit < 0) return fail(LITEVAR_E_INVALID_ARG, "spin_limit must not be negative");
   return LITEVAR_OK;
 }
 
@@ -96,6 +97,7 @@ static void fill_handle(const Geom& g, const PlanSizes& z, const litevar_plan_op
     plan->radii[k] = r;
   }
   plan->n_sink_scales = g.n_sink;
+  plan->spin_limit = (opts && opts->spin_limit > 0) ? opts->spin_limit : kDefaultSpinLimit;
 }
 
 litevar_status litevar_mask_plan_stats(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
@@ -143,7 +145,10 @@ litevar_status litevar_plan_check(const litevar_plan* plan, void* stream) {
   rc = read_header(plan, (hipStream_t)stream, h);
   if (rc) return rc;
   if (h.magic != kMagic) return fail(LITEVAR_E_PLAN_CORRUPT, "device blob has a bad magic");
-  if (h.error) return fail(LITEVAR_E_PLAN_CORRUPT, "device builder disagrees with the host sizing");
+  if (h.error == kErrBuilder) return fail(LITEVAR_E_PLAN_CORRUPT, "device builder disagrees with the host sizing");
+  if (h.error == kErrWaitGaveUp)
+    return fail(LITEVAR_E_PLAN_CORRUPT, "an attention kernel's bounded wait gave up (its output is invalid)");
+  if (h.error) return fail(LITEVAR_E_PLAN_CORRUPT, "device blob carries the unknown error mark %d", h.error);
   if (h.blob_bytes != plan->blob_bytes || h.n_groups != plan->n_groups ||
       h.n_steps != plan->n_steps || h.n_union != plan->n_union_keys ||
       h.retained_pairs != plan->retained_pairs)
@@ -244,6 +249,8 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
   a.n_groups = plan->n_groups;
   a.q_len = plan->q_len;
+  a.hdr = (Header*)(plan->d_blob);
+  a.spin_limit = plan->spin_limit > 0 ? plan->spin_limit : kDefaultSpinLimit;
   if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);
   return launch_attn_bf16(plan, a, (hipStream_t)stream);
 }

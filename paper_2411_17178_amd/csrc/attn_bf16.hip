@@ -63,6 +63,7 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
   const int bh = (seq / a.n_groups) * 8 + xcd, grp = seq % a.n_groups;
   if (bh >= a.B * a.H) return;
   const int b = bh / a.H, h = bh % a.H;
+  if (!plan_usable(a.hdr)) return;
   const GroupDesc gd = a.groups[grp];
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
   if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
@@ -121,10 +122,27 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
       const int nc = ph + D;
       if (nc < P) {
         // chunk nc reuses the slot of chunk nc - NR, which steps of phases up to
-        // nc - NR + A may still read: wait until every compute wave is past them
+        // nc - NR + A may still read: wait until every compute wave is past them.  The wait
+        // is bounded: when it runs out (a plan that does not fit this kernel) the loader
+        // stops loading, marks the plan's header, lets every compute wave run to its end on
+        // whatever the ring holds, and exits like any other wave.
         const int need = nc - NR + A + 1;
-        if (need > 0)
-          while (lds_min_progress<NW>(progress) < need) __builtin_amdgcn_s_sleep(1);
+        if (need > 0) {
+          int polls = 0;
+          bool gave_up = false;
+          while (lds_min_progress<NW>(progress) < need) {
+            if (++polls > a.spin_limit) { gave_up = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+          }
+          if (gave_up) {
+            wait_vmcnt<0>();
+            if (lane == 0) {
+              lds_store_i32_nowait(landed, 0x7fffffff);
+              a.hdr->error = kErrWaitGaveUp;
+            }
+            return;
+          }
+        }
         // token batch nb serves chunks [T nb, T nb + T), T = kTokBatchChunks.  It is issued
         // together with chunk T (nb - 1): every chunk of batch nb - 2 (same half of the token
         // ring) has been issued by then, and the batch has landed before chunk T nb is issued
@@ -250,9 +268,18 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
   // (flag accesses in inline assembly: a volatile access would also wait for the wave's
   // outstanding descriptor prefetches)
   int32_t* const my_progress = progress + wave;
+  bool gave_up = false;                        // a wait of this wave ran out: it waits no more
   auto enter_phase = [&](int ph) {             // all steps of earlier phases are done
     if (lane == 0) lds_store_i32_nowait(my_progress, ph);
-    while (lds_load_i32_nowait(landed) <= ph) __builtin_amdgcn_s_sleep(1);
+    int polls = 0;
+    while (!gave_up && lds_load_i32_nowait(landed) <= ph) {
+      if (++polls > a.spin_limit) {            // (bounded: the loader may have stopped)
+        gave_up = true;
+        if (lane == 0) a.hdr->error = kErrWaitGaveUp;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
   };
   int ph = 0;
   if (n_steps > 0) {
@@ -260,7 +287,7 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
     int end = pe[0];
     auto advance_to = [&](int s) {             // wait until step s may run
       if (s >= end) {
-        do { ++ph; end = pe[ph]; } while (s >= end);
+        do { ++ph; end = pe[ph]; } while (s >= end && ph + 1 < P);   // (the table's last entry covers every step)
         enter_phase(ph);
       }
     };

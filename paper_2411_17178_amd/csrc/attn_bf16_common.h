@@ -47,6 +47,16 @@ __device__ inline float max_across_rows(float x) {
   return fmaxf(__uint_as_float(b0), __uint_as_float(b1));
 }
 
+// What every attention kernel checks before it reads anything else of the plan: the blob's
+// header carries the magic and not the builder's error mark.  A zeroed, stale or half-built
+// blob then makes the launch a no-op instead of a walk over garbage.  (Scalar loads: the
+// header is the same for every workgroup.)
+__device__ inline bool plan_usable(const Header* hdr) {
+  const const_i32_ptr w = (const_i32_ptr)hdr;
+  return w[0] == (int32_t)(kMagic & 0xffffffffu) && w[1] == (int32_t)(kMagic >> 32) &&
+         w[offsetof(Header, error) / 4] != kErrBuilder;
+}
+
 template <int N> __device__ inline void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   // gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt/lgkmcnt left at max

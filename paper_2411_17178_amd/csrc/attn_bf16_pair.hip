@@ -117,7 +117,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int bh = (seq / a.n_groups) * 8 + xcd, grp = seq % a.n_groups;
   if (bh >= a.B * a.H) return;
   const int b = bh / a.H, h = bh % a.H;
-  const GroupDesc gd = a.groups[grp];
+  const bool usable = plan_usable(a.hdr);
+  const GroupDesc gd = a.groups[grp];      // (requested together with the header words, used behind the check)
+  if (!usable) return;
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
   if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
 

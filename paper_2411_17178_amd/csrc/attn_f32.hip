@@ -4,12 +4,13 @@
 // and lane masks as the bf16 MFMA kernel, reading K and V rows straight from global
 // memory, with a scalar online softmax (Section 2 of the paper: softmax over the
 // kept keys only).
-#include "internal.h"
+#include "attn_bf16_common.h"
 
 namespace lv {
 
 __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a, int n_waves) {
   const int wv = blockIdx.x % n_waves, bh = blockIdx.x / n_waves;
+  if (!plan_usable(a.hdr)) return;
   const WaveDesc wd = a.waves[wv];
   if (wd.ny == 0) return;
   const int b = bh / a.H, h = bh % a.H;

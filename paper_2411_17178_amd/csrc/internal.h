@@ -40,6 +40,8 @@ struct AttnArgs {
   const int32_t* step_tok;
   int n_groups;
   int q_len;                     // query rows per (batch, head)
+  Header* hdr;                   // the blob's header: checked by every kernel before the plan is used
+  int spin_limit;                // polls after which a kernel's wait on an LDS flag gives up
 };
 
 litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);

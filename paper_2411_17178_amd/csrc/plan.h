@@ -74,11 +74,16 @@ struct Header {      // first 256 bytes of the blob
   int32_t n_groups, n_waves;
   int64_t n_steps, n_union, n_phase_entries;
   int64_t retained_pairs;
-  int32_t error;       // set by the builder when a capacity would be exceeded
+  int32_t error;       // kErrBuilder: set by the builder when a capacity would be exceeded (the
+                       // work-list sections are then not written and no kernel uses the plan);
+                       // kErrWaitGaveUp: an attention kernel's bounded wait on an LDS flag ran out
   int32_t pad0;
   uint64_t pad[24];
 };
 static_assert(sizeof(Header) == 256, "header size");
+
+enum HeaderError { kErrNone = 0, kErrBuilder = 1, kErrWaitGaveUp = 2 };
+constexpr int kDefaultSpinLimit = 1 << 22;   // polls of about 64 cycles each
 
 enum Section { kSecHeader = 0, kSecWin, kSecGroups, kSecWaves, kSecPhaseEnd, kSecUnion,
                kSecStepAddr, kSecStepMask, kSecStepTok, kSecEnd, kNumSections };
