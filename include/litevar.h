@@ -272,6 +272,25 @@ litevar_status litevar_peak_copy(const void* d_src, void* d_dst, size_t bytes, v
 litevar_status litevar_peak_read(const void* d_src, size_t bytes, void* d_out, void* stream);
 litevar_status litevar_peak_mfma_bf16(int32_t iters, void* d_out, double* flops, void* stream);
 
+/*
+ * litevar_window_calibrate for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, kernels and results as litevar_window_calibrate, but the
+ * per-workgroup partial sums live in an array that is part of the library's device image
+ * (LITEVAR_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of a caller's
+ * workspace.  Calls no allocating routine.  Problems whose partial sums
+ * (litevar_window_calibrate_workspace_bytes) exceed the array are rejected with
+ * LITEVAR_E_UNSUPPORTED before anything is launched (the 256x256 VAR scale list fits for
+ * up to 40 heads).  The first call on a device resolves the array's address
+ * (hipGetSymbolAddress); make that call outside a capture.  All calls on one GPU share the
+ * array: calls that overlap on one GPU (different streams) race; calls on one stream are
+ * ordered and need no clearing, since every partial sum that is read is written first.
+ */
+#define LITEVAR_STATIC_SCRATCH_BYTES (8u << 20)
+litevar_status litevar_window_calibrate_static(const int32_t* scales, int32_t n_scales,
+                                               const float* d_attn, int32_t N, int32_t H, float r0,
+                                               int32_t* d_radius, double* d_mass, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

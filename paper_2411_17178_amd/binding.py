@@ -71,7 +71,7 @@ def load_library():
                  "litevar_window_table_export", "litevar_mask_export_dense",
                  "litevar_mask_export_csr", "litevar_windowed_attn_fwd",
                  "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate",
-                 "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16"):
+                 "litevar_window_calibrate_static", "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16"):
         getattr(lib, name).restype = C.c_int32
     _lib = lib
     return lib
@@ -275,6 +275,27 @@ def litevar_window_calibrate(scales, attn_map, r0, with_mass=False, stream=None)
         C.c_void_p(radius.data_ptr()), C.c_void_p(mass.data_ptr()) if with_mass else None,
         _stream_handle(stream)))
     return (radius, mass) if with_mass else radius
+
+
+def litevar_window_calibrate_static(scales, attn_map, r0, radius, mass=None, stream=None):
+    """litevar_window_calibrate on the library's static scratch array: allocates nothing, the
+    caller brings the outputs `radius` [H, K, K] int32 and, optionally, `mass`
+    [H, K, K, smax] float64."""
+    lib = load_library()
+    assert attn_map.is_cuda and attn_map.dtype == torch.float32 and attn_map.is_contiguous()
+    N, H, L, L2 = attn_map.shape
+    K = len(scales)
+    assert L == L2 and radius.is_cuda and radius.dtype == torch.int32 and radius.shape == (H, K, K)
+    assert radius.is_contiguous()
+    if mass is not None:
+        assert mass.is_cuda and mass.dtype == torch.float64 and mass.is_contiguous()
+        assert mass.shape == (H, K, K, max(int(s) for s in scales))
+    sc = (C.c_int32 * K)(*[int(s) for s in scales])
+    _check(lib.litevar_window_calibrate_static(
+        sc, C.c_int32(K), C.c_void_p(attn_map.data_ptr()), C.c_int32(N), C.c_int32(H),
+        C.c_float(r0), C.c_void_p(radius.data_ptr()),
+        C.c_void_p(mass.data_ptr()) if mass is not None else None, _stream_handle(stream)))
+    return radius
 
 
 def litevar_peak_copy(src, dst, stream=None):

@@ -19,6 +19,8 @@
 // by prefix and picks the radius.
 #include "internal.h"
 
+#include <mutex>
+
 namespace lv {
 
 namespace {
@@ -171,6 +173,46 @@ size_t calib_workspace(const CalibArgs& a, int H) {
   return (size_t)H * a.K * a.K * a.splits * a.max_tiles * a.smax * sizeof(double);
 }
 
+litevar_status calibrate_with(CalibArgs& a, const float* d_attn, int32_t N, int32_t H, float r0,
+                              void* d_workspace, size_t workspace_bytes, int32_t* d_radius,
+                              double* d_mass, void* stream);
+
+litevar_status check_calib_args(const float* d_attn, int32_t N, int32_t H, float r0,
+                                const int32_t* d_radius, const double* d_mass) {
+  if (N < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "N and H must be positive");
+  if (!(r0 > 0.f) || r0 > 1.f) return fail(LITEVAR_E_INVALID_ARG, "r0 must be in (0, 1] (got %g)", r0);
+  if (!d_attn || !d_radius) return fail(LITEVAR_E_INVALID_ARG, "d_attn or d_radius is NULL");
+  if (d_mass && ((uintptr_t)d_mass & 7)) return fail(LITEVAR_E_INVALID_ARG, "d_mass must be 8-byte aligned");
+  return LITEVAR_OK;
+}
+
+// Scratch memory of litevar_window_calibrate_static, the entry point for callers that cannot
+// allocate: the per-workgroup partial sums live in this array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy, at its own address, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// kernels get the resolved device address as an argument like any other workspace.
+constexpr size_t kStaticScratchBytes = LITEVAR_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};       // resolved once per device, with that device current
+
+litevar_status static_scratch(void** out) {
+  int dev = -1;
+  if (litevar_status s = hip_check(hipGetDevice(&dev), "hipGetDevice")) return s;
+  if (dev < 0 || dev >= kMaxDevices) return fail(LITEVAR_E_UNSUPPORTED, "device index %d above %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (litevar_status s = hip_check(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return s;
+    if (!p) return fail(LITEVAR_E_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LITEVAR_OK;
+}
+
 }  // namespace
 
 }  // namespace lv
@@ -195,12 +237,36 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
                                         void* stream) {
   CalibArgs a;
   if (litevar_status s = calib_geom(scales, n_scales, a)) return s;
-  if (N < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "N and H must be positive");
-  if (!(r0 > 0.f) || r0 > 1.f) return fail(LITEVAR_E_INVALID_ARG, "r0 must be in (0, 1] (got %g)", r0);
-  if (!d_attn || !d_radius || !d_workspace)
-    return fail(LITEVAR_E_INVALID_ARG, "d_attn, d_radius or d_workspace is NULL");
-  if (((uintptr_t)d_workspace & 7) || (d_mass && ((uintptr_t)d_mass & 7)))
-    return fail(LITEVAR_E_INVALID_ARG, "d_workspace and d_mass must be 8-byte aligned");
+  return calibrate_with(a, d_attn, N, H, r0, d_workspace, workspace_bytes, d_radius, d_mass, stream);
+}
+
+litevar_status litevar_window_calibrate_static(const int32_t* scales, int32_t n_scales,
+                                               const float* d_attn, int32_t N, int32_t H, float r0,
+                                               int32_t* d_radius, double* d_mass, void* stream) {
+  CalibArgs a;
+  if (litevar_status s = calib_geom(scales, n_scales, a)) return s;
+  if (litevar_status s = check_calib_args(d_attn, N, H, r0, d_radius, d_mass)) return s;
+  const size_t need = calib_workspace(a, H);
+  if (need > kStaticScratchBytes)
+    return fail(LITEVAR_E_UNSUPPORTED, "the partial sums need %zu bytes, the library's static scratch "
+                "array holds %zu (LITEVAR_STATIC_SCRATCH_BYTES): use litevar_window_calibrate with a "
+                "caller-owned workspace", need, (size_t)kStaticScratchBytes);
+  void* ptr = nullptr;
+  if (litevar_status s = static_scratch(&ptr)) return s;
+  return calibrate_with(a, d_attn, N, H, r0, ptr, kStaticScratchBytes, d_radius, d_mass, stream);
+}
+
+}  // extern "C"
+
+namespace lv {
+namespace {
+
+litevar_status calibrate_with(CalibArgs& a, const float* d_attn, int32_t N, int32_t H, float r0,
+                              void* d_workspace, size_t workspace_bytes, int32_t* d_radius,
+                              double* d_mass, void* stream) {
+  if (litevar_status s = check_calib_args(d_attn, N, H, r0, d_radius, d_mass)) return s;
+  if (!d_workspace) return fail(LITEVAR_E_INVALID_ARG, "d_workspace is NULL");
+  if ((uintptr_t)d_workspace & 7) return fail(LITEVAR_E_INVALID_ARG, "d_workspace must be 8-byte aligned");
   if (workspace_bytes < calib_workspace(a, H))
     return fail(LITEVAR_E_INVALID_ARG, "workspace of %zu bytes, %zu needed", workspace_bytes,
                 calib_workspace(a, H));
@@ -215,4 +281,5 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
   return hip_check(hipGetLastError(), "calibration pick launch");
 }
 
-}  // extern "C"
+}  // namespace
+}  // namespace lv
