@@ -407,6 +407,96 @@ int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, 
   return LVO_OK;
 }
 
+/* ---- QKV8: attention on 8-bit Q, K, V (Section 4, "Quantization Scheme": min-max
+ * quantisation with dynamic parameters computed online from the data's maximum and
+ * minimum) ----
+ *
+ * The printed quantiser is x_q = round(clamp((x - z)/s, -2^(B-1), 2^(B-1))) with
+ * z = (max + min)/2 and a scale "s = max(abs(x))" that lacks the integer range, and a clamp
+ * whose upper bound is not a B-bit code.  Reading taken here (the usual min-max form with
+ * the paper's zero point): z = (max + min)/2, s = ((max - min)/2) / (2^(B-1) - 1), codes
+ * clamped to [-2^(B-1), 2^(B-1) - 1], rounding to nearest with ties to even; the
+ * dequantised value is s x_q + z.  Granularity (the paper does not state one): one (s, z)
+ * per token row of D values, computed from that row alone.  A constant row has s = 0: all
+ * codes are 0 and the row dequantises to z exactly.
+ *
+ * A code is an integer decided by a floating-point comparison; the decision is taken in
+ * binary32, in the order z = (max + min) * 0.5f, s = ((max - min) * 0.5f) / qmax,
+ * t = (x - z) / s, nearest-even, so that an implementation in that precision can produce
+ * the same codes bit for bit.  Everything after the codes is fp64. */
+int lvo_quantize_rows(const void* x, int32_t dtype, int64_t rows, int32_t D, int32_t bits,
+                      int32_t* codes, double* scale, double* zero) {
+  if (!x || !codes || !scale || !zero || rows < 0 || D < 1 || bits < 2 || bits > 16) return LVO_BAD_ARG;
+  if (dtype != LVO_F64 && dtype != LVO_F32 && dtype != LVO_BF16) return LVO_BAD_ARG;
+  const float qmax = (float)((1 << (bits - 1)) - 1), qmin = -(float)(1 << (bits - 1));
+  for (int64_t r = 0; r < rows; ++r) {
+    float mx = -INFINITY, mn = INFINITY;
+    for (int32_t d = 0; d < D; ++d) {
+      const float v = (float)load_elem(x, dtype, r * D + d);
+      if (v > mx) mx = v;
+      if (v < mn) mn = v;
+    }
+    const float z = (mx + mn) * 0.5f;
+    const float s = ((mx - mn) * 0.5f) / qmax;
+    for (int32_t d = 0; d < D; ++d) {
+      const float v = (float)load_elem(x, dtype, r * D + d);
+      float t = 0.0f;
+      if (s > 0.0f) {
+        t = (v - z) / s;
+        if (t < qmin) t = qmin;
+        if (t > qmax) t = qmax;
+        t = nearbyintf(t);               /* default rounding mode: nearest, ties to even */
+      }
+      codes[r * D + d] = (int32_t)t;
+    }
+    scale[r] = (double)s;
+    zero[r] = (double)z;
+  }
+  return LVO_OK;
+}
+
+/* s x_q + z, in fp64 */
+int lvo_dequantize_rows(const int32_t* codes, const double* scale, const double* zero,
+                        int64_t rows, int32_t D, double* out) {
+  if (!codes || !scale || !zero || !out || rows < 0 || D < 1) return LVO_BAD_ARG;
+  for (int64_t r = 0; r < rows; ++r)
+    for (int32_t d = 0; d < D; ++d) out[r * D + d] = scale[r] * (double)codes[r * D + d] + zero[r];
+  return LVO_OK;
+}
+
+/* Windowed attention with Q, K and V quantised to `bits` bits per token row and
+ * dequantised again (the arithmetic of the attention itself stays fp64): the result that an
+ * 8-bit Q/K/V implementation approximates.  Arguments as lvo_attn. */
+int lvo_attn_qkv8(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
+                  int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
+                  int32_t dtype, int32_t B, int32_t H, int32_t D, double sm_scale, int32_t bits,
+                  int64_t bh_begin, int64_t bh_end, double* out) {
+  if (check_desc(K, scales, radii, n_sink, qb, qe)) return LVO_BAD_ARG;
+  if (!q || !k || !v || !out || B < 1 || H < 1 || D < 1) return LVO_BAD_ARG;
+  const int64_t L = lvo_seq_len(K, scales);
+  const int64_t Lq = lvo_scale_offset(K, scales, qe) - lvo_scale_offset(K, scales, qb);
+  const int64_t nq = (int64_t)B * H * Lq, nk = (int64_t)B * H * L;
+  int32_t* codes = (int32_t*)malloc((size_t)(nk > nq ? nk : nq) * D * sizeof(int32_t));
+  double* sc = (double*)malloc((size_t)(nk > nq ? nk : nq) * sizeof(double));
+  double* zp = (double*)malloc((size_t)(nk > nq ? nk : nq) * sizeof(double));
+  double* qd = (double*)malloc((size_t)nq * D * sizeof(double));
+  double* kd = (double*)malloc((size_t)nk * D * sizeof(double));
+  double* vd = (double*)malloc((size_t)nk * D * sizeof(double));
+  int rc = LVO_NO_MEM;
+  if (codes && sc && zp && qd && kd && vd) {
+    rc = lvo_quantize_rows(q, dtype, nq, D, bits, codes, sc, zp);
+    if (!rc) rc = lvo_dequantize_rows(codes, sc, zp, nq, D, qd);
+    if (!rc) rc = lvo_quantize_rows(k, dtype, nk, D, bits, codes, sc, zp);
+    if (!rc) rc = lvo_dequantize_rows(codes, sc, zp, nk, D, kd);
+    if (!rc) rc = lvo_quantize_rows(v, dtype, nk, D, bits, codes, sc, zp);
+    if (!rc) rc = lvo_dequantize_rows(codes, sc, zp, nk, D, vd);
+    if (!rc) rc = lvo_attn(K, scales, radii, n_sink, qb, qe, qd, kd, vd, LVO_F64, B, H, D, sm_scale,
+                           0, NULL, bh_begin, bh_end, out);
+  }
+  free(codes); free(sc); free(zp); free(qd); free(kd); free(vd);
+  return rc;
+}
+
 int lvo_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -220,5 +220,56 @@ def calibrate(scales, p, r0, with_mass=False):
     return (radius, mass) if with_mass else radius
 
 
+def quantize_rows(x, bits=8):
+    """Section 4 min-max quantiser, one (scale, zero) per row of the last axis.
+    Returns (codes int32 like x, scale float64 [rows], zero float64 [rows])."""
+    x = np.ascontiguousarray(x)
+    code = _dtype_code(x)
+    D = x.shape[-1]
+    rows = x.size // D
+    codes = np.empty(x.shape, dtype=np.int32)
+    scale = np.empty(x.shape[:-1], dtype=np.float64)
+    zero = np.empty(x.shape[:-1], dtype=np.float64)
+    rc = _L().lvo_quantize_rows(_p(x), C.c_int32(code), C.c_int64(rows), C.c_int32(D),
+                                C.c_int32(bits), _p(codes), _p(scale), _p(zero))
+    if rc:
+        raise ValueError(f"lvo_quantize_rows failed: {rc}")
+    return codes, scale, zero
+
+
+def dequantize_rows(codes, scale, zero):
+    codes = np.ascontiguousarray(codes, dtype=np.int32)
+    scale = np.ascontiguousarray(scale, dtype=np.float64)
+    zero = np.ascontiguousarray(zero, dtype=np.float64)
+    D = codes.shape[-1]
+    out = np.empty(codes.shape, dtype=np.float64)
+    rc = _L().lvo_dequantize_rows(_p(codes), _p(scale), _p(zero), C.c_int64(codes.size // D),
+                                  C.c_int32(D), _p(out))
+    if rc:
+        raise ValueError(f"lvo_dequantize_rows failed: {rc}")
+    return out
+
+
+def attn_qkv8(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, bits=8, bh_range=None):
+    """fp64 windowed attention on Q, K, V quantised per token row to `bits` bits and
+    dequantised (Section 4).  Shapes as attn(); returns [B,H,Lq,D]."""
+    s, r = _i32(scales), _rtab(scales, radii)
+    qb, qe, Lq = _qrange(scales, q_scales)
+    q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
+    code = _dtype_code(q)
+    assert _dtype_code(k) == code and _dtype_code(v) == code
+    B, H, lq, D = q.shape
+    assert lq == Lq and k.shape == (B, H, seq_len(scales), D) and v.shape == k.shape
+    b0, b1 = (0, B * H) if bh_range is None else bh_range
+    out = np.zeros((B, H, Lq, D), dtype=np.float64)
+    rc = _L().lvo_attn_qkv8(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink), C.c_int32(qb),
+                            C.c_int32(qe), _p(q), _p(k), _p(v), C.c_int32(code), C.c_int32(B),
+                            C.c_int32(H), C.c_int32(D), C.c_double(sm_scale), C.c_int32(bits),
+                            C.c_int64(b0), C.c_int64(b1), _p(out))
+    if rc:
+        raise ValueError(f"lvo_attn_qkv8 failed: {rc}")
+    return out
+
+
 def num_threads():
     return int(_L().lvo_num_threads())

@@ -464,3 +464,50 @@ def test_random_configurations_sweep(lv):
         o = _gpu_attn(lv, plan, q, k, v, 0.125)
         ref = _oracle_attn(scales, radii, q, k, v, 0.125, n_sink, q_scales)
         assert _maxerr(o, ref) <= TOL[dtype], it
+
+
+# ---- failure handling: every kernel exits normally ----------------------------------------
+
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_zeroed_plan_makes_the_launch_a_no_op(lv, waves):
+    """a blob without the header's magic (zeroed, stale, half-built) is not walked: the
+    attention kernels return at once, the output is untouched, litevar_plan_check says so"""
+    w = workloads.get("var_d16")
+    for dtype in ("bf16", "f32"):
+        q, k, v = workloads.make_qkv(w.scales, 1, 2, 64, dtype, 3)
+        plan = _plan(lv, w, waves)
+        torch.cuda.synchronize()
+        plan.blob.zero_()
+        out = torch.full(q.shape, 7.0, dtype=q.dtype, device="cuda")
+        print(f"  zeroed plan: waves={waves} {dtype}", flush=True)
+        lv.litevar_windowed_attn_fwd(plan, q.cuda(), k.cuda(), v.cuda(), w.sm_scale, out=out)
+        torch.cuda.synchronize()
+        assert bool((out == 7.0).all())
+        with pytest.raises(lv.LitevarError) as e:
+            lv.litevar_plan_check(plan)
+        assert e.value.status == -5
+
+
+@pytest.mark.parametrize("waves", [4, 8])
+def test_bounded_wait_gives_up_and_reports(lv, waves):
+    """with a spin limit of one poll the compute waves' first wait for the loader runs out:
+    the launch still ends (every wave exits normally), the plan's header carries the mark
+    and litevar_plan_check reports it; a plan with the default limit is unaffected"""
+    w = workloads.get("var_d16")
+    q, k, v = workloads.make_qkv(w.scales, 1, 2, 64, "bf16", 3)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    good = _plan(lv, w, waves)
+    want = lv.litevar_windowed_attn_fwd(good, qd, kd, vd, w.sm_scale)
+    tiny = lv.litevar_mask_build(w.scales, w.radius, None, w.n_sink, w.q_scales,
+                                 waves_per_group=waves, spin_limit=1)
+    lv.litevar_plan_check(tiny)
+    print(f"  spin limit 1: waves={waves}", flush=True)
+    lv.litevar_windowed_attn_fwd(tiny, qd, kd, vd, w.sm_scale)
+    torch.cuda.synchronize()
+    with pytest.raises(lv.LitevarError) as e:
+        lv.litevar_plan_check(tiny)
+    assert e.value.status == -5 and "gave up" in str(e.value)
+    lv.litevar_plan_check(good)
+    again = lv.litevar_windowed_attn_fwd(good, qd, kd, vd, w.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(want, again)

@@ -15,6 +15,7 @@ import oracle
 import oracle.oracle as front
 import test_oracle_calibrate_pins as cal_pins
 import test_oracle_pins as pins
+import test_oracle_qkv8_pins as q8_pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "litevar_oracle.c")
 
@@ -70,6 +71,26 @@ MISTAKES = [
      [("if (found < 0 && (all == 0.0 || in / all >= r0)) found = r;",
        "if (found < 0 && (all == 0.0 || in / (all + 1.0) >= r0)) found = r;")],
      cal_pins.test_split_mass_between_centre_and_ring),
+    ("quantiser scale as printed (no integer range)",
+     [("const float s = ((mx - mn) * 0.5f) / qmax;", "const float s = fmaxf(fabsf(mx), fabsf(mn));")],
+     q8_pins.test_hand_derived_rows),
+    ("quantiser without the zero point",
+     [("const float z = (mx + mn) * 0.5f;", "const float z = 0.0f * (mx + mn);")],
+     q8_pins.test_hand_derived_rows),
+    ("quantiser rounds half away from zero",
+     [("t = nearbyintf(t);", "t = roundf(t);")],
+     q8_pins.test_hand_derived_rows),
+    ("quantiser truncates",
+     [("t = nearbyintf(t);", "t = truncf(t);")],
+     q8_pins.test_code_range_extremes_and_round_trip_bound),
+    ("dequantisation forgets the zero point",
+     [("out[r * D + d] = scale[r] * (double)codes[r * D + d] + zero[r];",
+       "out[r * D + d] = scale[r] * (double)codes[r * D + d];")],
+     q8_pins.test_constant_value_rows_are_exact),
+    ("quantised attention leaves V unquantised",
+     [("if (!rc) rc = lvo_dequantize_rows(codes, sc, zp, nk, D, vd);",
+       "if (!rc) for (int64_t i = 0; i < nk * D; ++i) vd[i] = load_elem(v, dtype, i);")],
+     q8_pins.test_quantised_attention_is_attention_of_the_dequantised_tensors_and_close_to_plain),
     ("calibration window one key too wide",
      [("for (int32_t i = 0; i < K * K; ++i) rad[i] = r;", "for (int32_t i = 0; i < K * K; ++i) rad[i] = r + 1;")],
      lambda: cal_pins.test_mass_at_a_known_distance_from_the_centre(1)),
