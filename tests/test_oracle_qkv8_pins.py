@@ -134,8 +134,10 @@ def test_constant_value_rows_are_exact():
     scales = (1, 2, 3)
     q = np.random.default_rng(1).standard_normal((1, 1, 14, 64)).astype(np.float32)
     k = np.random.default_rng(2).standard_normal((1, 1, 14, 64)).astype(np.float32)
-    v = np.repeat(np.arange(14, dtype=np.float32)[None, None, :, None], 64, axis=3)
+    v = np.repeat(np.arange(1, 15, dtype=np.float32)[None, None, :, None], 64, axis=3)
     out = oracle.attn_qkv8(scales, [-1] * 3, q, k, v, 0.125)
-    # every V row is constant: it dequantises exactly, so each output row is constant too and
-    # the first token (which sees only itself) returns V[0] = 0
-    assert np.abs(out - out[..., :1]).max() < 1e-12 and np.abs(out[0, 0, 0]).max() == 0.0
+    # every V row is constant: it dequantises exactly (to its zero point), so each output row
+    # is constant too, lies between the smallest and largest value it can see, and the first
+    # token (which sees only itself) returns V[0] = 1
+    assert np.abs(out - out[..., :1]).max() < 1e-12 and np.all(out[0, 0, 0] == 1.0)
+    assert np.all(out[0, 0, 1:5] >= 1.0) and np.all(out[0, 0, 1:5] <= 5.0)
