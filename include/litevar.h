@@ -259,6 +259,46 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
                                         int32_t* d_radius, double* d_mass, void* stream);
 
 /*
+ * QKV8 (Section 4, "Quantization Scheme": min-max quantisation of Q, K and V to 8-bit
+ * integers with dynamic parameters computed online from the data's maximum and minimum).
+ * One (scale s, zero point z) per token row of D = 64 values:
+ *   z = (max + min)/2,  s = ((max - min)/2) / 127,  code = rne(clamp((x - z)/s, -128, 127)),
+ *   dequantised value = s * code + z   (a constant row has s = 0 and codes 0).
+ * The printed formula's scale lacks the integer range and its clamp's upper bound is not an
+ * 8-bit code; this is the repaired min-max form with the paper's zero point.  Codes are
+ * decided in binary32 in the order written above.
+ *
+ * litevar_qkv8_quantize    d_x DEVICE bf16 or fp32 [rows][row_stride >= 64] (16-byte aligned
+ *                          rows), d_codes DEVICE int8 [rows][64], d_scale_zero DEVICE float
+ *                          [rows][2] = (s, z) per row.
+ * litevar_qkv8_dequantize  d_out_bf16 DEVICE bf16 [rows][64] = bf16(s * code + z).
+ * litevar_windowed_attn_qkv8_fwd
+ *                          litevar_windowed_attn_fwd on 8-bit operands: d_q int8
+ *                          [B,H,q_len,64] with d_q_sz float [B,H,q_len,2], d_k / d_v int8
+ *                          [B,H,kv_len,64] with their (s, z); all packed.  d_o DEVICE bf16
+ *                          [B,H,q_len,64].  The operands are dequantised once into
+ *                          d_workspace (DEVICE, 256-byte aligned,
+ *                          litevar_windowed_attn_qkv8_workspace_bytes() bytes, contents
+ *                          undefined before and after) and the bf16 kernels run on that copy:
+ *                          results equal attention on the dequantised tensors up to their
+ *                          rounding to bf16 and the bf16 path's own rounding.  Other arguments
+ *                          as litevar_windowed_attn_fwd.  Asynchronous on `stream`.
+ */
+litevar_status litevar_qkv8_quantize(const void* d_x, litevar_dtype dt, int64_t rows, int64_t row_stride,
+                                     int32_t D, int8_t* d_codes, float* d_scale_zero, void* stream);
+litevar_status litevar_qkv8_dequantize(const int8_t* d_codes, const float* d_scale_zero, int64_t rows,
+                                       int32_t D, void* d_out_bf16, void* stream);
+litevar_status litevar_windowed_attn_qkv8_workspace_bytes(const litevar_plan* plan, int32_t B, int32_t H,
+                                                          size_t* out_bytes);
+litevar_status litevar_windowed_attn_qkv8_fwd(const litevar_plan* plan, const int8_t* d_q,
+                                              const float* d_q_sz, const int8_t* d_k,
+                                              const float* d_k_sz, const int8_t* d_v,
+                                              const float* d_v_sz, void* d_o, int32_t B, int32_t H,
+                                              int32_t D, float sm_scale, const uint8_t* d_cfg_share,
+                                              uint32_t flags, void* d_workspace, size_t workspace_bytes,
+                                              void* stream);
+
+/*
  * Diagnostics for benchmark reports (measurement, Section 4's efficiency figures are quoted
  * against what the hardware delivers): litevar_peak_copy enqueues a streaming copy of `bytes`
  * bytes (DEVICE pointers, 16-byte aligned, size a multiple of 16; HBM traffic = 2 x bytes);

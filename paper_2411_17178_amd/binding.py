@@ -71,7 +71,9 @@ def load_library():
                  "litevar_window_table_export", "litevar_mask_export_dense",
                  "litevar_mask_export_csr", "litevar_windowed_attn_fwd",
                  "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate",
-                 "litevar_window_calibrate_static", "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16"):
+                 "litevar_window_calibrate_static", "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16", "litevar_qkv8_quantize",
+                 "litevar_qkv8_dequantize", "litevar_windowed_attn_qkv8_workspace_bytes",
+                 "litevar_windowed_attn_qkv8_fwd"):
         getattr(lib, name).restype = C.c_int32
     _lib = lib
     return lib
@@ -296,6 +298,63 @@ def litevar_window_calibrate_static(scales, attn_map, r0, radius, mass=None, str
         C.c_float(r0), C.c_void_p(radius.data_ptr()),
         C.c_void_p(mass.data_ptr()) if mass is not None else None, _stream_handle(stream)))
     return radius
+
+
+def litevar_qkv8_quantize(x, stream=None):
+    """Per-token 8-bit min-max quantisation of x [..., 64] (bf16 or fp32 CUDA tensor, packed):
+    returns (codes int8 like x, scale_zero float32 [..., 2])."""
+    assert x.is_cuda and x.is_contiguous() and x.shape[-1] == 64
+    dt = {torch.bfloat16: DT_BF16, torch.float32: DT_F32}[x.dtype]
+    rows = x.numel() // 64
+    codes = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    sz = torch.empty(x.shape[:-1] + (2,), dtype=torch.float32, device=x.device)
+    _check(load_library().litevar_qkv8_quantize(
+        C.c_void_p(x.data_ptr()), C.c_int32(dt), C.c_int64(rows), C.c_int64(64), C.c_int32(64),
+        C.c_void_p(codes.data_ptr()), C.c_void_p(sz.data_ptr()), _stream_handle(stream)))
+    return codes, sz
+
+
+def litevar_qkv8_dequantize(codes, scale_zero, stream=None):
+    assert codes.is_cuda and codes.dtype == torch.int8 and codes.is_contiguous() and codes.shape[-1] == 64
+    assert scale_zero.is_cuda and scale_zero.dtype == torch.float32 and scale_zero.is_contiguous()
+    assert scale_zero.shape == codes.shape[:-1] + (2,)
+    out = torch.empty(codes.shape, dtype=torch.bfloat16, device=codes.device)
+    _check(load_library().litevar_qkv8_dequantize(
+        C.c_void_p(codes.data_ptr()), C.c_void_p(scale_zero.data_ptr()), C.c_int64(codes.numel() // 64),
+        C.c_int32(64), C.c_void_p(out.data_ptr()), _stream_handle(stream)))
+    return out
+
+
+def litevar_windowed_attn_qkv8_fwd(plan, q8, q_sz, k8, k_sz, v8, v_sz, sm_scale, out=None,
+                                   cfg_share=None, workspace=None, stream=None):
+    """Windowed attention on 8-bit Q, K, V (codes int8 [B,H,L,64] + (scale, zero) float32
+    [B,H,L,2], as litevar_qkv8_quantize returns them); output bf16 [B,H,q_len,64]."""
+    lib = load_library()
+    B, H, Lq, D = q8.shape
+    for t, sz in ((q8, q_sz), (k8, k_sz), (v8, v_sz)):
+        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous()
+        assert sz.is_cuda and sz.dtype == torch.float32 and sz.is_contiguous() and sz.shape == t.shape[:-1] + (2,)
+    assert Lq == plan.q_len and k8.shape == (B, H, plan.kv_len, D) and v8.shape == k8.shape
+    n = C.c_size_t(0)
+    _check(lib.litevar_windowed_attn_qkv8_workspace_bytes(C.byref(plan.handle), C.c_int32(B), C.c_int32(H), C.byref(n)))
+    if workspace is None:
+        workspace = torch.empty(n.value, dtype=torch.uint8, device=q8.device)
+    assert workspace.is_cuda and workspace.numel() * workspace.element_size() >= n.value
+    if out is None:
+        out = torch.empty(q8.shape, dtype=torch.bfloat16, device=q8.device)
+    assert out.dtype == torch.bfloat16 and out.shape == q8.shape and out.is_contiguous()
+    flags, share_ptr = 0, None
+    if cfg_share is not None:
+        assert cfg_share.is_cuda and cfg_share.dtype == torch.uint8 and cfg_share.is_contiguous()
+        assert cfg_share.shape == (H, plan.n_scales)
+        flags, share_ptr = FLAG_CFG_SHARE, C.c_void_p(cfg_share.data_ptr())
+    _check(lib.litevar_windowed_attn_qkv8_fwd(
+        C.byref(plan.handle), C.c_void_p(q8.data_ptr()), C.c_void_p(q_sz.data_ptr()),
+        C.c_void_p(k8.data_ptr()), C.c_void_p(k_sz.data_ptr()), C.c_void_p(v8.data_ptr()),
+        C.c_void_p(v_sz.data_ptr()), C.c_void_p(out.data_ptr()), C.c_int32(B), C.c_int32(H), C.c_int32(D),
+        C.c_float(sm_scale), share_ptr, C.c_uint32(flags), C.c_void_p(workspace.data_ptr()),
+        C.c_size_t(workspace.numel() * workspace.element_size()), _stream_handle(stream)))
+    return out
 
 
 def litevar_peak_copy(src, dst, stream=None):
