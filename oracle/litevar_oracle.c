@@ -27,6 +27,15 @@
  *   - tokens of a scale are stored row-major (y major, x minor);
  *   - masking happens before the softmax, so kept weights renormalise to 1;
  *   - CFG layout: batch rows [0, B/2) conditional, b + B/2 the partner.
+ * A second reading of the window, mode LVO_BAND (Section 2, step (2), taken
+ * literally): the attention map of query scale k, [s_k^2, sum_{i<=k} s_i^2], is
+ * cut into parts -- the first spans the first three key scales (those of them the
+ * query sees), every later key scale is a part -- and in a part of n columns the
+ * query with flattened index i keeps the columns within radius r of the part's
+ * diagonal, floor((2i+1) n / (2 s_k^2)).  The radius of a part is the table entry
+ * of its last key scale; a part whose last key scale is below n_sink stays dense.
+ * Section 2, step (3) determines the window size for each scale, part and head:
+ * the attention functions take one radius table per head when asked to.
  *
  * Parity pins live in tests/ (golden worked example, closed-form pair
  * counts, brute force in numpy, reduction to dense scaled-dot-product
@@ -46,6 +55,7 @@
 #define LVO_CAP (-3)
 
 enum { LVO_F64 = 0, LVO_F32 = 1, LVO_BF16 = 2 };
+enum { LVO_WINDOW = 0, LVO_BAND = 1 };
 
 /* ---- geometry (Section 2: scale k has s_k^2 tokens) -------------------- */
 
@@ -85,7 +95,43 @@ int lvo_token_coords(int32_t K, const int32_t* scales, int64_t t,
  * radius of part j of query scale k's attention map (Section 2, step (3): the
  * window size is determined for each scale and part); < 0 means "no window in
  * that part". */
+/* The band reading (LVO_BAND): parts, and a band around each part's diagonal. */
+static int allowed_band(int32_t K, const int32_t* scales, const int32_t* radii,
+                        int32_t n_sink, int32_t qk, int32_t qy, int32_t qx,
+                        int32_t kj, int32_t ky, int32_t kx) {
+  if (kj > qk) return 0;                 /* block-causal across scales */
+  /* the part that key scale kj belongs to: key scales [first, last] */
+  int32_t first = kj < 3 ? 0 : kj;
+  int32_t last = kj < 3 ? (qk < 2 ? qk : 2) : kj;
+  if (last < n_sink) return 1;           /* leading parts kept dense */
+  int32_t r = radii[(int64_t)qk * K + last];
+  if (r < 0) return 1;                   /* dense part */
+  int64_t n = 0, col = 0;                /* columns of the part; this key's column in it */
+  for (int32_t i = first; i <= last; ++i) {
+    if (i < kj) col += (int64_t)scales[i] * scales[i];
+    n += (int64_t)scales[i] * scales[i];
+  }
+  col += (int64_t)ky * scales[kj] + kx;
+  int64_t nk = (int64_t)scales[qk] * scales[qk];
+  int64_t i = (int64_t)qy * scales[qk] + qx;
+  int64_t c = ((2 * i + 1) * n) / (2 * nk);     /* the part's diagonal at row i */
+  int64_t d = col - c;
+  if (d < 0) d = -d;
+  return d <= r;
+}
+
+static int allowed_window(int32_t K, const int32_t* scales, const int32_t* radii,
+                          int32_t n_sink, int32_t qk, int32_t qy, int32_t qx,
+                          int32_t kj, int32_t ky, int32_t kx);
+
 static int allowed_coords(int32_t K, const int32_t* scales, const int32_t* radii,
+                          int32_t n_sink, int32_t mode, int32_t qk, int32_t qy, int32_t qx,
+                          int32_t kj, int32_t ky, int32_t kx) {
+  if (mode == LVO_BAND) return allowed_band(K, scales, radii, n_sink, qk, qy, qx, kj, ky, kx);
+  return allowed_window(K, scales, radii, n_sink, qk, qy, qx, kj, ky, kx);
+}
+
+static int allowed_window(int32_t K, const int32_t* scales, const int32_t* radii,
                           int32_t n_sink, int32_t qk, int32_t qy, int32_t qx,
                           int32_t kj, int32_t ky, int32_t kx) {
   if (kj > qk) return 0;                 /* block-causal across scales */
@@ -103,11 +149,11 @@ static int allowed_coords(int32_t K, const int32_t* scales, const int32_t* radii
 
 /* allowed(q, t) on flattened token indices of the full sequence */
 int lvo_allowed(int32_t K, const int32_t* scales, const int32_t* radii,
-                int32_t n_sink, int64_t tq, int64_t tk) {
+                int32_t n_sink, int32_t mode, int64_t tq, int64_t tk) {
   int32_t qk, qy, qx, kj, ky, kx;
   if (lvo_token_coords(K, scales, tq, &qk, &qy, &qx) != LVO_OK) return LVO_BAD_ARG;
   if (lvo_token_coords(K, scales, tk, &kj, &ky, &kx) != LVO_OK) return LVO_BAD_ARG;
-  return allowed_coords(K, scales, radii, n_sink, qk, qy, qx, kj, ky, kx);
+  return allowed_coords(K, scales, radii, n_sink, mode, qk, qy, qx, kj, ky, kx);
 }
 
 typedef struct { int32_t k, y, x; } coord_t;
@@ -131,7 +177,7 @@ static int check_desc(int32_t K, const int32_t* scales, const int32_t* radii,
 /* ---- masks and index sets --------------------------------------------- */
 
 /* dense byte mask [Lq][L]; rows are the queries of scales [qb, qe) */
-int lvo_mask_dense(int32_t K, const int32_t* scales, const int32_t* radii,
+int lvo_mask_dense(int32_t K, const int32_t* scales, const int32_t* radii, int32_t mode,
                    int32_t n_sink, int32_t qb, int32_t qe, uint8_t* mask) {
   if (check_desc(K, scales, radii, n_sink, qb, qe) || !mask) return LVO_BAD_ARG;
   int64_t L = lvo_seq_len(K, scales);
@@ -142,13 +188,13 @@ int lvo_mask_dense(int32_t K, const int32_t* scales, const int32_t* radii,
   for (int64_t q = q0; q < q1; ++q)
     for (int64_t t = 0; t < L; ++t)
       mask[(q - q0) * L + t] = (uint8_t)allowed_coords(
-          K, scales, radii, n_sink, c[q].k, c[q].y, c[q].x, c[t].k, c[t].y, c[t].x);
+          K, scales, radii, n_sink, mode, c[q].k, c[q].y, c[q].x, c[t].k, c[t].y, c[t].x);
   free(c);
   return LVO_OK;
 }
 
 /* per-query count of allowed keys: counts[Lq] */
-int lvo_row_counts(int32_t K, const int32_t* scales, const int32_t* radii,
+int lvo_row_counts(int32_t K, const int32_t* scales, const int32_t* radii, int32_t mode,
                    int32_t n_sink, int32_t qb, int32_t qe, int64_t* counts) {
   if (check_desc(K, scales, radii, n_sink, qb, qe) || !counts) return LVO_BAD_ARG;
   int64_t L = lvo_seq_len(K, scales);
@@ -159,7 +205,7 @@ int lvo_row_counts(int32_t K, const int32_t* scales, const int32_t* radii,
   for (int64_t q = q0; q < q1; ++q) {
     int64_t n = 0;
     for (int64_t t = 0; t < L; ++t)
-      n += allowed_coords(K, scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
+      n += allowed_coords(K, scales, radii, n_sink, mode, c[q].k, c[q].y, c[q].x,
                           c[t].k, c[t].y, c[t].x);
     counts[q - q0] = n;
   }
@@ -169,7 +215,7 @@ int lvo_row_counts(int32_t K, const int32_t* scales, const int32_t* radii,
 
 /* ascending index sets in CSR form: rowptr[Lq+1] (caller-filled from
  * lvo_row_counts by prefix sum), cols[rowptr[Lq]] */
-int lvo_index_sets(int32_t K, const int32_t* scales, const int32_t* radii,
+int lvo_index_sets(int32_t K, const int32_t* scales, const int32_t* radii, int32_t mode,
                    int32_t n_sink, int32_t qb, int32_t qe,
                    const int64_t* rowptr, int32_t* cols, int64_t cols_cap) {
   if (check_desc(K, scales, radii, n_sink, qb, qe) || !rowptr || !cols) return LVO_BAD_ARG;
@@ -183,7 +229,7 @@ int lvo_index_sets(int32_t K, const int32_t* scales, const int32_t* radii,
   for (int64_t q = q0; q < q1; ++q) {
     int64_t w = rowptr[q - q0];
     for (int64_t t = 0; t < L; ++t)
-      if (allowed_coords(K, scales, radii, n_sink, c[q].k, c[q].y, c[q].x,
+      if (allowed_coords(K, scales, radii, n_sink, mode, c[q].k, c[q].y, c[q].x,
                          c[t].k, c[t].y, c[t].x)) {
         if (w < rowptr[q - q0 + 1]) cols[w] = (int32_t)t;
         ++w;
@@ -215,12 +261,12 @@ static double load_elem(const void* p, int32_t dtype, int64_t i) {
  * receives the normalised weights, 0 for masked keys.
  */
 static int attn_row(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
-                    const coord_t* c, int64_t L, int64_t tq,
+                    int32_t mode, const coord_t* c, int64_t L, int64_t tq,
                     const double* qrow, const double* Kd, const double* Vd,
                     int32_t D, double sm_scale, double* z, double* out, double* probs) {
   double m = -INFINITY;
   for (int64_t t = 0; t < L; ++t) {
-    if (!allowed_coords(K, scales, radii, n_sink, c[tq].k, c[tq].y, c[tq].x,
+    if (!allowed_coords(K, scales, radii, n_sink, mode, c[tq].k, c[tq].y, c[tq].x,
                         c[t].k, c[t].y, c[t].x)) { z[t] = NAN; continue; }
     double s = 0.0;
     for (int32_t d = 0; d < D; ++d) s += qrow[d] * Kd[t * D + d];
@@ -245,8 +291,11 @@ static int attn_row(int32_t K, const int32_t* scales, const int32_t* radii, int3
  * rows: optional list of n_rows query indices local to [0, Lq) (NULL = all);
  * out: [B,H,n_rows,D] fp64.  bh_begin/bh_end restrict the (b*H+h) range
  * (used to time or check a sample); rows outside it are left untouched.
+ * mode: LVO_WINDOW or LVO_BAND.  radii: one [K][K] table, or, when radii_per_head is
+ * non-zero, one per head, [H][K][K].
  */
 int lvo_attn(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
+             int32_t mode, int32_t radii_per_head,
              int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
              int32_t dtype, int32_t B, int32_t H, int32_t D, double sm_scale,
              int64_t n_rows, const int64_t* rows, int64_t bh_begin, int64_t bh_end,
@@ -287,7 +336,9 @@ int lvo_attn(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_s
           int64_t ql = rows ? rows[r] : r;
           for (int32_t d = 0; d < D; ++d)
             qrow[d] = load_elem(q, dtype, (bh * Lq + ql) * D + d);
-          attn_row(K, scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
+          /* Section 2, step (3): head h may have a radius table of its own, [H][K][K] */
+          const int32_t* rad_h = radii_per_head ? radii + (bh % H) * (int64_t)K * K : radii;
+          attn_row(K, scales, rad_h, n_sink, mode, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
                    z, out + (bh * n_rows + r) * D, NULL);
         }
       }
@@ -300,7 +351,7 @@ int lvo_attn(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_s
 
 /* normalised weights of one (b,h,query) over all L keys: probs[L] fp64 */
 int lvo_attn_probs(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
-                   int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
+                   int32_t mode, int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
                    int32_t dtype, int32_t B, int32_t H, int32_t D, double sm_scale,
                    int64_t bh, int64_t ql, double* probs, double* out_row) {
   if (check_desc(K, scales, radii, n_sink, qb, qe)) return LVO_BAD_ARG;
@@ -321,7 +372,7 @@ int lvo_attn_probs(int32_t K, const int32_t* scales, const int32_t* radii, int32
       Vd[i] = load_elem(v, dtype, bh * L * D + i);
     }
     for (int32_t d = 0; d < D; ++d) qrow[d] = load_elem(q, dtype, (bh * Lq + ql) * D + d);
-    rc = attn_row(K, scales, radii, n_sink, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
+    rc = attn_row(K, scales, radii, n_sink, mode, c, L, q0 + ql, qrow, Kd, Vd, D, sm_scale,
                   z, out_row, probs);
   }
   free(c); free(Kd); free(Vd); free(z); free(qrow);
@@ -395,7 +446,7 @@ int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, 
                     const int64_t q = oq + (int64_t)qy * sk + qx, t = ok + (int64_t)ky * sj + kx;
                     const double v = p[(((int64_t)n * H + h) * L + q) * L + t];
                     all += v;
-                    if (allowed_coords(K, scales, rad, 0, k, qy, qx, j, ky, kx)) in += v;
+                    if (allowed_coords(K, scales, rad, 0, LVO_WINDOW, k, qy, qx, j, ky, kx)) in += v;
                   }
           if (mout) mout[r] = in;
           if (found < 0 && (all == 0.0 || in / all >= r0)) found = r;
@@ -468,7 +519,7 @@ int lvo_dequantize_rows(const int32_t* codes, const double* scale, const double*
  * dequantised again (the arithmetic of the attention itself stays fp64): the result that an
  * 8-bit Q/K/V implementation approximates.  Arguments as lvo_attn. */
 int lvo_attn_qkv8(int32_t K, const int32_t* scales, const int32_t* radii, int32_t n_sink,
-                  int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
+                  int32_t mode, int32_t qb, int32_t qe, const void* q, const void* k, const void* v,
                   int32_t dtype, int32_t B, int32_t H, int32_t D, double sm_scale, int32_t bits,
                   int64_t bh_begin, int64_t bh_end, double* out) {
   if (check_desc(K, scales, radii, n_sink, qb, qe)) return LVO_BAD_ARG;
@@ -490,7 +541,7 @@ int lvo_attn_qkv8(int32_t K, const int32_t* scales, const int32_t* radii, int32_
     if (!rc) rc = lvo_dequantize_rows(codes, sc, zp, nk, D, kd);
     if (!rc) rc = lvo_quantize_rows(v, dtype, nk, D, bits, codes, sc, zp);
     if (!rc) rc = lvo_dequantize_rows(codes, sc, zp, nk, D, vd);
-    if (!rc) rc = lvo_attn(K, scales, radii, n_sink, qb, qe, qd, kd, vd, LVO_F64, B, H, D, sm_scale,
+    if (!rc) rc = lvo_attn(K, scales, radii, n_sink, mode, 0, qb, qe, qd, kd, vd, LVO_F64, B, H, D, sm_scale,
                            0, NULL, bh_begin, bh_end, out);
   }
   free(codes); free(sc); free(zp); free(qd); free(kd); free(vd);

@@ -74,9 +74,9 @@ def token_coords(scales, t):
     return k.value, y.value, x.value
 
 
-def allowed(scales, radii, n_sink, tq, tk):
+def allowed(scales, radii, n_sink, tq, tk, mode=0):
     s, r = _i32(scales), _rtab(scales, radii)
-    rc = _L().lvo_allowed(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+    rc = _L().lvo_allowed(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink), C.c_int32(mode),
                           C.c_int64(tq), C.c_int64(tk))
     if rc < 0:
         raise ValueError("token out of range")
@@ -90,37 +90,38 @@ def _qrange(scales, q_scales):
     return qb, qe, off[qe] - off[qb]
 
 
-def mask_dense(scales, radii, n_sink=0, q_scales=None):
+def mask_dense(scales, radii, n_sink=0, q_scales=None, mode=0):
+    """mode 0: square window in the key scale's grid; mode 1: band around each part's diagonal"""
     s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     m = np.empty((Lq, seq_len(scales)), dtype=np.uint8)
-    rc = _L().lvo_mask_dense(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+    rc = _L().lvo_mask_dense(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(mode), C.c_int32(n_sink),
                              C.c_int32(qb), C.c_int32(qe), _p(m))
     if rc:
         raise ValueError(f"lvo_mask_dense failed: {rc}")
     return m
 
 
-def row_counts(scales, radii, n_sink=0, q_scales=None):
+def row_counts(scales, radii, n_sink=0, q_scales=None, mode=0):
     s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     cnt = np.empty(Lq, dtype=np.int64)
-    rc = _L().lvo_row_counts(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+    rc = _L().lvo_row_counts(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(mode), C.c_int32(n_sink),
                              C.c_int32(qb), C.c_int32(qe), _p(cnt))
     if rc:
         raise ValueError(f"lvo_row_counts failed: {rc}")
     return cnt
 
 
-def index_sets(scales, radii, n_sink=0, q_scales=None):
+def index_sets(scales, radii, n_sink=0, q_scales=None, mode=0):
     """(rowptr[Lq+1] int64, cols int32): ascending allowed keys of every query."""
     s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
-    cnt = row_counts(scales, radii, n_sink, q_scales)
+    cnt = row_counts(scales, radii, n_sink, q_scales, mode)
     rowptr = np.zeros(Lq + 1, dtype=np.int64)
     np.cumsum(cnt, out=rowptr[1:])
     cols = np.empty(int(rowptr[-1]), dtype=np.int32)
-    rc = _L().lvo_index_sets(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+    rc = _L().lvo_index_sets(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(mode), C.c_int32(n_sink),
                              C.c_int32(qb), C.c_int32(qe), _p(rowptr), _p(cols),
                              C.c_int64(cols.size))
     if rc:
@@ -139,9 +140,17 @@ def _dtype_code(a):
 
 
 def attn(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, rows=None,
-         bh_range=None):
-    """fp64 windowed attention.  q [B,H,Lq,D]; k,v [B,H,L,D]; returns [B,H,n_rows,D]."""
-    s, r = _i32(scales), _rtab(scales, radii)
+         bh_range=None, mode=0):
+    """fp64 windowed attention.  q [B,H,Lq,D]; k,v [B,H,L,D]; returns [B,H,n_rows,D].
+    radii: [K], [K][K], or one table per head [H][K][K]."""
+    s = _i32(scales)
+    rr = np.asarray(radii, dtype=np.int32)
+    per_head = rr.ndim == 3
+    if per_head:
+        assert rr.shape == (q.shape[1], len(s), len(s))
+        r = np.ascontiguousarray(rr)
+    else:
+        r = _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
     q, k, v = (np.ascontiguousarray(a) for a in (q, k, v))
     code = _dtype_code(q)
@@ -156,6 +165,7 @@ def attn(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, rows=None,
     b0, b1 = (0, B * H) if bh_range is None else bh_range
     out = np.zeros((B, H, n_rows, D), dtype=np.float64)
     rc = _L().lvo_attn(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+                       C.c_int32(mode), C.c_int32(1 if per_head else 0),
                        C.c_int32(qb), C.c_int32(qe), _p(q), _p(k), _p(v),
                        C.c_int32(code), C.c_int32(B), C.c_int32(H), C.c_int32(D),
                        C.c_double(sm_scale), C.c_int64(n_rows),
@@ -166,7 +176,7 @@ def attn(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, rows=None,
     return out
 
 
-def attn_probs(scales, radii, q, k, v, sm_scale, bh, ql, n_sink=0, q_scales=None):
+def attn_probs(scales, radii, q, k, v, sm_scale, bh, ql, n_sink=0, q_scales=None, mode=0):
     """(probs[L], out[D]) of one (b*H+h, local query) pair, fp64."""
     s, r = _i32(scales), _rtab(scales, radii)
     qb, qe, Lq = _qrange(scales, q_scales)
@@ -175,7 +185,7 @@ def attn_probs(scales, radii, q, k, v, sm_scale, bh, ql, n_sink=0, q_scales=None
     B, H, lq, D = q.shape
     probs = np.zeros(seq_len(scales), dtype=np.float64)
     out = np.zeros(D, dtype=np.float64)
-    rc = _L().lvo_attn_probs(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink),
+    rc = _L().lvo_attn_probs(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink), C.c_int32(mode),
                              C.c_int32(qb), C.c_int32(qe), _p(q), _p(k), _p(v),
                              C.c_int32(code), C.c_int32(B), C.c_int32(H), C.c_int32(D),
                              C.c_double(sm_scale), C.c_int64(bh), C.c_int64(ql),
@@ -250,7 +260,8 @@ def dequantize_rows(codes, scale, zero):
     return out
 
 
-def attn_qkv8(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, bits=8, bh_range=None):
+def attn_qkv8(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, bits=8, bh_range=None,
+              mode=0):
     """fp64 windowed attention on Q, K, V quantised per token row to `bits` bits and
     dequantised (Section 4).  Shapes as attn(); returns [B,H,Lq,D]."""
     s, r = _i32(scales), _rtab(scales, radii)
@@ -262,7 +273,7 @@ def attn_qkv8(scales, radii, q, k, v, sm_scale, n_sink=0, q_scales=None, bits=8,
     assert lq == Lq and k.shape == (B, H, seq_len(scales), D) and v.shape == k.shape
     b0, b1 = (0, B * H) if bh_range is None else bh_range
     out = np.zeros((B, H, Lq, D), dtype=np.float64)
-    rc = _L().lvo_attn_qkv8(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink), C.c_int32(qb),
+    rc = _L().lvo_attn_qkv8(C.c_int32(len(s)), _p(s), _p(r), C.c_int32(n_sink), C.c_int32(mode), C.c_int32(qb),
                             C.c_int32(qe), _p(q), _p(k), _p(v), C.c_int32(code), C.c_int32(B),
                             C.c_int32(H), C.c_int32(D), C.c_double(sm_scale), C.c_int32(bits),
                             C.c_int64(b0), C.c_int64(b1), _p(out))

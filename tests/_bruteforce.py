@@ -52,3 +52,34 @@ def masked_attention(q, k, v, mask, sm_scale):
     e = np.exp(z)
     p = e / e.sum(axis=1, keepdims=True)
     return p @ v, p
+
+
+def dense_mask_band(scales, radii, n_sink=0, q_scales=None):
+    """The band reading, from its definition: parts of the flattened attention map (the first
+    spans the first three key scales, every later key scale is a part) and, per part, the
+    columns within the radius of the part's diagonal.  Exact fractions for the diagonal."""
+    from fractions import Fraction
+    K = len(scales)
+    off = [0]
+    for s in scales:
+        off.append(off[-1] + s * s)
+    qb, qe = (0, K) if q_scales is None else q_scales
+    rows = []
+    for k in range(qb, qe):
+        m = scales[k] * scales[k]
+        # parts as (first key scale, last key scale)
+        parts = [(0, min(2, k))] + [(j, j) for j in range(3, k + 1)]
+        for i in range(m):
+            row = np.zeros(off[-1], dtype=bool)
+            for first, last in parts:
+                n = off[last + 1] - off[first]
+                rad = radii[k][last] if hasattr(radii[0], "__len__") else radii[last]
+                if last < n_sink or rad < 0:
+                    row[off[first]:off[last + 1]] = True
+                    continue
+                diag = int((Fraction(2 * i + 1, 2 * m) * n) // 1)
+                for c in range(n):
+                    if abs(c - diag) <= rad:
+                        row[off[first] + c] = True
+            rows.append(row)
+    return np.array(rows)

@@ -26,7 +26,8 @@ MISTAKES = [
       ("((2 * (int64_t)qx + 1) * sj) / (2 * sk)", "((int64_t)qx * sj) / sk")],
      pins.test_golden_worked_example),
     ("same-scale tokens hidden (strict causal clause)",
-     [("if (kj > qk) return 0;", "if (kj >= qk && !(kj == qk && ky == qy && kx == qx)) return 0;")],
+     [("if (kj > qk) return 0;                 /* block-causal across scales */\n  if (kj < n_sink) return 1;",
+       "if (kj >= qk && !(kj == qk && ky == qy && kx == qx)) return 0;\n  if (kj < n_sink) return 1;")],
      pins.test_golden_worked_example),
     ("diamond instead of square window",
      [("return dy <= r && dx <= r;", "return dy + dx <= r;")],
