@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--chunk", type=int, default=0, help="keys per LDS chunk (0 = library default)")
     ap.add_argument("--depth", type=int, default=0, help="chunks in flight (0 = library default)")
     ap.add_argument("--spare", type=int, default=-1, help="spare ring chunks (-1 = library default)")
+    ap.add_argument("--ppw", type=int, default=0, help="16 patches per group: patches per wave (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--dense", action="store_true", help="dense block-causal path (radius -1)")
@@ -252,7 +253,7 @@ def main():
         sys.exit(3)
     torch.cuda.set_device(0)
 
-    tiling = (args.waves, args.chunk, args.depth, args.spare)
+    tiling = (args.waves, args.chunk, args.depth, args.spare, args.ppw)
     w = workloads.get(args.workload)
     layers = args.layers or LAYERS[w.name]
     res, ctx = run_workload(args.workload, args.dense, args.steps, args.warmup, layers, tiling,
@@ -323,7 +324,7 @@ def main():
         extra = []
         for name, dense in EXTRA:
             torch.cuda.empty_cache()
-            r, _ = run_workload(name, dense, 4 if dense else 8, 2, min(LAYERS[name], 8), (0, 0, 0, -1))
+            r, _ = run_workload(name, dense, 4 if dense else 8, 2, min(LAYERS[name], 8), (0, 0, 0, -1, 0))
             extra.append(r)
         win = next(r for r in extra if r["workload"] == "var_d36_512")
         den = next(r for r in extra if r["workload"] == "var_d36_512_dense")

@@ -72,7 +72,36 @@ typedef struct litevar_mask_desc {
                                           litevar_window_calibrate); overrides both radius
                                           fields when non-NULL; entries with key scale > query
                                           scale are ignored */
+  int32_t n_heads;                     /* 0, or the number of heads H (<= LITEVAR_MAX_HEADS) of
+                                          radius_per_head */
+  const int32_t* radius_per_head;      /* optional [H][K][K], [head][query scale][key scale]
+                                          (Section 2, step (3): the window size is determined for
+                                          each scale, part and head; the layout of
+                                          litevar_window_calibrate's d_radius); overrides the other
+                                          radius fields; heads with equal tables share one
+                                          work-list inside the plan.  Attention calls with such a
+                                          plan must pass H = n_heads */
+  int32_t mask_mode;                   /* LITEVAR_MASK_WINDOW_2D or LITEVAR_MASK_BAND_1D */
 } litevar_mask_desc;
+
+/*
+ * The two readings of the window of Section 2 (the paper's figure is its only definition):
+ *   LITEVAR_MASK_WINDOW_2D  a square window of radius r around the query's position mapped into
+ *                           the key scale's grid, one part per key scale (the default; see the
+ *                           top of this file);
+ *   LITEVAR_MASK_BAND_1D    Section 2, step (2) read literally: the attention map of query
+ *                           scale k, [s_k^2, sum of s_i^2], is cut into parts, the first
+ *                           spanning the first three key scales (those of them the query sees),
+ *                           every later key scale a part of its own; in a part of n columns the
+ *                           query with flattened index i keeps the columns c with
+ *                           |c - floor((2i+1) n / (2 s_k^2))| <= r, a band of width 2r+1 around
+ *                           the part's diagonal.  The radius of a part is the entry of its last
+ *                           key scale; a part whose last key scale is below n_sink_scales is
+ *                           dense.  Radii up to 32767.  Query patches are 16 consecutive
+ *                           queries.  No window table exists in this mode.
+ */
+enum { LITEVAR_MASK_WINDOW_2D = 0, LITEVAR_MASK_BAND_1D = 1 };
+#define LITEVAR_MAX_HEADS 256
 
 /*
  * Host-side handle of a built plan.  Plain data, owned by the caller, may be
@@ -107,7 +136,13 @@ typedef struct litevar_plan {
   int32_t n_sink_scales;
   int32_t patches_per_wave; /* 16 patches per group only: 0 = chosen per launch, else 1 or 2 */
   int32_t spin_limit;       /* bound of the kernels' LDS-flag waits, in polls */
-  int32_t reserved;
+  int32_t mask_mode;
+  int32_t n_heads;          /* 0, or the number of heads the plan holds radius tables for */
+  int32_t n_head_groups;    /* distinct radius tables; n_groups, n_patches count one head group,
+                               n_steps, n_union_keys, retained_pairs and computed_pairs are summed
+                               over the head groups (one group: the values of every head) */
+  uint8_t head_group[LITEVAR_MAX_HEADS];           /* head -> head group */
+  int64_t retained_pairs_of_group[LITEVAR_MAX_HEADS]; /* kept pairs per (batch, head) of a head group */
 } litevar_plan;
 
 /* Tuning knobs of the plan; zero-initialise for the defaults. */
@@ -132,6 +167,13 @@ typedef struct litevar_plan_opts {
                                0 = default (2^22).  Tests of that path pass 1. */
   int32_t reserved[1];
 } litevar_plan_opts;
+
+/*
+ * Scale table (Section 2: scale k holds s_k^2 tokens, stored one scale after the other):
+ * out_offsets[k] = index of scale k's first token, out_offsets[K] = sequence length.
+ * Host-only.  scales: HOST [n_scales]; out_offsets: HOST [n_scales + 1].
+ */
+litevar_status litevar_scale_offsets(const int32_t* scales, int32_t n_scales, int64_t* out_offsets);
 
 /*
  * Size in bytes of the device blob a plan for `desc` needs.  Host-only, no HIP
@@ -171,32 +213,33 @@ litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_p
 litevar_status litevar_plan_check(const litevar_plan* plan, void* stream);
 
 /*
- * Window table as built on the device, for parity checks: d_out is DEVICE
- * int16 [K][K][side_max][2]; entry (k, j, c) holds the inclusive [lo, hi] key
+ * Window table as built on the device (Section 2: the window of every scale and part), for
+ * parity checks; `head` selects the radius table (0 when the plan has one for all heads);
+ * window mode only.  d_out is DEVICE int16 [K][K][side_max][2]; entry (k, j, c) holds the inclusive [lo, hi] key
  * coordinates of scale j that query coordinate c of scale k keeps along one axis
  * (the 2-D window is the product of the row and column intervals); (-1, -1) where
  * j > k or c >= s_k.
  */
-litevar_status litevar_window_table_export(const litevar_plan* plan, int16_t* d_out,
+litevar_status litevar_window_table_export(const litevar_plan* plan, int32_t head, int16_t* d_out,
                                            size_t out_bytes, void* stream);
 
 /*
- * What the work-list encodes, as a dense byte mask: d_mask is DEVICE uint8
- * [q_len][kv_len], 1 = kept pair.  Written from the per-wave steps the attention
+ * What the work-list encodes (Section 2: the kept pairs of every part), as a dense byte mask
+ * of head `head`: d_mask is DEVICE uint8 [q_len][kv_len], 1 = kept pair.  Written from the per-wave steps the attention
  * kernel consumes (not from the window table).  d_pair_count: optional DEVICE
  * uint64[1], receives the number of (query, key) entries in the work-list, which
  * equals the mask's popcount iff no pair is listed twice.
  */
-litevar_status litevar_mask_export_dense(const litevar_plan* plan, uint8_t* d_mask,
+litevar_status litevar_mask_export_dense(const litevar_plan* plan, int32_t head, uint8_t* d_mask,
                                          size_t mask_bytes, uint64_t* d_pair_count,
                                          void* stream);
 
 /*
- * Same content in CSR form: d_rowptr DEVICE int64 [q_len + 1]; d_cols DEVICE
- * int32 [cols_cap], each row's kept keys in the order the work-list visits them
- * (ascending token index).  cols_cap >= plan->retained_pairs.
+ * Same content in CSR form (the index sets of Section 2's windows): d_rowptr DEVICE int64
+ * [q_len + 1]; d_cols DEVICE int32 [cols_cap], each row's kept keys in ascending token
+ * order.  cols_cap >= the head's kept pairs (plan->retained_pairs_of_group[...]).
  */
-litevar_status litevar_mask_export_csr(const litevar_plan* plan, int64_t* d_rowptr,
+litevar_status litevar_mask_export_csr(const litevar_plan* plan, int32_t head, int64_t* d_rowptr,
                                        int32_t* d_cols, size_t cols_cap, void* stream);
 
 typedef enum { LITEVAR_BF16 = 0, LITEVAR_F32 = 1 } litevar_dtype;

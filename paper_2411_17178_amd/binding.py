@@ -13,6 +13,8 @@ _LIB_PATH = os.path.join(_HERE, "liblitevar.so")
 _lib = None
 
 MAX_SCALES = 32
+MAX_HEADS = 256
+MASK_WINDOW_2D, MASK_BAND_1D = 0, 1
 FLAG_CFG_SHARE = 1
 DT_BF16, DT_F32 = 0, 1
 
@@ -27,7 +29,9 @@ class _MaskDesc(C.Structure):
     _fields_ = [("n_scales", C.c_int32), ("scales", C.POINTER(C.c_int32)),
                 ("radius", C.c_int32), ("radius_per_key_scale", C.POINTER(C.c_int32)),
                 ("n_sink_scales", C.c_int32), ("q_scale_begin", C.c_int32),
-                ("q_scale_end", C.c_int32), ("radius_per_scale_pair", C.POINTER(C.c_int32))]
+                ("q_scale_end", C.c_int32), ("radius_per_scale_pair", C.POINTER(C.c_int32)),
+                ("n_heads", C.c_int32), ("radius_per_head", C.POINTER(C.c_int32)),
+                ("mask_mode", C.c_int32)]
 
 
 class _PlanOpts(C.Structure):
@@ -48,7 +52,9 @@ class _Plan(C.Structure):
                 ("retained_pairs", C.c_int64), ("computed_pairs", C.c_int64),
                 ("off", C.c_uint64 * 12), ("scales", C.c_int32 * MAX_SCALES),
                 ("radii", C.c_int32 * MAX_SCALES), ("n_sink_scales", C.c_int32),
-                ("patches_per_wave", C.c_int32), ("spin_limit", C.c_int32), ("reserved", C.c_int32)]
+                ("patches_per_wave", C.c_int32), ("spin_limit", C.c_int32), ("mask_mode", C.c_int32),
+                ("n_heads", C.c_int32), ("n_head_groups", C.c_int32), ("head_group", C.c_uint8 * MAX_HEADS),
+                ("retained_pairs_of_group", C.c_int64 * MAX_HEADS)]
 
 
 def lib_path():
@@ -67,7 +73,7 @@ def load_library():
     lib.litevar_status_string.restype = C.c_char_p
     lib.litevar_last_error.restype = C.c_char_p
     lib.litevar_version.restype = C.c_int32
-    for name in ("litevar_mask_plan_bytes", "litevar_mask_plan_stats", "litevar_mask_build", "litevar_plan_check",
+    for name in ("litevar_scale_offsets", "litevar_mask_plan_bytes", "litevar_mask_plan_stats", "litevar_mask_build", "litevar_plan_check",
                  "litevar_window_table_export", "litevar_mask_export_dense",
                  "litevar_mask_export_csr", "litevar_windowed_attn_fwd",
                  "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate",
@@ -90,23 +96,29 @@ def _stream_handle(stream):
     return C.c_void_p(stream.cuda_stream)
 
 
-def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales):
+def _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales, mask_mode=0):
     K = len(scales)
     sc = (C.c_int32 * K)(*[int(s) for s in scales])
-    # radius_per_key_scale: [K] (one radius per key scale) or a table [K][K]
-    # ([query scale][key scale], one window size per scale and part)
-    rp = pair = None
+    # radius_per_key_scale: [K] (one radius per key scale), a table [K][K] ([query scale][key
+    # scale], one window size per scale and part) or one such table per head, [H][K][K]
+    rp = pair = heads = None
+    n_heads = 0
     if radius_per_key_scale is not None:
         rows = list(radius_per_key_scale)
-        if len(rows) and hasattr(rows[0], "__len__"):
+        if len(rows) and hasattr(rows[0], "__len__") and len(rows[0]) and hasattr(rows[0][0], "__len__"):
+            n_heads = len(rows)
+            assert all(len(t) == K and all(len(r) == K for r in t) for t in rows), "radius tables must be [H][K][K]"
+            heads = (C.c_int32 * (n_heads * K * K))(*[int(r) for t in rows for row in t for r in row])
+        elif len(rows) and hasattr(rows[0], "__len__"):
             assert len(rows) == K and all(len(r) == K for r in rows), "radius table must be [K][K]"
             pair = (C.c_int32 * (K * K))(*[int(r) for row in rows for r in row])
         else:
             assert len(rows) == K, "one radius per key scale"
             rp = (C.c_int32 * K)(*[int(r) for r in rows])
     qb, qe = (0, K) if q_scales is None else q_scales
-    d = _MaskDesc(K, sc, int(radius), rp, int(n_sink_scales), int(qb), int(qe), pair)
-    d._keep = (sc, rp, pair)
+    d = _MaskDesc(K, sc, int(radius), rp, int(n_sink_scales), int(qb), int(qe), pair, n_heads, heads,
+                  int(mask_mode))
+    d._keep = (sc, rp, pair, heads)
     return d
 
 
@@ -142,9 +154,18 @@ class Plan:
         return [self.handle.scales[i] for i in range(self.handle.n_scales)]
 
 
+def litevar_scale_offsets(scales):
+    """[first token of scale 0, ..., of scale K-1, sequence length] (the library's scale table)."""
+    K = len(scales)
+    sc = (C.c_int32 * K)(*[int(s) for s in scales])
+    out = (C.c_int64 * (K + 1))()
+    _check(load_library().litevar_scale_offsets(sc, C.c_int32(K), out))
+    return [int(x) for x in out]
+
+
 def litevar_mask_plan_bytes(scales, radius, radius_per_key_scale=None, n_sink_scales=0,
-                            q_scales=None, waves_per_group=0, batch_heads=0):
-    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
+                            q_scales=None, waves_per_group=0, batch_heads=0, mask_mode=0):
+    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales, mask_mode)
     o = _make_opts(waves_per_group, batch_heads)
     n = C.c_size_t(0)
     _check(load_library().litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
@@ -152,9 +173,9 @@ def litevar_mask_plan_bytes(scales, radius, radius_per_key_scale=None, n_sink_sc
 
 
 def litevar_mask_plan_stats(scales, radius, radius_per_key_scale=None, n_sink_scales=0,
-                            q_scales=None, waves_per_group=0, batch_heads=0):
+                            q_scales=None, waves_per_group=0, batch_heads=0, mask_mode=0):
     """Host-only dry run: a Plan without a device blob (sizes and pair counts only)."""
-    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
+    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales, mask_mode)
     o = _make_opts(waves_per_group, batch_heads)
     handle = _Plan()
     _check(load_library().litevar_mask_plan_stats(C.byref(d), C.byref(o), C.byref(handle)))
@@ -163,13 +184,13 @@ def litevar_mask_plan_stats(scales, radius, radius_per_key_scale=None, n_sink_sc
 
 def litevar_mask_build(scales, radius, radius_per_key_scale=None, n_sink_scales=0, q_scales=None,
                        waves_per_group=0, device="cuda", stream=None, blob=None, batch_heads=0,
-                       spin_limit=0):
+                       spin_limit=0, mask_mode=0):
     """Build a plan on the device.  `blob` (optional uint8 CUDA tensor, large enough and
     256-byte aligned) is reused as the plan's storage instead of a fresh allocation.
     `batch_heads` (optional): B * H of the launches the plan is for, which lets the library
     pick smaller groups for small batches."""
     lib = load_library()
-    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales)
+    d = _make_desc(scales, radius, radius_per_key_scale, n_sink_scales, q_scales, mask_mode)
     o = _make_opts(waves_per_group, batch_heads, spin_limit)
     n = C.c_size_t(0)
     _check(lib.litevar_mask_plan_bytes(C.byref(d), C.byref(o), C.byref(n)))
@@ -187,32 +208,33 @@ def litevar_plan_check(plan, stream=None):
     _check(load_library().litevar_plan_check(C.byref(plan.handle), _stream_handle(stream)))
 
 
-def litevar_window_table_export(plan, stream=None):
+def litevar_window_table_export(plan, stream=None, head=0):
     K, smax = plan.n_scales, plan.side_max
     out = torch.empty((K, K, smax, 2), dtype=torch.int16, device=plan.blob.device)
     _check(load_library().litevar_window_table_export(
-        C.byref(plan.handle), C.c_void_p(out.data_ptr()), C.c_size_t(out.numel() * 2),
+        C.byref(plan.handle), C.c_int32(head), C.c_void_p(out.data_ptr()), C.c_size_t(out.numel() * 2),
         _stream_handle(stream)))
     return out
 
 
-def litevar_mask_export_dense(plan, stream=None):
-    """(uint8 [q_len, kv_len] mask, number of work-list entries)."""
+def litevar_mask_export_dense(plan, stream=None, head=0):
+    """(uint8 [q_len, kv_len] mask of head `head`, number of work-list entries)."""
     mask = torch.empty((plan.q_len, plan.kv_len), dtype=torch.uint8, device=plan.blob.device)
     count = torch.empty(1, dtype=torch.int64, device=plan.blob.device)
     _check(load_library().litevar_mask_export_dense(
-        C.byref(plan.handle), C.c_void_p(mask.data_ptr()), C.c_size_t(mask.numel()),
+        C.byref(plan.handle), C.c_int32(head), C.c_void_p(mask.data_ptr()), C.c_size_t(mask.numel()),
         C.c_void_p(count.data_ptr()), _stream_handle(stream)))
     return mask, count
 
 
-def litevar_mask_export_csr(plan, stream=None):
+def litevar_mask_export_csr(plan, stream=None, head=0):
+    kept = int(plan.retained_pairs_of_group[plan.head_group[head] if plan.n_heads else 0])
     rowptr = torch.empty(plan.q_len + 1, dtype=torch.int64, device=plan.blob.device)
-    cols = torch.empty(max(1, plan.retained_pairs), dtype=torch.int32, device=plan.blob.device)
+    cols = torch.empty(max(1, kept), dtype=torch.int32, device=plan.blob.device)
     _check(load_library().litevar_mask_export_csr(
-        C.byref(plan.handle), C.c_void_p(rowptr.data_ptr()), C.c_void_p(cols.data_ptr()),
+        C.byref(plan.handle), C.c_int32(head), C.c_void_p(rowptr.data_ptr()), C.c_void_p(cols.data_ptr()),
         C.c_size_t(cols.numel()), _stream_handle(stream)))
-    return rowptr, cols[:plan.retained_pairs]
+    return rowptr, cols[:kept]
 
 
 def _strides(t):
@@ -265,7 +287,7 @@ def litevar_window_calibrate(scales, attn_map, r0, with_mass=False, stream=None)
     sc = (C.c_int32 * K)(*[int(s) for s in scales])
     n = C.c_size_t(0)
     _check(lib.litevar_window_calibrate_workspace_bytes(sc, C.c_int32(K), C.c_int32(H), C.byref(n)))
-    assert L == L2 == sum(int(s) * int(s) for s in scales)
+    assert L == L2 == litevar_scale_offsets(scales)[-1]
     dev = attn_map.device
     work = torch.empty(max(1, (n.value + 7) // 8), dtype=torch.float64, device=dev)
     radius = torch.empty((H, K, K), dtype=torch.int32, device=dev)
@@ -287,7 +309,7 @@ def litevar_window_calibrate_static(scales, attn_map, r0, radius, mass=None, str
     assert attn_map.is_cuda and attn_map.dtype == torch.float32 and attn_map.is_contiguous()
     N, H, L, L2 = attn_map.shape
     K = len(scales)
-    assert L == L2 and radius.is_cuda and radius.dtype == torch.int32 and radius.shape == (H, K, K)
+    assert L == L2 == litevar_scale_offsets(scales)[-1] and radius.is_cuda and radius.dtype == torch.int32 and radius.shape == (H, K, K)
     assert radius.is_contiguous()
     if mass is not None:
         assert mass.is_cuda and mass.dtype == torch.float64 and mass.is_contiguous()

@@ -53,14 +53,28 @@ const char* litevar_last_error(void) { return g_err; }
 
 int32_t litevar_version(void) { return 100; }
 
+litevar_status litevar_scale_offsets(const int32_t* scales, int32_t n_scales, int64_t* out_offsets) {
+  if (!scales || !out_offsets) return fail(LITEVAR_E_INVALID_ARG, "scales or out_offsets is NULL");
+  if (n_scales < 1 || n_scales > kMaxScales)
+    return fail(LITEVAR_E_INVALID_ARG, "n_scales must be in 1..%d (got %d)", kMaxScales, n_scales);
+  int64_t L = 0;
+  for (int k = 0; k < n_scales; ++k) {
+    if (scales[k] < 1 || scales[k] > kMaxSide)
+      return fail(LITEVAR_E_INVALID_ARG, "scales[%d] = %d outside 1..%d", k, scales[k], kMaxSide);
+    out_offsets[k] = L; L += (int64_t)scales[k] * scales[k];
+  }
+  out_offsets[n_scales] = L;
+  return LITEVAR_OK;
+}
+
 litevar_status litevar_mask_plan_bytes(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
                                        size_t* out_bytes) {
   if (!out_bytes) return fail(LITEVAR_E_INVALID_ARG, "out_bytes is NULL");
-  Geom g;
-  litevar_status rc = make_geom(desc, opts, g);
+  PlanSpec sp;
+  litevar_status rc = make_spec(desc, opts, sp);
   if (rc) return rc;
   PlanSizes z;
-  rc = size_plan(g, z);
+  rc = size_plan(sp, z);
   if (rc) return rc;
   *out_bytes = (size_t)z.bytes;
   return LITEVAR_OK;
@@ -73,8 +87,13 @@ static litevar_status check_patches_per_wave(const litevar_plan_opts* opts) {
   return LITEVAR_OK;
 }
 
-static void fill_handle(const Geom& g, const PlanSizes& z, const litevar_plan_opts* opts, litevar_plan* plan) {
+static void fill_handle(const PlanSpec& sp, const PlanSizes& z, const litevar_plan_opts* opts, litevar_plan* plan) {
+  const Geom& g = sp.g;
   memset(plan, 0, sizeof *plan);
+  plan->mask_mode = g.mode == kModeBand ? LITEVAR_MASK_BAND_1D : LITEVAR_MASK_WINDOW_2D;
+  plan->n_heads = sp.n_heads; plan->n_head_groups = g.n_hg;
+  memcpy(plan->head_group, sp.head_group, sizeof plan->head_group);
+  for (int i = 0; i < g.n_hg && i < kMaxHeads; ++i) plan->retained_pairs_of_group[i] = z.pairs_of_group[i];
   plan->patches_per_wave = (opts && g.NW == 16) ? opts->patches_per_wave : 0;
   plan->blob_bytes = z.bytes;
   plan->n_scales = g.K;
@@ -90,10 +109,14 @@ static void fill_handle(const Geom& g, const PlanSizes& z, const litevar_plan_op
   for (int i = 0; i < kNumSections; ++i) plan->off[i] = z.off[i];
   for (int k = 0; k < g.K; ++k) {
     plan->scales[k] = g.s[k];
-    // widest window of key scale k over the plan's query scales (-1 if one of them is dense)
+    // widest window of key scale k over the plan's query scales and head groups (-1 if one
+    // of them is dense)
     int r = 0;
-    for (int q = (g.qb > k ? g.qb : k); q < g.qe; ++q)
-      r = (r < 0 || g.rad[q][k] < 0) ? -1 : (g.rad[q][k] > r ? g.rad[q][k] : r);
+    for (int hg = 0; hg < g.n_hg; ++hg)
+      for (int q = (g.qb > k ? g.qb : k); q < g.qe; ++q) {
+        const int rq = sp.rad_all[((size_t)hg * g.K + q) * g.K + k];
+        r = (r < 0 || rq < 0) ? -1 : (rq > r ? rq : r);
+      }
     plan->radii[k] = r;
   }
   plan->n_sink_scales = g.n_sink;
@@ -103,14 +126,14 @@ static void fill_handle(const Geom& g, const PlanSizes& z, const litevar_plan_op
 litevar_status litevar_mask_plan_stats(const litevar_mask_desc* desc, const litevar_plan_opts* opts,
                                        litevar_plan* stats) {
   if (!stats) return fail(LITEVAR_E_INVALID_ARG, "stats is NULL");
-  Geom g;
-  litevar_status rc = make_geom(desc, opts, g);
+  PlanSpec sp;
+  litevar_status rc = make_spec(desc, opts, sp);
   if (rc) return rc;
   PlanSizes z;
-  rc = size_plan(g, z);
+  rc = size_plan(sp, z);
   if (rc) return rc;
   if (litevar_status s = check_patches_per_wave(opts)) return s;
-  fill_handle(g, z, opts, stats);
+  fill_handle(sp, z, opts, stats);
   return LITEVAR_OK;
 }
 
@@ -118,11 +141,11 @@ litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_p
                                   void* d_blob, size_t blob_bytes, void* stream,
                                   litevar_plan* plan) {
   if (!plan) return fail(LITEVAR_E_INVALID_ARG, "plan is NULL");
-  Geom g;
-  litevar_status rc = make_geom(desc, opts, g);
+  PlanSpec sp;
+  litevar_status rc = make_spec(desc, opts, sp);
   if (rc) return rc;
   PlanSizes z;
-  rc = size_plan(g, z);
+  rc = size_plan(sp, z);
   if (rc) return rc;
   if (!d_blob) return fail(LITEVAR_E_INVALID_ARG, "d_blob is NULL");
   if ((uintptr_t)d_blob & 255) return fail(LITEVAR_E_INVALID_ARG, "d_blob must be 256-byte aligned");
@@ -130,9 +153,9 @@ litevar_status litevar_mask_build(const litevar_mask_desc* desc, const litevar_p
     return fail(LITEVAR_E_PLAN_TOO_SMALL, "plan needs %llu bytes, buffer has %llu",
                 (unsigned long long)z.bytes, (unsigned long long)blob_bytes);
   if (litevar_status s = check_patches_per_wave(opts)) return s;
-  rc = build_plan(g, z, d_blob, (hipStream_t)stream);
+  rc = build_plan(sp, z, d_blob, (hipStream_t)stream);
   if (rc) return rc;
-  fill_handle(g, z, opts, plan);
+  fill_handle(sp, z, opts, plan);
   plan->magic = kMagic;
   plan->d_blob = d_blob;
   return LITEVAR_OK;
@@ -149,44 +172,55 @@ litevar_status litevar_plan_check(const litevar_plan* plan, void* stream) {
   if (h.error == kErrWaitGaveUp)
     return fail(LITEVAR_E_PLAN_CORRUPT, "an attention kernel's bounded wait gave up (its output is invalid)");
   if (h.error) return fail(LITEVAR_E_PLAN_CORRUPT, "device blob carries the unknown error mark %d", h.error);
-  if (h.blob_bytes != plan->blob_bytes || h.n_groups != plan->n_groups ||
+  if (h.blob_bytes != plan->blob_bytes || h.n_groups != plan->n_groups * plan->n_head_groups ||
       h.n_steps != plan->n_steps || h.n_union != plan->n_union_keys ||
       h.retained_pairs != plan->retained_pairs)
     return fail(LITEVAR_E_PLAN_CORRUPT, "device blob does not match the handle");
   return LITEVAR_OK;
 }
 
-litevar_status litevar_window_table_export(const litevar_plan* plan, int16_t* d_out,
+static litevar_status check_head(const litevar_plan* plan, int32_t head) {
+  const int n = plan->n_heads > 0 ? plan->n_heads : 1;
+  if (head < 0 || head >= n) return fail(LITEVAR_E_INVALID_ARG, "head %d outside the plan's 0..%d", head, n - 1);
+  return LITEVAR_OK;
+}
+
+litevar_status litevar_window_table_export(const litevar_plan* plan, int32_t head, int16_t* d_out,
                                            size_t out_bytes, void* stream) {
   litevar_status rc = check_plan(plan);
   if (rc) return rc;
+  if (litevar_status s = check_head(plan, head)) return s;
+  if (plan->mask_mode != LITEVAR_MASK_WINDOW_2D)
+    return fail(LITEVAR_E_UNSUPPORTED, "the band mode has no window table");
   if (!d_out) return fail(LITEVAR_E_INVALID_ARG, "d_out is NULL");
   const size_t need = (size_t)plan->n_scales * plan->n_scales * plan->side_max * 2 * sizeof(int16_t);
   if (out_bytes < need)
     return fail(LITEVAR_E_INVALID_ARG, "window table needs %zu bytes, buffer has %zu", need, out_bytes);
-  return export_window_table(plan, d_out, (hipStream_t)stream);
+  return export_window_table(plan, head, d_out, (hipStream_t)stream);
 }
 
-litevar_status litevar_mask_export_dense(const litevar_plan* plan, uint8_t* d_mask, size_t mask_bytes,
+litevar_status litevar_mask_export_dense(const litevar_plan* plan, int32_t head, uint8_t* d_mask, size_t mask_bytes,
                                          uint64_t* d_pair_count, void* stream) {
   litevar_status rc = check_plan(plan);
   if (rc) return rc;
+  if (litevar_status s = check_head(plan, head)) return s;
   if (!d_mask) return fail(LITEVAR_E_INVALID_ARG, "d_mask is NULL");
   const size_t need = (size_t)plan->q_len * plan->kv_len;
   if (mask_bytes < need)
     return fail(LITEVAR_E_INVALID_ARG, "dense mask needs %zu bytes, buffer has %zu", need, mask_bytes);
-  return export_dense(plan, d_mask, d_pair_count, (hipStream_t)stream);
+  return export_dense(plan, head, d_mask, d_pair_count, (hipStream_t)stream);
 }
 
-litevar_status litevar_mask_export_csr(const litevar_plan* plan, int64_t* d_rowptr, int32_t* d_cols,
+litevar_status litevar_mask_export_csr(const litevar_plan* plan, int32_t head, int64_t* d_rowptr, int32_t* d_cols,
                                        size_t cols_cap, void* stream) {
   litevar_status rc = check_plan(plan);
   if (rc) return rc;
+  if (litevar_status s = check_head(plan, head)) return s;
   if (!d_rowptr || !d_cols) return fail(LITEVAR_E_INVALID_ARG, "d_rowptr or d_cols is NULL");
-  if ((int64_t)cols_cap < plan->retained_pairs)
-    return fail(LITEVAR_E_INVALID_ARG, "cols_cap %zu below the %lld kept pairs", cols_cap,
-                (long long)plan->retained_pairs);
-  return export_csr(plan, d_rowptr, d_cols, cols_cap, (hipStream_t)stream);
+  const int64_t kept = plan->retained_pairs_of_group[plan->n_heads > 0 ? plan->head_group[head] : 0];
+  if ((int64_t)cols_cap < kept)
+    return fail(LITEVAR_E_INVALID_ARG, "cols_cap %zu below the %lld kept pairs", cols_cap, (long long)kept);
+  return export_csr(plan, head, d_rowptr, d_cols, cols_cap, (hipStream_t)stream);
 }
 
 static bool strides_ok(const int64_t* s, int B, int H, int64_t len, int D, int64_t out[3]) {
@@ -248,6 +282,9 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   a.step_mask = (const uint64_t*)(blob + plan->off[kSecStepMask]);
   a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
   a.n_groups = plan->n_groups;
+  if (plan->n_heads > 0 && H != plan->n_heads)
+    return fail(LITEVAR_E_INVALID_ARG, "the plan holds radius tables for %d heads, the call has H = %d", plan->n_heads, H);
+  a.head_map = plan->n_heads > 0 ? (const int32_t*)(blob + plan->off[kSecHeadMap]) : nullptr;
   a.q_len = plan->q_len;
   a.hdr = (Header*)(plan->d_blob);
   a.spin_limit = plan->spin_limit > 0 ? plan->spin_limit : kDefaultSpinLimit;

@@ -64,7 +64,8 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
   if (bh >= a.B * a.H) return;
   const int b = bh / a.H, h = bh % a.H;
   if (!plan_usable(a.hdr)) return;
-  const GroupDesc gd = a.groups[grp];
+  const int grp_g = grp + (a.head_map ? a.head_map[h] * a.n_groups : 0);   // the head group's copy of the work-list
+  const GroupDesc gd = a.groups[grp_g];
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
   if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
 
@@ -157,12 +158,12 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
 
   // ---------------- compute waves ----------------
   const int n = lane & 15, g4 = lane >> 4;
-  const WaveDesc wd = a.waves[grp * NW + wave];
+  const WaveDesc wd = a.waves[grp_g * NW + wave];
   const int n_steps = __builtin_amdgcn_readfirstlane(wd.n_steps);
 
   // Q^T as the B operand: lane (n, g4) holds Q[query n][16*g4 .. 16*g4+15]
   const int dy = n >> 2, dx = n & 3;
-  const int qrow = (dy < wd.ny && dx < wd.nx) ? wd.q_base + dy * wd.sk + dx : -1;
+  const int qrow = ((wd.valid >> n) & 1u) ? wd.q_base + dy * wd.sk + dx : -1;
   bf16x8 qb0, qb1;
   {
     uint4 z = {0, 0, 0, 0}, q0 = z, q1 = z;

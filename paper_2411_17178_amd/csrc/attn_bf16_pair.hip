@@ -118,7 +118,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   if (bh >= a.B * a.H) return;
   const int b = bh / a.H, h = bh % a.H;
   const bool usable = plan_usable(a.hdr);
-  const GroupDesc gd = a.groups[grp];      // (requested together with the header words, used behind the check)
+  // heads with a radius table of their own use their head group's copy of the work-list
+  const int grp_g = grp + (a.head_map ? a.head_map[h] * a.n_groups : 0);
+  const GroupDesc gd = a.groups[grp_g];    // (requested together with the header words, used behind the check)
   if (!usable) return;
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
   if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
@@ -181,24 +183,24 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // descriptors, phase tables, the extent of the group's steps) is fetched before the first
   // vector memory operation: behind the burst of first chunks of all workgroups a scalar
   // miss would take microseconds, and the vector loads below depend on these values.
-  // Patch descriptor words: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16}
+  // Patch descriptor words: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16, pairs, valid}
   // (two patches per wave: p and its partner two patch rows below, columns swapped)
   const int pa = wave, pb_ = PW == 2 ? ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1) : wave;
-  const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp * 16 + pa), wB = (const_i32_ptr)(a.waves + grp * 16 + pb_);
-  const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp * 16), wL = (const_i32_ptr)(a.waves + grp * 16 + 15);
+  const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp_g * 16 + pa), wB = (const_i32_ptr)(a.waves + grp_g * 16 + pb_);
+  const const_i32_ptr wF = (const_i32_ptr)(a.waves + grp_g * 16), wL = (const_i32_ptr)(a.waves + grp_g * 16 + 15);
   const const_i32_ptr peA = (const_i32_ptr)(a.phase_end + gd.phase_base + pa * NC);
   const const_i32_ptr peB = (const_i32_ptr)(a.phase_end + gd.phase_base + pb_ * NC);
   auto last_chunk = [&](int ph) -> int { return min(2 * ph, NC - 1); };   // of phase ph (clamped)
-  struct PatchWords { int step_begin, q_base, sk_ny, nx_kq; };
-  const PatchWords pwA = {wA[0], wA[2], wA[3], wA[4]}, pwB = {wB[0], wB[2], wB[3], wB[4]};
+  struct PatchWords { int step_begin, q_base, sk_ny, valid; };
+  const PatchWords pwA = {wA[0], wA[2], wA[3], wA[6]}, pwB = {wB[0], wB[2], wB[3], wB[6]};
   const int first_step = wF[0], n_group_steps = wL[0] + wL[1] - first_step;
   // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
   // phase p + 2 is fetched during phase p
   // (one patch per wave: the second patch's counts are the constant 0 and its code goes away)
   int endA = peA[0], endB = PW == 2 ? peB[0] : 0;
   int end1A = peA[last_chunk(1)], end1B = PW == 2 ? peB[last_chunk(1)] : 0;
-  asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.nx_kq),
-               "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.nx_kq),
+  asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.valid),
+               "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.valid),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
 
   // ---- prologue, vector part: chunk 0 first.  The key list usually starts with whole key
@@ -222,11 +224,11 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   // local query row of this lane's query column (-1 = none)
   auto query_row = [&](const PatchWords& w, int n, bool clamped) -> int {
-    const int sk = w.sk_ny & 0xffff, ny = w.sk_ny >> 16, nx = w.nx_kq & 0xffff;
+    const int sk = w.sk_ny & 0xffff;
     const int dy = n >> 2, dx = n & 3;
     const int r = w.q_base + dy * sk + dx;
     if (clamped) return max(min(r, a.q_len - 1), 0);
-    return (dy < ny && dx < nx) ? r : -1;
+    return ((w.valid >> n) & 1) ? r : -1;
   };
   // Q rows are loaded unconditionally, from a clamped row where the lane has no query: such
   // a column of S^T holds scores of some other query, all of its mask bits are clear and it

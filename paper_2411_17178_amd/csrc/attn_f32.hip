@@ -11,15 +11,15 @@ namespace lv {
 __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a, int n_waves) {
   const int wv = blockIdx.x % n_waves, bh = blockIdx.x / n_waves;
   if (!plan_usable(a.hdr)) return;
-  const WaveDesc wd = a.waves[wv];
-  if (wd.ny == 0) return;
   const int b = bh / a.H, h = bh % a.H;
+  const WaveDesc wd = a.waves[wv + (a.head_map ? a.head_map[h] * n_waves : 0)];   // the head group's patches
+  if (wd.ny == 0) return;
   const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + wd.kq];
   if (shared && b >= a.B / 2) return;
 
   const int lane = threadIdx.x, n = lane % 16, g4 = lane / 16;
   const int dy = n / 4, dx = n % 4;
-  const int qrow = (dy < wd.ny && dx < wd.nx) ? wd.q_base + dy * wd.sk + dx : -1;
+  const int qrow = ((wd.valid >> n) & 1u) ? wd.q_base + dy * wd.sk + dx : -1;
 
   const float* Q = (const float*)a.q + b * a.qs[0] + h * a.qs[1];
   const float* Kp = (const float*)a.k + b * a.ks[0] + h * a.ks[1];

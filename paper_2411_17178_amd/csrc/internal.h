@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "../../include/litevar.h"
 #include "plan.h"
 
@@ -12,19 +14,34 @@ litevar_status fail(litevar_status code, const char* fmt, ...);
 litevar_status hip_check(hipError_t e, const char* what);
 
 struct PlanSizes {
-  int64_t n_steps, n_union, n_phase_entries, retained_pairs;
+  int64_t n_steps, n_union, n_phase_entries, retained_pairs;   // summed over the head groups
+  int64_t pairs_of_group[kMaxHeads];                           // kept pairs per (batch, head) of each head group
   uint64_t off[kNumSections];
   uint64_t bytes;
 };
 
-litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* opts, Geom& g);
-litevar_status size_plan(const Geom& g, PlanSizes& z);
-litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipStream_t st);
+// What a mask descriptor asks for: the geometry, and one radius table per head group
+// (heads with equal tables share a group).  g.rad holds the table of the group that was
+// loaded last; make_spec and size_plan leave group 0 loaded.
+struct PlanSpec {
+  Geom g;
+  int n_heads = 0;                      // 0: one table for all heads
+  std::vector<int16_t> rad_all;         // [n_hg][K][K]
+  uint8_t head_group[kMaxHeads] = {};   // head -> head group
+  void load_head_group(int hg) {
+    for (int k = 0; k < g.K; ++k)
+      for (int j = 0; j < g.K; ++j) g.rad[k][j] = rad_all[((size_t)hg * g.K + k) * g.K + j];
+  }
+};
+
+litevar_status make_spec(const litevar_mask_desc* d, const litevar_plan_opts* opts, PlanSpec& sp);
+litevar_status size_plan(PlanSpec& sp, PlanSizes& z);
+litevar_status build_plan(PlanSpec& sp, const PlanSizes& z, void* d_blob, hipStream_t st);
 litevar_status read_header(const litevar_plan* pl, hipStream_t st, Header& h);
 
-litevar_status export_window_table(const litevar_plan* pl, int16_t* d_out, hipStream_t st);
-litevar_status export_dense(const litevar_plan* pl, uint8_t* d_mask, uint64_t* d_count, hipStream_t st);
-litevar_status export_csr(const litevar_plan* pl, int64_t* d_rowptr, int32_t* d_cols, size_t cap,
+litevar_status export_window_table(const litevar_plan* pl, int head, int16_t* d_out, hipStream_t st);
+litevar_status export_dense(const litevar_plan* pl, int head, uint8_t* d_mask, uint64_t* d_count, hipStream_t st);
+litevar_status export_csr(const litevar_plan* pl, int head, int64_t* d_rowptr, int32_t* d_cols, size_t cap,
                           hipStream_t st);
 
 struct AttnArgs {
@@ -38,7 +55,8 @@ struct AttnArgs {
   const GroupDesc* groups; const WaveDesc* waves; const int32_t* phase_end;
   const int32_t* union_tok; const uint2* step_addr; const uint64_t* step_mask;
   const int32_t* step_tok;
-  int n_groups;
+  int n_groups;                  // groups of one head group
+  const int32_t* head_map;       // head -> head group, or nullptr when all heads share one
   int q_len;                     // query rows per (batch, head)
   Header* hdr;                   // the blob's header: checked by every kernel before the plan is used
   int spin_limit;                // polls after which a kernel's wait on an LDS flag gives up

@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <vector>
 
 namespace lv {
 
@@ -27,7 +28,8 @@ static void choose_tiling(Geom& g, int waves, int chunk, int depth, int spare) {
   }
 }
 
-litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* opts, Geom& g) {
+litevar_status make_spec(const litevar_mask_desc* d, const litevar_plan_opts* opts, PlanSpec& sp) {
+  Geom& g = sp.g;
   if (!d) return fail(LITEVAR_E_INVALID_ARG, "desc is NULL");
   if (d->n_scales < 1 || d->n_scales > kMaxScales)
     return fail(LITEVAR_E_INVALID_ARG, "n_scales must be in 1..%d (got %d)", kMaxScales, d->n_scales);
@@ -44,14 +46,42 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
     if (s > g.smax) g.smax = s;
   }
   g.off[g.K] = (int)L; g.L = (int)L;
-  for (int k = 0; k < g.K; ++k)
-    for (int j = 0; j < g.K; ++j) {
-      const int r = d->radius_per_scale_pair ? d->radius_per_scale_pair[k * g.K + j]
-                  : d->radius_per_key_scale ? d->radius_per_key_scale[j] : d->radius;
-      if (r < LITEVAR_RADIUS_DENSE)
-        return fail(LITEVAR_E_INVALID_ARG, "radius %d of key scale %d (query scale %d) is below -1", r, j, k);
-      g.rad[k][j] = (short)(r > kMaxSide ? kMaxSide : r);
-    }
+  if (d->mask_mode != LITEVAR_MASK_WINDOW_2D && d->mask_mode != LITEVAR_MASK_BAND_1D)
+    return fail(LITEVAR_E_INVALID_ARG, "unknown mask_mode %d", d->mask_mode);
+  g.mode = d->mask_mode == LITEVAR_MASK_BAND_1D ? kModeBand : kModeWindow;
+
+  // radius tables: one per head when radius_per_head is given (heads with equal tables are
+  // put into one head group and share its work-list), else one for all heads
+  if (d->n_heads < 0 || d->n_heads > kMaxHeads)
+    return fail(LITEVAR_E_INVALID_ARG, "n_heads must be in 0..%d (got %d)", kMaxHeads, d->n_heads);
+  if ((d->n_heads > 0) != (d->radius_per_head != nullptr))
+    return fail(LITEVAR_E_INVALID_ARG, "n_heads and radius_per_head must be given together");
+  const int KK = g.K * g.K;
+  sp.n_heads = d->n_heads;
+  sp.rad_all.clear();
+  const int n_tables = d->n_heads > 0 ? d->n_heads : 1;
+  int n_hg = 0;
+  std::vector<int16_t> tab(KK);
+  for (int h = 0; h < n_tables; ++h) {
+    for (int k = 0; k < g.K; ++k)
+      for (int j = 0; j < g.K; ++j) {
+        const int r = d->radius_per_head ? d->radius_per_head[(int64_t)h * KK + k * g.K + j]
+                    : d->radius_per_scale_pair ? d->radius_per_scale_pair[k * g.K + j]
+                    : d->radius_per_key_scale ? d->radius_per_key_scale[j] : d->radius;
+        if (r < LITEVAR_RADIUS_DENSE)
+          return fail(LITEVAR_E_INVALID_ARG, "radius %d of key scale %d (query scale %d) is below -1", r, j, k);
+        // (entries above the diagonal are never used: normalised so that equal tables compare equal)
+        tab[k * g.K + j] = j > k ? (int16_t)0 : (int16_t)(r > kMaxRadius ? kMaxRadius : r);
+      }
+    int found = -1;
+    for (int q = 0; q < n_hg && found < 0; ++q)
+      if (memcmp(&sp.rad_all[(size_t)q * KK], tab.data(), KK * sizeof(int16_t)) == 0) found = q;
+    if (found < 0) { found = n_hg++; sp.rad_all.insert(sp.rad_all.end(), tab.begin(), tab.end()); }
+    sp.head_group[h] = (uint8_t)found;
+  }
+  g.n_hg = n_hg;
+  sp.load_head_group(0);
+
   if (d->n_sink_scales < 0 || d->n_sink_scales > g.K)
     return fail(LITEVAR_E_INVALID_ARG, "n_sink_scales %d outside 0..%d", d->n_sink_scales, g.K);
   g.n_sink = d->n_sink_scales;
@@ -106,9 +136,10 @@ litevar_status make_geom(const litevar_mask_desc* d, const litevar_plan_opts* op
     const int k = g.qe - 1 - i;
     g.grp_off[i] = (int)ng;
     ng += (int64_t)groups_y(g, k) * groups_x(g, k);
-    np += (int64_t)patches_per_side(g, k) * patches_per_side(g, k);
+    np += (int64_t)scale_patches(g, k);
   }
   g.grp_off[g.qe - g.qb] = (int)ng;
+  if (ng * g.n_hg > (int64_t)1 << 26) return fail(LITEVAR_E_UNSUPPORTED, "too many groups");
   g.n_groups = (int)ng; g.n_patches = (int)np;
   return LITEVAR_OK;
 }
@@ -117,43 +148,64 @@ static uint64_t align256(uint64_t x) { return (x + 255) & ~(uint64_t)255; }
 
 // The sizing walk visits every (patch, key) pair on the host (tens of milliseconds for the
 // largest plans).  Callers size and then build with the same descriptor, often repeatedly,
-// so the last result is remembered per thread, keyed by the whole geometry.
-static thread_local struct { bool valid; Geom g; PlanSizes z; } g_last_sizing = {false, {}, {}};
+// so the last result is remembered per thread, keyed by the whole specification.
+static thread_local struct { bool valid; PlanSpec sp; PlanSizes z; } g_last_sizing = {false, {}, {}};
 
-static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z);
+static litevar_status size_plan_uncached(PlanSpec& sp, PlanSizes& z);
 
-litevar_status size_plan(const Geom& g, PlanSizes& z) {
-  if (g_last_sizing.valid && memcmp(&g_last_sizing.g, &g, sizeof g) == 0) { z = g_last_sizing.z; return LITEVAR_OK; }
-  const litevar_status rc = size_plan_uncached(g, z);
-  if (rc == LITEVAR_OK) { g_last_sizing.g = g; g_last_sizing.z = z; g_last_sizing.valid = true; }
+static bool same_spec(const PlanSpec& a, const PlanSpec& b) {
+  // (the Geom holds the radii of the head group that was loaded last: compare it with
+  // group 0 loaded on both sides, which is how make_spec leaves it)
+  return memcmp(&a.g, &b.g, sizeof a.g) == 0 && a.n_heads == b.n_heads && a.rad_all == b.rad_all &&
+         memcmp(a.head_group, b.head_group, sizeof a.head_group) == 0;
+}
+
+litevar_status size_plan(PlanSpec& sp, PlanSizes& z) {
+  if (g_last_sizing.valid && same_spec(g_last_sizing.sp, sp)) { z = g_last_sizing.z; return LITEVAR_OK; }
+  const litevar_status rc = size_plan_uncached(sp, z);
+  sp.load_head_group(0);
+  if (rc == LITEVAR_OK) { g_last_sizing.sp = sp; g_last_sizing.z = z; g_last_sizing.valid = true; }
   return rc;
 }
 
-static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z) {
+static litevar_status size_plan_uncached(PlanSpec& sp, PlanSizes& z) {
+  Geom& g = sp.g;
   memset(&z, 0, sizeof z);
-  for (int grp = 0; grp < g.n_groups; ++grp) {
-    int k, gy, gx;
-    group_coords(g, grp, k, gy, gx);
-    const GroupExtent e = group_extent(g, k, gy, gx);
-    const int nu = group_union_keys(g, e);
-    const int nph = (nu + g.C - 1) / g.C;
-    z.n_union += (int64_t)nph * g.C;
-    z.n_phase_entries += (int64_t)nph * g.NW;
-    for (int w = 0; w < g.NW; ++w) {
-      CountSink sink;
-      const int ns = walk_patch(g, e, patch_extent(g, k, gy, gx, w), sink);
-      if (ns > 65535) return fail(LITEVAR_E_UNSUPPORTED, "a query patch needs more than 65535 steps");
-      z.n_steps += ns;
-      z.retained_pairs += sink.pairs;
+  for (int hg = 0; hg < g.n_hg; ++hg) {
+    sp.load_head_group(hg);
+    const ArithWin win{g};
+    const ArithRad rad{g};
+    int64_t pairs_hg = 0;
+    for (int grp = 0; grp < g.n_groups; ++grp) {
+      int k, gy, gx;
+      group_coords(g, grp, k, gy, gx);
+      const GroupExtent e = group_extent(g, k, gy, gx);
+      const int nu = group_union_keys(g, win, rad, e);
+      const int nph = (nu + g.C - 1) / g.C;
+      z.n_union += (int64_t)nph * g.C;
+      z.n_phase_entries += (int64_t)nph * g.NW;
+      for (int w = 0; w < g.NW; ++w) {
+        CountSink sink;
+        const int ns = walk_patch(g, e, patch_extent(g, k, gy, gx, w), sink);
+        if (ns > 65535) return fail(LITEVAR_E_UNSUPPORTED, "a query patch needs more than 65535 steps");
+        z.n_steps += ns;
+        pairs_hg += sink.pairs;
+      }
     }
+    z.retained_pairs += pairs_hg;
+    if (hg < kMaxHeads) z.pairs_of_group[hg] = pairs_hg;
   }
   if (z.n_steps > (int64_t)1 << 26 || z.n_union > (int64_t)1 << 30)
     return fail(LITEVAR_E_UNSUPPORTED, "work-list too large (%lld steps)", (long long)z.n_steps);
+  const uint64_t ngt = (uint64_t)g.n_groups * g.n_hg;
   uint64_t o = 0;
   z.off[kSecHeader] = o; o += sizeof(Header);
-  z.off[kSecWin] = o; o = align256(o + (uint64_t)g.K * g.K * g.smax * 2 * sizeof(int16_t));
-  z.off[kSecGroups] = o; o = align256(o + (uint64_t)g.n_groups * sizeof(GroupDesc));
-  z.off[kSecWaves] = o; o = align256(o + (uint64_t)g.n_groups * g.NW * sizeof(WaveDesc));
+  z.off[kSecWin] = o;
+  o = align256(o + (g.mode == kModeWindow ? (uint64_t)g.n_hg * g.K * g.K * g.smax * 2 * sizeof(int16_t) : 0));
+  z.off[kSecRad] = o; o = align256(o + (uint64_t)g.n_hg * g.K * g.K * sizeof(int16_t));
+  z.off[kSecHeadMap] = o; o = align256(o + (uint64_t)kMaxHeads * sizeof(int32_t));
+  z.off[kSecGroups] = o; o = align256(o + ngt * sizeof(GroupDesc));
+  z.off[kSecWaves] = o; o = align256(o + ngt * g.NW * sizeof(WaveDesc));
   z.off[kSecPhaseEnd] = o; o = align256(o + (uint64_t)z.n_phase_entries * sizeof(int32_t));
   z.off[kSecUnion] = o; o = align256(o + (uint64_t)z.n_union * sizeof(int32_t));
   z.off[kSecStepAddr] = o; o = align256(o + (uint64_t)z.n_steps * 64 * sizeof(uint2));
@@ -167,14 +219,15 @@ static litevar_status size_plan_uncached(const Geom& g, PlanSizes& z) {
 // ---- device: builder kernels -------------------------------------------------
 
 struct BlobPtrs {
-  Header* hdr; int16_t* win; GroupDesc* groups; WaveDesc* waves; int32_t* phase_end;
-  int32_t* union_tok; uint2* step_addr; uint64_t* step_mask; int32_t* step_tok;
+  Header* hdr; int16_t* win; int16_t* rad; int32_t* head_map; GroupDesc* groups; WaveDesc* waves;
+  int32_t* phase_end; int32_t* union_tok; uint2* step_addr; uint64_t* step_mask; int32_t* step_tok;
 };
 
 static BlobPtrs blob_ptrs(void* blob, const uint64_t* off) {
   char* b = (char*)blob;
   BlobPtrs p;
   p.hdr = (Header*)(b + off[kSecHeader]); p.win = (int16_t*)(b + off[kSecWin]);
+  p.rad = (int16_t*)(b + off[kSecRad]); p.head_map = (int32_t*)(b + off[kSecHeadMap]);
   p.groups = (GroupDesc*)(b + off[kSecGroups]); p.waves = (WaveDesc*)(b + off[kSecWaves]);
   p.phase_end = (int32_t*)(b + off[kSecPhaseEnd]); p.union_tok = (int32_t*)(b + off[kSecUnion]);
   p.step_addr = (uint2*)(b + off[kSecStepAddr]); p.step_mask = (uint64_t*)(b + off[kSecStepMask]);
@@ -184,40 +237,115 @@ static BlobPtrs blob_ptrs(void* blob, const uint64_t* off) {
 
 struct Caps { int64_t n_steps, n_union, n_phase_entries, retained_pairs; uint64_t bytes; };
 
-// K1: win[k][j][c] = inclusive [lo, hi]; (-1,-1) where undefined
-__global__ void k_window_table(Geom g, int16_t* win) {
+// K1, once per head group (g.rad holds that group's radii): the radius table
+// rad[hg][k][j] (-1: dense part) and, in window mode, the window table
+// win[hg][k][j][c] = inclusive [lo, hi]; (-1,-1) where undefined.  Every other builder
+// kernel reads these tables and never the radii of the descriptor.
+__global__ void k_tables(Geom g, int hg, int16_t* win, int16_t* rad) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < g.K * g.K) {
+    const int j = idx % g.K, k = idx / g.K;
+    rad[(size_t)hg * g.K * g.K + idx] = j > k ? (int16_t)0 : (j < g.n_sink ? (int16_t)-1 : g.rad[k][j]);
+  }
+  if (g.mode != kModeWindow) return;
   const int total = g.K * g.K * g.smax;
   if (idx >= total) return;
   const int c = idx % g.smax, j = (idx / g.smax) % g.K, k = idx / (g.smax * g.K);
   Interval iv = {-1, -1};
   if (j <= k && c < g.s[k]) iv = win_interval(g, k, j, c);
-  win[2 * idx] = (int16_t)iv.lo; win[2 * idx + 1] = (int16_t)iv.hi;
+  int16_t* out = win + ((size_t)hg * total + idx) * 2;
+  out[0] = (int16_t)iv.lo; out[1] = (int16_t)iv.hi;
 }
 
-// Wave-cooperative form of walk_patch(): the 64 lanes of a wave take 64 consecutive keys of
-// the patch's box in a key scale at a time (several rows of a narrow box, or 64 columns of
-// one row).  The kept keys of a pass get consecutive places in the
-// patch's key list; a pass is cut where a step fills up (32 keys) or where the next key's
-// 2^logS-key block lies more than A blocks after the block of the step's first key, exactly
-// as in the serial walk, so both produce the same steps.  Sink receives
+struct HeadMapArg { uint8_t group[kMaxHeads]; };
+
+__global__ void k_head_map(HeadMapArg m, int n_heads, int32_t* out) {
+  const int i = threadIdx.x;
+  if (i < kMaxHeads) out[i] = i < n_heads ? m.group[i] : 0;
+}
+
+// Placement of the kept keys of one pass (64 candidate keys, one per lane, in key order) in
+// the patch's steps: they get consecutive places; a pass is cut where a step fills up (32
+// keys) or where the next key's 2^logS-key block lies more than A blocks after the block of
+// the step's first key, exactly as in the serial walk, so both produce the same steps.
+// Sink receives
 //   keys(step, idx, upos, token, qmask, take)   per pass segment: lanes with take set hold
 //                                               the key that becomes entry idx of the step
 //   close(step, n_keys, last_upos)              when a step is complete (wave-uniform)
 template <class Sink>
-__device__ int wave_walk_patch(const Geom& g, const GroupExtent& e, const PatchExtent& p, Sink& sink, int lane) {
+struct WavePacker {
+  const Geom& g; Sink& sink; int lane;
+  int step = 0, cnt = 0, first_block = 0, last_upos = 0;
+  __device__ void pass(bool kept, int upos, int tok, unsigned qmask) {
+    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    const int blk = upos >> g.logS;
+    uint64_t km = __ballot(kept);                     // kept keys of this pass not yet placed
+    while (km) {
+      const int fl = __builtin_ctzll(km);
+      const int fblk = __shfl(blk, fl);
+      if (cnt > 0 && fblk - first_block > g.A) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
+      if (cnt == 0) first_block = fblk;
+      const bool mine = (km >> lane) & 1;
+      // lanes whose key still fits the step's span (blocks grow with the lane), ranked
+      const uint64_t fit = __ballot(mine && blk - first_block <= g.A);
+      const int rank = __builtin_popcountll(fit & lt_mask);
+      const bool take = ((fit >> lane) & 1) && rank < kStepKeys - cnt;
+      const uint64_t tm = __ballot(take);
+      sink.keys(step, cnt + rank, upos, tok, qmask, take);
+      last_upos = __shfl(upos, 63 - __builtin_clzll(tm));
+      cnt += __builtin_popcountll(tm);
+      km &= ~tm;
+      if (cnt == kStepKeys) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
+    }
+  }
+  __device__ int finish() {
+    if (cnt > 0) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
+    return step;
+  }
+};
+
+// Wave-cooperative form of walk_patch(): the 64 lanes of a wave take 64 consecutive candidate
+// keys at a time (window mode: several rows of a narrow box, or 64 columns of one row of the
+// patch's box in a key scale; band mode: 64 columns of the patch's range in a part).
+template <class Sink>
+__device__ int wave_walk_patch(const Geom& g, const TableWin& win, const TableRad& rad, const GroupExtent& e,
+                               const PatchExtent& p, Sink& sink, int lane) {
   if (p.ny == 0) return 0;
-  const int logS = g.logS, A = g.A;
-  const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  int step = 0, cnt = 0, first_block = 0, last_upos = 0, ubase = 0;
+  WavePacker<Sink> pack{g, sink, lane};
+  int ubase = 0;
+  if (g.mode == kModeBand) {
+    const int nk = g.s[e.k] * g.s[e.k];
+    for (int pt = 0; pt < band_parts(e.k); ++pt) {
+      const BandPart b = band_part(g, rad, e.k, pt);
+      const int glo = band_interval(b, nk, e.qy0).lo, ghi = band_interval(b, nk, e.qy1).hi;
+      // the sixteen queries' intervals: one lane each (a 64-bit division), handed round
+      Interval mine = {1, 0};
+      if (lane < p.nx) mine = band_interval(b, nk, p.y0 + lane);
+      Interval iv[kPatchQueries];
+#pragma unroll
+      for (int n = 0; n < kPatchQueries; ++n) { iv[n].lo = __shfl(mine.lo, n); iv[n].hi = __shfl(mine.hi, n); }
+      const int clo = iv[0].lo, chi = __shfl(mine.hi, p.nx - 1);
+      for (int c0 = clo; c0 <= chi; c0 += 64) {
+        const int c = c0 + lane;
+        unsigned qmask = 0;
+        if (c <= chi) {
+#pragma unroll
+          for (int n = 0; n < kPatchQueries; ++n) qmask |= (unsigned)(c >= iv[n].lo && c <= iv[n].hi) << n;
+        }
+        pack.pass(qmask != 0, ubase + c - glo, b.tok0 + c, qmask);
+      }
+      ubase += ghi - glo + 1;
+    }
+    return pack.finish();
+  }
   for (int j = 0; j <= e.k; ++j) {
     // The twelve window intervals of this key scale (four patch rows, four patch columns, the
-    // group's first and last row and column) are computed by twelve lanes at once -- each
-    // costs an integer division -- and handed round with v_readlane.
+    // group's first and last row and column) are fetched from the table by twelve lanes at
+    // once and handed round with v_readlane.
     const int sk = g.s[e.k];
     int cq = lane < 4 ? p.y0 + lane : lane < 8 ? p.x0 + lane - 4 : lane == 8 ? e.qy0 : lane == 9 ? e.qy1 : lane == 10 ? e.qx0 : e.qx1;
     cq = cq < sk ? cq : sk - 1;
-    const Interval mine_iv = win_interval(g, e.k, j, cq);
+    const Interval mine_iv = win(e.k, j, cq);
     const Interval none = {1, 0};
     Interval rw[kPatch], cw[kPatch];
 #pragma unroll
@@ -256,32 +384,12 @@ __device__ int wave_walk_patch(const Geom& g, const GroupExtent& e, const PatchE
 #pragma unroll
           for (int d = 0; d < kPatch; ++d) cb |= (unsigned)(x >= cw[d].lo && x <= cw[d].hi) << d;
         }
-        const unsigned qmask = (cb * 0x1111u) & rowmask;
-        const int upos = urow + x, blk = upos >> logS;
-        uint64_t km = __ballot(cb != 0);                // kept keys of this pass not yet placed
-        while (km) {
-          const int fl = __builtin_ctzll(km);
-          const int fblk = __shfl(blk, fl);
-          if (cnt > 0 && fblk - first_block > A) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
-          if (cnt == 0) first_block = fblk;
-          const bool mine = (km >> lane) & 1;
-          // lanes whose key still fits the step's span (blocks grow with the lane), ranked
-          const uint64_t fit = __ballot(mine && blk - first_block <= A);
-          const int rank = __builtin_popcountll(fit & lt_mask);
-          const bool take = ((fit >> lane) & 1) && rank < kStepKeys - cnt;
-          const uint64_t tm = __ballot(take);
-          sink.keys(step, cnt + rank, upos, trow + x, qmask, take);
-          last_upos = __shfl(upos, 63 - __builtin_clzll(tm));
-          cnt += __builtin_popcountll(tm);
-          km &= ~tm;
-          if (cnt == kStepKeys) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
-        }
+        pack.pass(cb != 0, urow + x, trow + x, (cb * 0x1111u) & rowmask);
       }
     }
     ubase += (gb.yhi - gb.ylo + 1) * gw;
   }
-  if (cnt > 0) { sink.close(step, cnt, last_upos); ++step; }
-  return step;
+  return pack.finish();
 }
 
 struct WaveCountSink {
@@ -290,46 +398,72 @@ struct WaveCountSink {
   __device__ void close(int, int, int) {}
 };
 
+// the tables of the head group that global group G belongs to
+struct GroupTables { TableWin win; TableRad rad; int grp; };
+__device__ inline GroupTables group_tables(const Geom& g, const BlobPtrs& p, int G) {
+  const int hg = G / g.n_groups;
+  GroupTables t;
+  t.win = TableWin{p.win + (size_t)hg * g.K * g.K * g.smax * 2, g.K, g.smax};
+  t.rad = TableRad{p.rad + (size_t)hg * g.K * g.K, g.K};
+  t.grp = G - hg * g.n_groups;
+  return t;
+}
+
 // K2a: one wave per (group, patch): number of steps and kept pairs; patch 0 also
 // sizes the group's union list
 __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
   const int idx = blockIdx.x, lane = threadIdx.x;
-  const int grp = idx / g.NW, w = idx % g.NW;
+  const int G = idx / g.NW, w = idx % g.NW;
+  const GroupTables t = group_tables(g, p, G);
   int k, gy, gx;
-  group_coords(g, grp, k, gy, gx);
+  group_coords(g, t.grp, k, gy, gx);
   const GroupExtent e = group_extent(g, k, gy, gx);
   const PatchExtent pe = patch_extent(g, k, gy, gx, w);
   WaveCountSink sink;
-  const int ns = wave_walk_patch(g, e, pe, sink, lane);
+  const int ns = wave_walk_patch(g, t.win, t.rad, e, pe, sink, lane);
   int pairs = sink.pairs;
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) pairs += __shfl_xor(pairs, d);
   if (lane == 0) {
     WaveDesc wd;
+    int q_base, sk; uint32_t valid;
+    patch_queries(g, k, pe, q_base, sk, valid);
     wd.step_begin = 0; wd.n_steps = ns;
-    wd.q_base = g.off[k] - g.q0 + pe.y0 * g.s[k] + pe.x0;
-    wd.sk = (int16_t)g.s[k]; wd.ny = (int16_t)pe.ny; wd.nx = (int16_t)pe.nx; wd.kq = (int16_t)k;
-    wd.pairs = pairs; wd.pad[0] = wd.pad[1] = 0;
+    wd.q_base = q_base;
+    wd.sk = (int16_t)sk; wd.ny = (int16_t)pe.ny; wd.nx = (int16_t)pe.nx; wd.kq = (int16_t)k;
+    wd.pairs = pairs; wd.valid = valid; wd.pad = 0;
     p.waves[idx] = wd;
   }
   if (w == 0 && lane == 0) {
     GroupDesc gd;
-    gd.union_base = 0; gd.n_union = group_union_keys(g, e);
+    gd.union_base = 0; gd.n_union = group_union_keys(g, t.win, t.rad, e);
     gd.n_phases = (gd.n_union + g.C - 1) / g.C;
     gd.k = k; gd.gy = gy; gd.gx = gx; gd.phase_base = 0;
-    // leading union entries whose token equals their position: whole key scales from
-    // scale 0 on, then the first rows of the next box if it starts at the scale's origin
+    // leading union entries whose token equals their position
     int ident = 0;
-    for (int j = 0; j <= k; ++j) {
-      const Box b = window_box(g, k, j, e.qy0, e.qy1, e.qx0, e.qx1);
-      const int gw = b.xhi - b.xlo + 1, rows = b.yhi - b.ylo + 1;
-      if (b.ylo != 0 || b.xlo != 0 || g.off[j] != ident) break;
-      if (gw != g.s[j]) { ident += gw; break; }
-      ident += rows * gw;
-      if (rows != g.s[j]) break;
+    if (g.mode == kModeBand) {
+      const int nk = g.s[k] * g.s[k];
+      for (int pt = 0; pt < band_parts(k); ++pt) {
+        const BandPart b = band_part(g, t.rad, k, pt);
+        const int glo = band_interval(b, nk, e.qy0).lo, ghi = band_interval(b, nk, e.qy1).hi;
+        if (b.tok0 + glo != ident) break;
+        ident += ghi - glo + 1;
+        if (ghi != b.cols - 1) break;
+      }
+    } else {
+      // whole key scales from scale 0 on, then the first rows of the next box if it starts
+      // at the scale's origin
+      for (int j = 0; j <= k; ++j) {
+        const Box b = window_box(t.win, k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+        const int gw = b.xhi - b.xlo + 1, rows = b.yhi - b.ylo + 1;
+        if (b.ylo != 0 || b.xlo != 0 || g.off[j] != ident) break;
+        if (gw != g.s[j]) { ident += gw; break; }
+        ident += rows * gw;
+        if (rows != g.s[j]) break;
+      }
     }
     gd.ident = ident;
-    p.groups[grp] = gd;
+    p.groups[G] = gd;
   }
 }
 
@@ -339,9 +473,10 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
 __global__ __launch_bounds__(1024) void k_scan(Geom g, BlobPtrs p, Caps caps) {
   __shared__ int64_t part[2][4][1024];
   const int t = threadIdx.x;
-  const int per = (g.n_groups + 1023) / 1024;
-  const int g0 = t * per < g.n_groups ? t * per : g.n_groups;
-  const int g1 = g0 + per < g.n_groups ? g0 + per : g.n_groups;
+  const int n_all = g.n_groups * g.n_hg;
+  const int per = (n_all + 1023) / 1024;
+  const int g0 = t * per < n_all ? t * per : n_all;
+  const int g1 = g0 + per < n_all ? g0 + per : n_all;
   int64_t v[4] = {0, 0, 0, 0};                          // steps, union keys, phase entries, pairs
   for (int grp = g0; grp < g1; ++grp) {
     v[1] += (int64_t)p.groups[grp].n_phases * g.C; v[2] += (int64_t)p.groups[grp].n_phases * g.NW;
@@ -371,31 +506,44 @@ __global__ __launch_bounds__(1024) void k_scan(Geom g, BlobPtrs p, Caps caps) {
     Header h;
     memset(&h, 0, sizeof h);
     h.magic = kMagic; h.blob_bytes = caps.bytes;
-    h.n_groups = g.n_groups; h.n_waves = g.n_groups * g.NW;
+    h.n_groups = n_all; h.n_waves = n_all * g.NW;
     h.n_steps = part[cur][0][t]; h.n_union = part[cur][1][t]; h.n_phase_entries = part[cur][2][t];
     h.retained_pairs = part[cur][3][t];
     h.error = (h.n_steps != caps.n_steps || h.n_union != caps.n_union ||
-               h.n_phase_entries != caps.n_phase_entries || h.retained_pairs != caps.retained_pairs) ? 1 : 0;
+               h.n_phase_entries != caps.n_phase_entries || h.retained_pairs != caps.retained_pairs) ? kErrBuilder : kErrNone;
     *p.hdr = h;
   }
 }
 
 // K2c: the group's key list (token indices), padded to whole chunks with its last key
 __global__ void k_fill_union(Geom g, BlobPtrs p, Caps caps) {
-  const int grp = blockIdx.x;
+  const int G = blockIdx.x;
   if (p.hdr->error) return;
-  const GroupDesc gd = p.groups[grp];
+  const GroupTables t = group_tables(g, p, G);
+  const GroupDesc gd = p.groups[G];
   const GroupExtent e = group_extent(g, gd.k, gd.gy, gd.gx);
   int32_t* out = p.union_tok + gd.union_base;
   if ((int64_t)gd.union_base + (int64_t)gd.n_phases * g.C > caps.n_union) return;
   int ubase = 0, last_tok = 0;
-  for (int j = 0; j <= e.k; ++j) {
-    const Box b = window_box(g, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
-    const int gw = b.xhi - b.xlo + 1, n = (b.yhi - b.ylo + 1) * gw;
-    for (int i = threadIdx.x; i < n; i += blockDim.x)
-      out[ubase + i] = g.off[j] + (b.ylo + i / gw) * g.s[j] + b.xlo + i % gw;
-    ubase += n;
-    last_tok = g.off[j] + b.yhi * g.s[j] + b.xhi;
+  if (g.mode == kModeBand) {
+    const int nk = g.s[e.k] * g.s[e.k];
+    for (int pt = 0; pt < band_parts(e.k); ++pt) {
+      const BandPart b = band_part(g, t.rad, e.k, pt);
+      const int glo = band_interval(b, nk, e.qy0).lo, ghi = band_interval(b, nk, e.qy1).hi;
+      const int n = ghi - glo + 1;
+      for (int i = threadIdx.x; i < n; i += blockDim.x) out[ubase + i] = b.tok0 + glo + i;
+      ubase += n;
+      last_tok = b.tok0 + ghi;
+    }
+  } else {
+    for (int j = 0; j <= e.k; ++j) {
+      const Box b = window_box(t.win, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+      const int gw = b.xhi - b.xlo + 1, n = (b.yhi - b.ylo + 1) * gw;
+      for (int i = threadIdx.x; i < n; i += blockDim.x)
+        out[ubase + i] = g.off[j] + (b.ylo + i / gw) * g.s[j] + b.xlo + i % gw;
+      ubase += n;
+      last_tok = g.off[j] + b.yhi * g.s[j] + b.xhi;
+    }
   }
   for (int i = gd.n_union + threadIdx.x; i < gd.n_phases * g.C; i += blockDim.x) out[i] = last_tok;
 }
@@ -452,8 +600,9 @@ __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps
   __shared__ StepBuf buf;
   const int idx = blockIdx.x, lane = threadIdx.x;
   if (p.hdr->error) return;
-  const int grp = idx / g.NW, w = idx % g.NW;
-  const GroupDesc gd = p.groups[grp];
+  const int G = idx / g.NW, w = idx % g.NW;
+  const GroupTables t = group_tables(g, p, G);
+  const GroupDesc gd = p.groups[G];
   const WaveDesc wd = p.waves[idx];
   if ((int64_t)wd.step_begin + wd.n_steps > caps.n_steps ||
       (int64_t)gd.phase_base + (int64_t)gd.n_phases * g.NW > caps.n_phase_entries) return;
@@ -466,7 +615,7 @@ __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps
   sink.mask = p.step_mask + (int64_t)wd.step_begin * 8;
   sink.toks = p.step_tok + (int64_t)wd.step_begin * kStepKeys;
   sink.phase_cnt = pe; sink.buf = &buf; sink.R = g.R; sink.logC = g.logC; sink.lane = lane;
-  wave_walk_patch(g, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink, lane);
+  wave_walk_patch(g, t.win, t.rad, e, patch_extent(g, gd.k, gd.gy, gd.gx, w), sink, lane);
   __syncthreads();
   if (lane == 0) {
     int acc = 0;
@@ -474,24 +623,33 @@ __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps
   }
 }
 
-litevar_status build_plan(const Geom& g, const PlanSizes& z, void* d_blob, hipStream_t st) {
+litevar_status build_plan(PlanSpec& sp, const PlanSizes& z, void* d_blob, hipStream_t st) {
+  Geom& g = sp.g;
   const BlobPtrs p = blob_ptrs(d_blob, z.off);
   Caps caps{z.n_steps, z.n_union, z.n_phase_entries, z.retained_pairs, z.bytes};
-  const int nwin = g.K * g.K * g.smax;
-  hipLaunchKernelGGL(k_window_table, dim3((nwin + 255) / 256), dim3(256), 0, st, g, p.win);
-  const int nw = g.n_groups * g.NW;
+  const int ntab = g.mode == kModeWindow ? g.K * g.K * g.smax : g.K * g.K;
+  for (int hg = 0; hg < g.n_hg; ++hg) {
+    sp.load_head_group(hg);
+    hipLaunchKernelGGL(k_tables, dim3((ntab + 255) / 256), dim3(256), 0, st, g, hg, p.win, p.rad);
+  }
+  sp.load_head_group(0);
+  HeadMapArg hm;
+  memcpy(hm.group, sp.head_group, sizeof hm.group);
+  hipLaunchKernelGGL(k_head_map, dim3(1), dim3(kMaxHeads), 0, st, hm, sp.n_heads, p.head_map);
+  const int n_all = g.n_groups * g.n_hg;
+  const int nw = n_all * g.NW;
   hipLaunchKernelGGL(k_count, dim3(nw), dim3(64), 0, st, g, p);
   hipLaunchKernelGGL(k_scan, dim3(1), dim3(1024), 0, st, g, p, caps);
-  hipLaunchKernelGGL(k_fill_union, dim3(g.n_groups), dim3(256), 0, st, g, p, caps);
+  hipLaunchKernelGGL(k_fill_union, dim3(n_all), dim3(256), 0, st, g, p, caps);
   hipLaunchKernelGGL(k_fill_steps, dim3(nw), dim3(64), 0, st, g, p, caps);
   return hip_check(hipGetLastError(), "plan builder launch");
 }
 
 // ---- parity exports -------------------------------------------------------------
 
-__global__ void k_export_win(int K, int smax, const int16_t* win, int16_t* out) {
+__global__ void k_export_win(int n, const int16_t* win, int16_t* out) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < K * K * smax * 2) out[idx] = win[idx];
+  if (idx < n) out[idx] = win[idx];
 }
 
 __global__ void k_fill_u8(uint8_t* p, size_t n, uint8_t v) {
@@ -504,15 +662,14 @@ __global__ void k_zero_u64(unsigned long long* p) { if (threadIdx.x == 0 && bloc
 
 // local query row handled by column n of a patch, or -1
 __device__ inline int patch_query_row(const WaveDesc& wd, int n) {
-  const int dy = n / 4, dx = n % 4;
-  return (dy < wd.ny && dx < wd.nx) ? wd.q_base + dy * wd.sk + dx : -1;
+  return ((wd.valid >> n) & 1u) ? wd.q_base + (n / 4) * wd.sk + n % 4 : -1;
 }
 
-// one 64-lane block per (group, wave); lane (n, g4) owns the bits of query n for the
-// keys {16t + 4*g4 + i} of every step
-__global__ void k_export_dense(int L, const WaveDesc* waves, const uint64_t* masks,
-                               const int32_t* toks, uint8_t* mask, unsigned long long* count) {
-  const WaveDesc wd = waves[blockIdx.x];
+// one 64-lane block per (group, wave) of the head's group; lane (n, g4) owns the bits of
+// query n for the keys {16t + 4*g4 + i} of every step
+__global__ void k_export_dense(int L, const WaveDesc* waves, const int32_t* head_map, int head, int waves_per_hg,
+                               const uint64_t* masks, const int32_t* toks, uint8_t* mask, unsigned long long* count) {
+  const WaveDesc wd = waves[(size_t)head_map[head] * waves_per_hg + blockIdx.x];
   const int lane = threadIdx.x, n = lane % 16, g4 = lane / 16;
   const int qrow = patch_query_row(wd, n);
   unsigned long long local = 0;
@@ -527,8 +684,9 @@ __global__ void k_export_dense(int L, const WaveDesc* waves, const uint64_t* mas
   if (count && local) atomicAdd(count, local);
 }
 
-__global__ void k_csr_count(const WaveDesc* waves, const uint64_t* masks, int64_t* rowptr) {
-  const WaveDesc wd = waves[blockIdx.x];
+__global__ void k_csr_count(const WaveDesc* waves, const int32_t* head_map, int head, int waves_per_hg,
+                            const uint64_t* masks, int64_t* rowptr) {
+  const WaveDesc wd = waves[(size_t)head_map[head] * waves_per_hg + blockIdx.x];
   const int lane = threadIdx.x, n = lane % 16;
   int cnt = 0;
   for (int s = 0; s < wd.n_steps; ++s)
@@ -558,9 +716,9 @@ __global__ void k_csr_scan(int64_t* rowptr, int n) {
 }
 
 // 16 threads per patch, one per query: walk the steps in order and list the kept tokens
-__global__ void k_csr_fill(const WaveDesc* waves, const uint64_t* masks, const int32_t* toks,
-                           const int64_t* rowptr, int32_t* cols, int64_t cap) {
-  const WaveDesc wd = waves[blockIdx.x];
+__global__ void k_csr_fill(const WaveDesc* waves, const int32_t* head_map, int head, int waves_per_hg,
+                           const uint64_t* masks, const int32_t* toks, const int64_t* rowptr, int32_t* cols, int64_t cap) {
+  const WaveDesc wd = waves[(size_t)head_map[head] * waves_per_hg + blockIdx.x];
   const int n = threadIdx.x;
   const int qrow = patch_query_row(wd, n);
   if (n >= 16 || qrow < 0) return;
@@ -578,33 +736,35 @@ __global__ void k_csr_fill(const WaveDesc* waves, const uint64_t* masks, const i
   }
 }
 
-litevar_status export_window_table(const litevar_plan* pl, int16_t* d_out, hipStream_t st) {
+static int head_group_of(const litevar_plan* pl, int head) { return pl->n_heads > 0 ? pl->head_group[head] : 0; }
+
+litevar_status export_window_table(const litevar_plan* pl, int head, int16_t* d_out, hipStream_t st) {
   const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
   const int n = pl->n_scales * pl->n_scales * pl->side_max * 2;
-  hipLaunchKernelGGL(k_export_win, dim3((n + 255) / 256), dim3(256), 0, st, pl->n_scales,
-                     pl->side_max, p.win, d_out);
+  hipLaunchKernelGGL(k_export_win, dim3((n + 255) / 256), dim3(256), 0, st, n,
+                     p.win + (size_t)head_group_of(pl, head) * n, d_out);
   return hip_check(hipGetLastError(), "window table export launch");
 }
 
-litevar_status export_dense(const litevar_plan* pl, uint8_t* d_mask, uint64_t* d_count,
+litevar_status export_dense(const litevar_plan* pl, int head, uint8_t* d_mask, uint64_t* d_count,
                             hipStream_t st) {
   const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
   const size_t n = (size_t)pl->q_len * pl->kv_len;
   hipLaunchKernelGGL(k_fill_u8, dim3(2048), dim3(256), 0, st, d_mask, n, (uint8_t)0);
   if (d_count) hipLaunchKernelGGL(k_zero_u64, dim3(1), dim3(64), 0, st, (unsigned long long*)d_count);
-  hipLaunchKernelGGL(k_export_dense, dim3(pl->n_groups * pl->waves_per_group), dim3(64), 0, st,
-                     pl->kv_len, p.waves, p.step_mask, p.step_tok, d_mask,
-                     (unsigned long long*)d_count);
+  const int nw = pl->n_groups * pl->waves_per_group;
+  hipLaunchKernelGGL(k_export_dense, dim3(nw), dim3(64), 0, st, pl->kv_len, p.waves, p.head_map, head, nw,
+                     p.step_mask, p.step_tok, d_mask, (unsigned long long*)d_count);
   return hip_check(hipGetLastError(), "dense mask export launch");
 }
 
-litevar_status export_csr(const litevar_plan* pl, int64_t* d_rowptr, int32_t* d_cols, size_t cap,
+litevar_status export_csr(const litevar_plan* pl, int head, int64_t* d_rowptr, int32_t* d_cols, size_t cap,
                           hipStream_t st) {
   const BlobPtrs p = blob_ptrs(pl->d_blob, pl->off);
   const int nw = pl->n_groups * pl->waves_per_group;
-  hipLaunchKernelGGL(k_csr_count, dim3(nw), dim3(64), 0, st, p.waves, p.step_mask, d_rowptr);
+  hipLaunchKernelGGL(k_csr_count, dim3(nw), dim3(64), 0, st, p.waves, p.head_map, head, nw, p.step_mask, d_rowptr);
   hipLaunchKernelGGL(k_csr_scan, dim3(1), dim3(1024), 0, st, d_rowptr, pl->q_len);
-  hipLaunchKernelGGL(k_csr_fill, dim3(nw), dim3(64), 0, st, p.waves, p.step_mask, p.step_tok,
+  hipLaunchKernelGGL(k_csr_fill, dim3(nw), dim3(64), 0, st, p.waves, p.head_map, head, nw, p.step_mask, p.step_tok,
                      d_rowptr, d_cols, (int64_t)cap);
   return hip_check(hipGetLastError(), "csr export launch");
 }

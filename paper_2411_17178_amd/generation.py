@@ -21,9 +21,7 @@ class GenerationLayer:
     def __init__(self, scales, radius, radius_per_key_scale=None, n_sink_scales=0,
                  waves_per_group=0, device="cuda", batch_heads=0):
         self.scales = [int(s) for s in scales]
-        self.offsets = [0]
-        for s in self.scales:
-            self.offsets.append(self.offsets[-1] + s * s)
+        self.offsets = binding.litevar_scale_offsets(self.scales)   # the library's scale table
         self.kv_len = self.offsets[-1]
         self.plans = [
             binding.litevar_mask_build(self.scales, radius, radius_per_key_scale, n_sink_scales,

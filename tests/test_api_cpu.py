@@ -42,12 +42,17 @@ def test_plan_struct_matches_header(lv, tmp_path):
     src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "litevar.h"\n'
                    'int main(void){printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(litevar_plan), '
                    'sizeof(litevar_plan_opts), sizeof(litevar_mask_desc), offsetof(litevar_plan, n_steps), '
-                   'offsetof(litevar_plan, off), offsetof(litevar_plan, n_sink_scales));return 0;}\n')
+                   'offsetof(litevar_plan, off), offsetof(litevar_plan, n_sink_scales));'
+                   'printf("%zu %zu %zu %zu\\n", offsetof(litevar_plan, head_group), '
+                   'offsetof(litevar_plan, retained_pairs_of_group), offsetof(litevar_mask_desc, radius_per_head), '
+                   'offsetof(litevar_mask_desc, mask_mode));return 0;}\n')
     exe = tmp_path / "sz"
     subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     assert got == [C.sizeof(_Plan), C.sizeof(_PlanOpts), C.sizeof(_MaskDesc), _Plan.n_steps.offset,
-                   _Plan.off.offset, _Plan.n_sink_scales.offset]
+                   _Plan.off.offset, _Plan.n_sink_scales.offset, _Plan.head_group.offset,
+                   _Plan.retained_pairs_of_group.offset, _MaskDesc.radius_per_head.offset,
+                   _MaskDesc.mask_mode.offset]
 
 
 def _totals():
@@ -119,12 +124,12 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu(lv):
     rc = lib.litevar_windowed_attn_fwd(C.byref(stats), p, p, p, p, 1, 1, 64, 0, None, None, None,
                                        C.c_float(0.125), None, C.c_uint32(0), None)
     assert rc == -5
-    assert lib.litevar_mask_export_dense(C.byref(stats), p, C.c_size_t(1 << 20), None, None) == -5
-    assert lib.litevar_mask_export_csr(C.byref(stats), p, p, C.c_size_t(1 << 20), None) == -5
-    assert lib.litevar_window_table_export(C.byref(stats), p, C.c_size_t(1 << 20), None) == -5
+    assert lib.litevar_mask_export_dense(C.byref(stats), 0, p, C.c_size_t(1 << 20), None, None) == -5
+    assert lib.litevar_mask_export_csr(C.byref(stats), 0, p, p, C.c_size_t(1 << 20), None) == -5
+    assert lib.litevar_window_table_export(C.byref(stats), 0, p, C.c_size_t(1 << 20), None) == -5
     assert lib.litevar_plan_check(None, None) == -1
     # forge a "built" handle to reach the argument checks of the attention call (still no HIP call)
-    stats.magic = 0x4c56415257494e31
+    stats.magic = 0x4c56415257494e32
     stats.d_blob = 4096
     f = lambda **kw: lib.litevar_windowed_attn_fwd(  # noqa: E731
         C.byref(stats), kw.get("q", p), p, p, kw.get("o", C.c_void_p(8192)), kw.get("B", 2),
@@ -197,3 +202,28 @@ def test_bench_refuses_more_than_one_gpu():
                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
     assert res.returncode != 0
     assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_host_sizing_of_band_mode_and_per_head_plans_matches_the_oracle(lv):
+    import numpy as np
+    import oracle
+    scales = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+    for waves in (4, 8, 16):
+        for rad, q_scales in ((2, None), (24, (9, 10)), (0, None)):
+            st = lv.litevar_mask_plan_stats(scales, rad, None, 0, q_scales, waves, mask_mode=1)
+            assert st.mask_mode == 1
+            assert st.retained_pairs == int(oracle.row_counts(scales, [rad] * 10, 0, q_scales, mode=1).sum())
+    g = np.random.default_rng(3)
+    tabs = g.integers(-1, 5, size=(3, 10, 10))
+    tabs = tabs[[0, 1, 0, 2, 1]]                      # five heads, three distinct tables
+    for mode in (0, 1):
+        st = lv.litevar_mask_plan_stats(scales, 0, tabs.tolist(), 2, None, 16, mask_mode=mode)
+        assert st.n_heads == 5 and st.n_head_groups == 3
+        assert [st.head_group[h] for h in range(5)] == [0, 1, 0, 2, 1]
+        per_group = [int(oracle.row_counts(scales, tabs[h], 2, mode=mode).sum()) for h in (0, 1, 3)]
+        assert [int(st.retained_pairs_of_group[i]) for i in range(3)] == per_group
+        assert st.retained_pairs == sum(per_group)
+    E = lv.LitevarError
+    import pytest as _pytest
+    with _pytest.raises(E):
+        lv.litevar_mask_plan_stats(scales, 1, mask_mode=2)
