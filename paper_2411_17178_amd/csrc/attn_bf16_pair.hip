@@ -183,7 +183,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // descriptors, phase tables, the extent of the group's steps) is fetched before the first
   // vector memory operation: behind the burst of first chunks of all workgroups a scalar
   // miss would take microseconds, and the vector loads below depend on these values.
-  // Patch descriptor words: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16, pairs, valid}
+  // Patch descriptor words: {step_begin, n_steps, q_base, sk | ny << 16, nx | kq << 16, pairs, valid, first_ends}
   // (two patches per wave: p and its partner two patch rows below, columns swapped)
   const int pa = wave, pb_ = PW == 2 ? ((wave >> 2) + 2) * 4 + ((wave & 3) ^ 1) : wave;
   const const_i32_ptr wA = (const_i32_ptr)(a.waves + grp_g * 16 + pa), wB = (const_i32_ptr)(a.waves + grp_g * 16 + pb_);
@@ -197,8 +197,11 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
   // phase p + 2 is fetched during phase p
   // (one patch per wave: the second patch's counts are the constant 0 and its code goes away)
-  int endA = peA[0], endB = PW == 2 ? peB[0] : 0;
-  int end1A = peA[last_chunk(1)], end1B = PW == 2 ? peB[last_chunk(1)] : 0;
+  // (those of phases 0 and 1 sit in the patch descriptor, so that nothing the first vector
+  // loads depend on waits for a second round of scalar loads behind the group descriptor)
+  const unsigned feA = (unsigned)wA[7], feB = PW == 2 ? (unsigned)wB[7] : 0u;
+  int endA = (int)(feA & 0xffffu), endB = (int)(feB & 0xffffu);
+  int end1A = (int)(feA >> 16), end1B = (int)(feB >> 16);
   asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.valid),
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.valid),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in

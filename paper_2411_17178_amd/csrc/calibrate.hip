@@ -31,6 +31,9 @@ struct CalibArgs {
   int K, N, H, smax, max_tiles, splits;
   int s[kMaxScales], off[kMaxScales + 1];
   int64_t L;
+  uint16_t slot_begin[kMaxScales * kMaxScales + 1];   // first workgroup of part k * K + j in a head's launch
+                                                      // (splits * tiles of the part's key scale each; none for j > k)
+  int n_slots;
   const float* p;       // [N][H][L][L]
   double* partial;      // [H][K][K][splits][max_tiles][smax]: per-distance sums of one workgroup
   int32_t* radius;      // [H][K][K]
@@ -38,18 +41,34 @@ struct CalibArgs {
   double r0;
 };
 
-__device__ inline int tiles_of(int sj) {
+__host__ __device__ inline int tiles_of(int sj) {
   const int w = 2 * sj - 1;
   return (w * w + kCalibThreads - 1) / kCalibThreads;
 }
 
-// grid (max_tiles * splits, K * K, H)
+// Which part and which of its workgroups a block is: the launch has one block per
+// (part with j <= k, split, tile of the part's key scale) and nothing else -- a launch over
+// the full (tiles x splits, K x K) rectangle spends most of its time starting workgroups
+// that have nothing to do.
+struct Slot { int k, j, tile, split; };
+__device__ inline Slot decode_slot(const CalibArgs& a, int b) {
+  int lo = 0, hi = a.K * a.K;                 // last part whose first workgroup is <= b
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.slot_begin[mid] <= b) lo = mid; else hi = mid;
+  }
+  Slot s;
+  s.k = lo / a.K; s.j = lo % a.K;
+  const int local = b - a.slot_begin[lo], nt = tiles_of(a.s[s.j]);
+  s.tile = local % nt; s.split = local / nt;
+  return s;
+}
+
+// grid (n_slots, 1, H)
 __global__ __launch_bounds__(kCalibThreads) void k_calib_mass(CalibArgs a) {
-  const int k = blockIdx.y / a.K, j = blockIdx.y % a.K, h = blockIdx.z;
-  const int tile = blockIdx.x % a.max_tiles, split = blockIdx.x / a.max_tiles;
-  if (j > k) return;
+  const Slot sl = decode_slot(a, blockIdx.x);
+  const int k = sl.k, j = sl.j, h = blockIdx.z, tile = sl.tile, split = sl.split;
   const int sk = a.s[k], sj = a.s[j];
-  if (tile >= tiles_of(sj)) return;
   __shared__ short cen[kMaxSide];          // centre of query coordinate c in key scale j
   __shared__ double sum_of[kCalibThreads];
   __shared__ short dist_of[kCalibThreads];
@@ -116,6 +135,130 @@ __global__ __launch_bounds__(kCalibThreads) void k_calib_mass(CalibArgs a) {
   }
 }
 
+// The same sums for maps whose largest side is at most kRowsMaxSide, one map row at a time.
+// Same grid and same partial-sum slots as k_calib_mass, but a workgroup owns a share of the
+// part's (sample, query) rows instead of a tile of offsets: a wave reads the row's s_j^2 keys
+// of the part with consecutive lanes on consecutive floats (whole cache lines, each value
+// read exactly once), every lane works out its key's distance from the row's centre and
+// adds the value to bin `distance` of a column of bins in LDS that belongs to this lane
+// alone (no two lanes on one address, and a lane's additions happen in program order, so
+// the sums repeat bit for bit).  At the end the 64 columns of a wave are folded by a fixed butterfly, the four waves
+// of the workgroup in order.
+constexpr int kRowsMaxSide = 64;           // bins of the four waves: 4 x side x 64 x 8 bytes of LDS
+constexpr int kRowsThreads = 256;
+
+// (A plain read-add-write on the lane's own column: LDS atomics -- ds_add_f64, and ds_add_u64
+// alike -- were measured at about 240 cycles per wave instruction here, six times the cost of
+// everything else in the loop; the read-add-write chains of the sixteen waves of a CU overlap.)
+__device__ inline void lds_add_f64(double* col, int d, double v) { col[d * 64] += v; }
+
+__global__ __launch_bounds__(kRowsThreads) void k_calib_mass_rows(CalibArgs a) {
+  extern __shared__ __align__(16) unsigned char calib_smem[];
+  const Slot sl = decode_slot(a, blockIdx.x);
+  const int k = sl.k, j = sl.j, h = blockIdx.z, tile = sl.tile, split = sl.split;
+  const int sk = a.s[k], sj = a.s[j];
+  const int nt = tiles_of(sj);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // LDS: bins[wave][d][lane] (fp64), then the centres of the part's query coordinates
+  double* const bins = (double*)calib_smem + (size_t)wave * sj * 64;
+  double* const fold = (double*)calib_smem + (size_t)4 * a.smax * 64;          // [4][smax]
+  short* const cen = (short*)(fold + 4 * a.smax);                              // [sk]
+  for (int c = threadIdx.x; c < sk; c += kRowsThreads) cen[c] = (short)(((2 * c + 1) * sj) / (2 * sk));
+  for (int i = lane; i < sj * 64; i += 64) bins[i] = 0.0;
+  __syncthreads();
+
+  double* const bins_lane = bins + lane;                                       // this lane's column of bins
+  const int nkeys = sj * sj, nq = sk * sk;
+  const int share = split * nt + tile, n_shares = a.splits * nt;               // this workgroup's rows
+  const float* part = a.p + (int64_t)h * a.L * a.L + (int64_t)a.off[k] * a.L + a.off[j];
+  const int64_t sample_stride = (int64_t)a.H * a.L * a.L;
+  // this wave's queries: first, first + stride, ...; the N samples of a query share its centre,
+  // so their values are added in registers first and binned once
+  const int first = share * 4 + wave, stride = n_shares * 4;
+  if (nkeys >= 64) {
+    constexpr int U = 4, NB = 8;                          // an item: 256 keys of a query's row, 8 samples: 32 loads
+    const int nchunk = (nkeys + 64 * U - 1) / (64 * U);
+    const int my_q = first < nq ? (nq - first + stride - 1) / stride : 0;
+    const int n_items = my_q * nchunk;
+    auto load_item = [&](int t, int n0, float (&v)[NB][U]) {
+      const int q = first + (t / nchunk) * stride, i0 = (t % nchunk) * 64 * U;
+      const float* row = part + (int64_t)q * a.L;
+#pragma unroll
+      for (int m = 0; m < NB; ++m)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int i = i0 + 64 * u + lane;
+          v[m][u] = (n0 + m < a.N && i < nkeys) ? row[(n0 + m) * sample_stride + i] : 0.f;
+        }
+    };
+    // the loads of the next item are in flight while this one is binned
+    float cur[NB][U], nxt[NB][U];
+    if (n_items > 0) load_item(0, 0, cur);
+    for (int t = 0; t < n_items; ++t) {
+      if (t + 1 < n_items) load_item(t + 1, 0, nxt);
+      const int q = first + (t / nchunk) * stride, i0 = (t % nchunk) * 64 * U;
+      const int cy = cen[q / sk], cx = cen[q % sk];
+      double acc[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc[u] = 0.0;
+#pragma unroll
+      for (int m = 0; m < NB; ++m)
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] += (double)cur[m][u];
+      for (int n0 = NB; n0 < a.N; n0 += NB) {             // (more than eight samples: further batches, not overlapped)
+        load_item(t, n0, cur);
+#pragma unroll
+        for (int m = 0; m < NB; ++m)
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc[u] += (double)cur[m][u];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + 64 * u + lane;
+        const int ky = i / sj, kx = i - ky * sj;
+        if (i < nkeys) lds_add_f64(bins_lane, max(abs(ky - cy), abs(kx - cx)), acc[u]);
+      }
+#pragma unroll
+      for (int m = 0; m < NB; ++m)
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[m][u] = nxt[m][u];
+    }
+  } else {
+    // a part with fewer than 64 keys per row: a pass covers 64 / nkeys queries, lane = (query, key)
+    const int qpp = 64 / nkeys;                           // queries per pass
+    const int sub = lane / nkeys, key = lane - sub * nkeys;
+    const int ky = key / sj, kx = key - ky * sj;
+    for (int t0 = 0; first + (int64_t)t0 * stride < nq; t0 += qpp) {
+      const int64_t q = first + (int64_t)(t0 + sub) * stride;
+      const bool in = sub < qpp && q < nq;
+      const int qq = in ? (int)q : first;
+      const int d = max(abs(ky - cen[qq / sk]), abs(kx - cen[qq % sk]));
+      const float* src = part + (int64_t)qq * a.L + key;
+      double acc = 0.0;
+      for (int n = 0; n < a.N; n += 8) {                  // eight loads in flight
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = n + u < a.N ? src[(n + u) * sample_stride] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += (double)v[u];
+      }
+      if (in) lds_add_f64(bins_lane, d, acc);
+    }
+  }
+  // fold the wave's 64 columns (fixed butterfly), then the four waves in order
+  for (int d = 0; d < sj; ++d) {
+    double x = bins[d * 64 + lane];
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) x += __shfl_xor(x, m);
+    if (lane == 0) fold[wave * a.smax + d] = x;
+  }
+  __syncthreads();
+  double* out = a.partial +
+      (((((int64_t)h * a.K + k) * a.K + j) * a.splits + split) * a.max_tiles + tile) * a.smax;
+  for (int d = threadIdx.x; d < sj; d += kRowsThreads)
+    out[d] = ((fold[d] + fold[a.smax + d]) + fold[2 * a.smax + d]) + fold[3 * a.smax + d];
+}
+
 // grid (K * K, H), one wave
 __global__ __launch_bounds__(64) void k_calib_pick(CalibArgs a) {
   const int k = blockIdx.x / a.K, j = blockIdx.x % a.K, h = blockIdx.y;
@@ -166,6 +309,15 @@ litevar_status calib_geom(const int32_t* scales, int32_t K, CalibArgs& a) {
   const int w = 2 * a.smax - 1;
   a.max_tiles = (w * w + kCalibThreads - 1) / kCalibThreads;
   a.splits = 64 / a.max_tiles < 1 ? 1 : (64 / a.max_tiles > 4 ? 4 : 64 / a.max_tiles);
+  int n = 0;
+  for (int kk = 0; kk < K; ++kk)
+    for (int j = 0; j < K; ++j) {
+      a.slot_begin[kk * K + j] = (uint16_t)n;
+      if (j <= kk) n += a.splits * tiles_of(a.s[j]);
+      if (n > 65535) return fail(LITEVAR_E_UNSUPPORTED, "too many parts and offset tiles for one launch");
+    }
+  a.slot_begin[K * K] = (uint16_t)n;
+  a.n_slots = n;
   return LITEVAR_OK;
 }
 
@@ -275,7 +427,18 @@ litevar_status calibrate_with(CalibArgs& a, const float* d_attn, int32_t N, int3
   a.N = N; a.H = H; a.p = d_attn; a.partial = (double*)d_workspace;
   a.radius = d_radius; a.mass = d_mass; a.r0 = (double)r0;
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(k_calib_mass, dim3(a.max_tiles * a.splits, a.K * a.K, H), dim3(kCalibThreads), 0, st, a);
+  if (a.smax <= kRowsMaxSide) {
+    // (maps of small scales, the usual case: whole rows with coalesced loads)
+    const size_t lds = (size_t)4 * a.smax * 64 * sizeof(double) + (size_t)4 * a.smax * sizeof(double) +
+                       (size_t)a.smax * sizeof(short) + 16;
+    if (lds > 64 * 1024)     // (beyond the default limit of dynamically sized LDS; no allocation involved)
+      if (litevar_status s = hip_check(hipFuncSetAttribute((const void*)k_calib_mass_rows,
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                                       "hipFuncSetAttribute")) return s;
+    hipLaunchKernelGGL(k_calib_mass_rows, dim3(a.n_slots, 1, H), dim3(kRowsThreads), lds, st, a);
+  } else {
+    hipLaunchKernelGGL(k_calib_mass, dim3(a.n_slots, 1, H), dim3(kCalibThreads), 0, st, a);
+  }
   if (litevar_status s = hip_check(hipGetLastError(), "calibration mass launch")) return s;
   hipLaunchKernelGGL(k_calib_pick, dim3(a.K * a.K, H), dim3(64), 0, st, a);
   return hip_check(hipGetLastError(), "calibration pick launch");

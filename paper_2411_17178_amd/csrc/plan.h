@@ -39,7 +39,8 @@ enum MaskMode { kModeWindow = 0, kModeBand = 1 };
 struct Geom {
   int K, qb, qe, n_sink;
   int L, Lq, q0, smax;
-  int NW, RH, RW;       // patches per group; group shape in patches (RH x RW, window mode)
+  int NW;               // patches per group
+  short grh[kMaxScales], grw[kMaxScales];   // window mode: group shape in patches (grh x grw <= NW) of every query scale
   int C, NR, A, D;      // chunk keys (a power of two), ring depth in chunks, look-back and
                         // prefetch depth in chunks; NR = A + 1 + D
   int logC;
@@ -78,7 +79,8 @@ struct WaveDesc {    // 32 bytes
   int16_t kq;          // query scale index
   int32_t pairs;       // kept pairs of this patch (statistics)
   uint32_t valid;      // bit n set: column n of the patch holds a query
-  int32_t pad;
+  uint32_t first_ends; // phase_end[0] | phase_end[min(2, n_phases - 1)] << 16: the step counts that the
+                       // 16-patch kernel needs before it can start, next to the patch's other words
 };
 static_assert(sizeof(WaveDesc) == 32 && sizeof(GroupDesc) == 32, "descriptor size");
 
@@ -176,6 +178,20 @@ struct ArithRad { const Geom& g; LV_HD int operator()(int k, int j) const { retu
 struct TableRad { const int16_t* rad; int K; LV_HD int operator()(int k, int j) const { return rad[k * K + j]; } };
 
 // ---- groups and patches ------------------------------------------------------------
+// Shape (rows x columns of patches, at most nw patches) of the groups that tile a grid of
+// pps x pps patches: the fewest groups; among those the most compact shape (a group streams
+// the bounding box of its queries' windows), then the taller one.
+inline void choose_group_shape(int pps, int nw, int& rh, int& rw) {
+  long best = -1;
+  rh = 1; rw = 1;
+  for (int h = 1; h <= nw && h <= pps; ++h) {
+    int w = nw / h; if (w > pps) w = pps;
+    const long groups = (long)((pps + h - 1) / h) * ((pps + w - 1) / w);
+    const long key = groups * 4096 + (h + w) * 32 + (32 - h);
+    if (best < 0 || key < best) { best = key; rh = h; rw = w; }
+  }
+}
+
 LV_HD int patches_per_side(const Geom& g, int k) { return (g.s[k] + kPatch - 1) / kPatch; }
 LV_HD int scale_patches(const Geom& g, int k) {
   if (g.mode == kModeBand) return (g.s[k] * g.s[k] + kPatchQueries - 1) / kPatchQueries;
@@ -183,11 +199,11 @@ LV_HD int scale_patches(const Geom& g, int k) {
 }
 LV_HD int groups_y(const Geom& g, int k) {
   if (g.mode == kModeBand) return (scale_patches(g, k) + g.NW - 1) / g.NW;
-  return (patches_per_side(g, k) + g.RH - 1) / g.RH;
+  return (patches_per_side(g, k) + g.grh[k] - 1) / g.grh[k];
 }
 LV_HD int groups_x(const Geom& g, int k) {
   if (g.mode == kModeBand) return 1;
-  return (patches_per_side(g, k) + g.RW - 1) / g.RW;
+  return (patches_per_side(g, k) + g.grw[k] - 1) / g.grw[k];
 }
 
 // group index (inside a head group) -> (query scale, gy, gx)
@@ -224,9 +240,9 @@ LV_HD GroupExtent group_extent(const Geom& g, int k, int gy, int gx) {
     e.qx0 = e.qx1 = 0;
     return e;
   }
-  e.qy0 = gy * g.RH * kPatch; e.qx0 = gx * g.RW * kPatch;
-  e.qy1 = e.qy0 + g.RH * kPatch - 1; if (e.qy1 > g.s[k] - 1) e.qy1 = g.s[k] - 1;
-  e.qx1 = e.qx0 + g.RW * kPatch - 1; if (e.qx1 > g.s[k] - 1) e.qx1 = g.s[k] - 1;
+  e.qy0 = gy * g.grh[k] * kPatch; e.qx0 = gx * g.grw[k] * kPatch;
+  e.qy1 = e.qy0 + g.grh[k] * kPatch - 1; if (e.qy1 > g.s[k] - 1) e.qy1 = g.s[k] - 1;
+  e.qx1 = e.qx0 + g.grw[k] * kPatch - 1; if (e.qx1 > g.s[k] - 1) e.qx1 = g.s[k] - 1;
   return e;
 }
 
@@ -244,9 +260,10 @@ LV_HD PatchExtent patch_extent(const Geom& g, int k, int gy, int gx, int wave) {
     p.ny = 1; p.nx = left < kPatchQueries ? left : kPatchQueries;
     return p;
   }
-  const int py = gy * g.RH + wave / g.RW, px = gx * g.RW + wave % g.RW;
+  const int rh = g.grh[k], rw = g.grw[k];
+  const int py = gy * rh + wave / rw, px = gx * rw + wave % rw;
   p.y0 = py * kPatch; p.x0 = px * kPatch;
-  if (wave >= g.RH * g.RW || p.y0 >= sk || p.x0 >= sk) { p.ny = p.nx = 0; return p; }
+  if (wave >= rh * rw || p.y0 >= sk || p.x0 >= sk) { p.ny = p.nx = 0; return p; }
   p.ny = sk - p.y0 < kPatch ? sk - p.y0 : kPatch;
   p.nx = sk - p.x0 < kPatch ? sk - p.x0 : kPatch;
   return p;

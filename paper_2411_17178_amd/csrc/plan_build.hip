@@ -13,9 +13,14 @@ namespace lv {
 static void choose_tiling(Geom& g, int waves, int chunk, int depth, int spare) {
   g.NW = waves;
   g.C = chunk; g.D = depth; g.A = 1;
-  if (waves == 16) { g.RH = 4; g.RW = 4; }       // 16 x 16 queries
-  else if (waves == 8) { g.RH = 4; g.RW = 2; }   // 16 rows x 8 columns of queries
-  else { g.RH = 2; g.RW = 2; }                   // 8 x 8 queries
+  // group shape of every scale: 4 x 4 patches (16 x 16 queries) where the scale's patch grid
+  // is a multiple of it, otherwise whatever needs the fewest workgroups (a 5 x 5 grid is
+  // tiled by two groups of 3 x 5 and 2 x 5 patches rather than by four of 16, 4, 4 and 1)
+  for (int k = 0; k < g.K; ++k) {
+    int rh, rw;
+    choose_group_shape((g.s[k] + kPatch - 1) / kPatch, waves, rh, rw);
+    g.grh[k] = (short)rh; g.grw[k] = (short)rw;
+  }
   g.NR = g.A + 1 + g.D + spare;
   g.logC = 0;
   while ((1 << g.logC) < g.C) ++g.logC;
@@ -431,7 +436,7 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
     wd.step_begin = 0; wd.n_steps = ns;
     wd.q_base = q_base;
     wd.sk = (int16_t)sk; wd.ny = (int16_t)pe.ny; wd.nx = (int16_t)pe.nx; wd.kq = (int16_t)k;
-    wd.pairs = pairs; wd.valid = valid; wd.pad = 0;
+    wd.pairs = pairs; wd.valid = valid; wd.first_ends = 0;
     p.waves[idx] = wd;
   }
   if (w == 0 && lane == 0) {
@@ -620,6 +625,8 @@ __global__ __launch_bounds__(64) void k_fill_steps(Geom g, BlobPtrs p, Caps caps
   if (lane == 0) {
     int acc = 0;
     for (int i = 0; i < gd.n_phases; ++i) { acc += pe[i]; pe[i] = acc; }
+    const int i1 = gd.n_phases - 1 < 2 ? gd.n_phases - 1 : 2;
+    p.waves[idx].first_ends = (uint32_t)pe[0] | ((uint32_t)pe[i1] << 16);   // (a patch has at most 65535 steps)
   }
 }
 
