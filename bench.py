@@ -110,12 +110,14 @@ def run_workload(name, dense, steps, warmup, layers, tiling, keep_layer0=False):
     for l in range(layers):
         os_.append(torch.empty_like(qs[l]))
 
-    nbytes = lv.litevar_mask_plan_bytes(w.scales, radius, None, w.n_sink, w.q_scales, tiling)
+    # (the plan is told the B * H of its launches: small batches get smaller groups)
+    BH = w.batch * w.heads
+    nbytes = lv.litevar_mask_plan_bytes(w.scales, radius, None, w.n_sink, w.q_scales, tiling, batch_heads=BH)
     blob = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
     def build_plan():
         return lv.litevar_mask_build(w.scales, radius, None, w.n_sink, w.q_scales,
-                                     waves_per_group=tiling, blob=blob)
+                                     waves_per_group=tiling, blob=blob, batch_heads=BH)
 
     plan = build_plan()
     lv.litevar_plan_check(plan)
@@ -148,14 +150,13 @@ def run_workload(name, dense, steps, warmup, layers, tiling, keep_layer0=False):
     attn_ms = sum(a.elapsed_time(b) for a, b in ev)       # all attention launches
     kernel_us = attn_ms * 1e3 / (steps * layers)          # average per launch
 
-    BH = w.batch * w.heads
     pairs = plan.retained_pairs * BH
     if share is not None:   # shared uncond (head, query scale) rows are not computed
         qb, qe = w.q_range
         per_scale = np.zeros(len(w.scales), dtype=np.int64)
         for k in range(qb, qe):
             per_scale[k] = lv.litevar_mask_plan_stats(w.scales, radius, None, w.n_sink, (k, k + 1),
-                                                      tiling).retained_pairs
+                                                      tiling, batch_heads=BH).retained_pairs
         sh = share.cpu().numpy().astype(np.int64)
         pairs -= int((sh * per_scale[None, :]).sum()) * (w.batch // 2)
     flops_layer = 256.0 * pairs
@@ -193,6 +194,90 @@ def run_workload(name, dense, steps, warmup, layers, tiling, keep_layer0=False):
     if not keep_layer0:
         ctx = None
     return res, ctx
+
+
+def run_variants(steps=8, layers=8):
+    """The rows built beyond the bf16 window path, on the headline shape (VAR-d30 KV step):
+    8-bit Q/K/V (paper Section 4), the band reading of the window, one radius table per head."""
+    import numpy as np
+    import torch
+
+    import paper_2411_17178_amd as lv
+    import workloads
+
+    dev = torch.device("cuda:0")
+    w = workloads.get("var_d30_kvstep")
+    BH, K = w.batch * w.heads, len(w.scales)
+    g = torch.Generator(device=dev).manual_seed(99)
+    qs = [torch.randn((w.batch, w.heads, 256, 64), generator=g, device=dev).to(torch.bfloat16) for _ in range(layers)]
+    ks = [torch.randn((w.batch, w.heads, 680, 64), generator=g, device=dev).to(torch.bfloat16) for _ in range(layers)]
+    vs = [torch.randn((w.batch, w.heads, 680, 64), generator=g, device=dev).to(torch.bfloat16) for _ in range(layers)]
+    outs = [torch.empty_like(q) for q in qs]
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps          # us
+
+    def attn_us(plan):
+        def layer_pass():
+            for l in range(layers):
+                lv.litevar_windowed_attn_fwd(plan, qs[l], ks[l], vs[l], w.sm_scale, out=outs[l])
+        return timed(layer_pass, steps) / layers
+
+    out = []
+    base = lv.litevar_mask_build(w.scales, w.radius, None, w.n_sink, w.q_scales, batch_heads=BH)
+    t_base = attn_us(base)
+
+    # ---- QKV8: quantiser (HBM-bound: 128 B read, 64 + 8 B written per row) and attention on 8-bit operands
+    t_quant = timed(lambda: [lv.litevar_qkv8_quantize(k) for k in ks], steps) / layers
+    rows = BH * 680
+    q8 = [lv.litevar_qkv8_quantize(t) for t in qs]
+    k8 = [lv.litevar_qkv8_quantize(t) for t in ks]
+    v8 = [lv.litevar_qkv8_quantize(t) for t in vs]
+    work = torch.empty(BH * (256 + 2 * 680) * 128, dtype=torch.uint8, device=dev)
+
+    def qkv8_pass():
+        for l in range(layers):
+            lv.litevar_windowed_attn_qkv8_fwd(base, *q8[l], *k8[l], *v8[l], w.sm_scale, out=outs[l], workspace=work)
+    t_q8 = timed(qkv8_pass, steps) / layers
+    bytes_q8 = BH * (256 * (72 + 128) + 2 * 680 * 72)
+    out.append({"variant": "qkv8", "section": "Section 4",
+                "quantize_us_per_tensor": round(t_quant, 2),
+                "quantize_gbs": round(rows * (128 + 72) / (t_quant * 1e-6) / 1e9, 1),
+                "quantize_frac_of_hbm_spec": round(rows * (128 + 72) / (t_quant * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                "attn_us_per_layer": round(t_q8, 2), "bf16_attn_us_per_layer": round(t_base, 2),
+                "algorithmic_bytes": bytes_q8,
+                "hbm_frac_of_spec_on_8bit_bytes": round(bytes_q8 / (t_q8 * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                "note": "operands are dequantised once into a bf16 workspace, then the bf16 kernel runs: "
+                        "the extra pass costs more than the halved K/V bytes save"})
+    del q8, k8, v8, work
+
+    # ---- band reading of the window (Section 2, step (2)): bands as wide as the window's footprint
+    band = lv.litevar_mask_build(w.scales, 24, None, w.n_sink, w.q_scales, batch_heads=BH, mask_mode=1)
+    t_band = attn_us(band)
+    out.append({"variant": "band_1d_radius_24", "section": "Section 2 step (2)",
+                "attn_us_per_layer": round(t_band, 2), "retained_pairs_per_bh": int(band.retained_pairs),
+                "kernel_tflops_retained": round(256.0 * band.retained_pairs * BH / (t_band * 1e-6) / 1e12, 1),
+                "tile_density": round(band.retained_pairs / band.computed_pairs, 4)})
+
+    # ---- one radius table per head (Section 2, step (3)): thirty heads, radii 2..4 per part
+    rng = np.random.default_rng(7)
+    tabs = rng.integers(2, 5, size=(w.heads, K, K))
+    ph = lv.litevar_mask_build(w.scales, 0, tabs.tolist(), w.n_sink, w.q_scales, batch_heads=BH)
+    t_ph = attn_us(ph)
+    pairs = sum(int(ph.retained_pairs_of_group[ph.head_group[h]]) for h in range(w.heads)) * w.batch
+    out.append({"variant": "radius_table_per_head", "section": "Section 2 step (3)",
+                "attn_us_per_layer": round(t_ph, 2), "heads": w.heads, "head_groups": int(ph.n_head_groups),
+                "kernel_tflops_retained": round(256.0 * pairs / (t_ph * 1e-6) / 1e12, 1),
+                "plan_bytes": int(ph.blob_bytes)})
+    return out
 
 
 def measure_peaks():
@@ -329,6 +414,8 @@ def main():
         win = next(r for r in extra if r["workload"] == "var_d36_512")
         den = next(r for r in extra if r["workload"] == "var_d36_512_dense")
         out["workloads"] = extra
+        torch.cuda.empty_cache()
+        out["variants"] = run_variants()
         out["d36_windowed_vs_dense"] = {
             "speedup": round(den["us_per_layer"] / win["us_per_layer"], 3),
             "flop_ratio": round(den["retained_pairs_per_bh"] / win["retained_pairs_per_bh"], 3)}

@@ -18,7 +18,9 @@
  *
  * Conventions
  *   - Every pointer argument says HOST or DEVICE.  The library allocates no
- *     device memory and keeps no global state besides a thread-local error string.
+ *     device memory.  Its only state: a thread-local error string, a thread-local memo of
+ *     the last plan sizing, a per-thread cache of the devices' CU counts, and the static
+ *     scratch array of litevar_window_calibrate_static with its resolved address.
  *   - All GPU work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and never synchronised, unless stated otherwise.
  *   - Arguments are validated on the host before any HIP call; a failed
@@ -277,9 +279,11 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
  * post-softmax attention maps of N reference samples, for every head, query scale k and
  * key scale j <= k: the smallest radius r >= 0 such that the values inside the radius-r
  * windows of the part (query scale k, key scale j), summed over the part's queries and the
- * samples, reach the fraction r0 of all of the part's values ("the window grows from zero
- * until R_w reaches R_0"; r0 = 1 keeps every non-zero value).  Windows and centres are those
- * of litevar_mask_build; a part without mass gets radius 0.
+ * samples, reach the fraction r0 of all of the part's values (r0 = 1 keeps every non-zero
+ * value).  Windows and centres are those of litevar_mask_build's window mode; a part without
+ * mass gets radius 0.  Parts are one per key scale here: the merged first part of Section 2,
+ * step (2) is not modelled, which is immaterial when the first three key scales are kept
+ * dense (n_sink_scales = 3).
  *
  *   scales, n_scales  HOST, as in litevar_mask_desc
  *   d_attn       DEVICE float32 [N][H][L][L], contiguous, L = sum of s_k^2: row q holds

@@ -8,19 +8,30 @@
 //
 // The group's key list is streamed once through an LDS ring of five chunks of 64 keys
 // (one 128-byte K row and one 128-byte V row per key, 16-byte pieces XOR-swizzled by
-// slot; 80 KiB, so that two workgroups share a CU).  A phase is two chunks: phase p = the
-// steps whose last key lies in chunk 2p or 2p+1.  A step spans at most two consecutive
-// chunks, so these steps read chunks 2p-1 .. 2p+1, while chunks 2p+2 and 2p+3 land in the
-// other two slots (chunk t lives in slot t mod 5; those slots held chunks 2p-3 and 2p-2,
-// which nobody reads after the barrier that ends phase p-1).  In phase p a wave
-//   issues the descriptor loads of its steps of this phase beyond the first of each patch
-//     and of the first step of each patch of phase p+1, and the token loads for its rows
-//     of chunks 2p+4 and 2p+5,
-//   runs the first step of each patch,
-//   issues four global_load_lds_dwordx4: its eight K rows and eight V rows of chunks 2p+2
-//     and 2p+3 (not right behind the barrier, where the loads of all eight waves would
-//     queue up in front of the first K reads),
-//   runs its other steps, waits for all its vector memory operations and joins the barrier.
+// slot; 80 KiB, so that two workgroups share a CU); chunk t lives in slot t mod 5.  The
+// plan counts NC chunks; the kernel runs P = NC / 2 + 1 phases: phase 0 is chunk 0 alone
+// (the first steps start on as little data as possible), phase p >= 1 is chunks 2p-1 and
+// 2p, i.e. the steps whose last key lies in one of them.  A step spans at most two
+// consecutive chunks, so a step that ends in chunk t reads chunks t-1 .. t: phase p reads
+// chunks 2p-2 .. 2p, which are three of the five slots; the other two slots held chunks
+// 2p-4 and 2p-3, which nobody reads after the barrier that ended phase p-1, and receive
+// chunks 2p+1 and 2p+2 (phase p+1) while phase p computes.
+//   Prologue: all scalar plan words, then the tokens of chunks 0-2 (if the list does not
+//     start with whole key scales), Q, the first step descriptors, chunk 0, and last
+//     chunks 1 and 2; it waits until at most those last two chunks' loads (2 * PW per
+//     wave) are outstanding (vmcnt 2 * PW), then the first barrier: chunk 0 is in.
+//   Phase p: a wave
+//     issues the descriptor loads of its steps of this phase beyond the first of each patch,
+//     runs the first step of each patch,
+//     waits for all its vector memory operations (p >= 1: the descriptors just requested;
+//       chunks 2p-1 and 2p were waited for at the end of phase p-1),
+//     requests the first descriptors and the tokens of phase p+1 and then issues its share
+//       of chunks 2p+1 and 2p+2 (p >= 1; in phase 0 chunks 1 and 2 are already in flight) --
+//       not right behind the barrier, where the loads of all eight waves would queue up in
+//       front of the first K reads, and behind the small loads, because a load issued behind
+//       a chunk is held up until the chunk's data is in,
+//     runs its other steps, waits for all its vector memory operations (vmcnt 0: the chunks
+//       of phase p+1 have landed) and joins the barrier.
 // Two chunks (32 KiB) per workgroup are in flight during a phase, and a key row is moved
 // from HBM/L2 to LDS exactly once per (batch, head, group).
 //

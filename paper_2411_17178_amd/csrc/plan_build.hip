@@ -116,6 +116,11 @@ litevar_status make_spec(const litevar_mask_desc* d, const litevar_plan_opts* op
       }
       constexpr int64_t kEnoughWorkgroups = 230;
       if (hint * g16 < kEnoughWorkgroups) waves = hint * g8 >= kEnoughWorkgroups ? 8 : 4;
+      // A full sequence of many query scales at a small batch: the launch is as long as its
+      // largest workgroup, and a group of 2 x 2 patches streams about half the keys of a
+      // group of 4 x 4 (VAR-d16, 32 pairs x 10 scales: 17.7 us with 16 patches per group,
+      // 15.0 with 8, 12.4 with 4).
+      else if (hint * g16 < 2 * 256 && g.qe - g.qb > 4) waves = 4;
     }
   }
   if (waves != 4 && waves != 8 && waves != 16)
