@@ -103,7 +103,8 @@ __device__ inline void lds_wait(uint2 (&va)[4][2]) {
 struct PatchState {       // one query patch of a wave
   bf16x8 qb0, qb1;        // Q^T as the B operand: lane (n, g4) holds Q[query n][16 g4 .. +15]
   f32x4 O[4], Lacc;       // O^T accumulators and row sums
-  float thr, negmc;       // softmax reference m as m + slack (scores above it move m) and -m c
+  float thr, negmc;       // the softmax reference m as -m c; thr = how far a score (in units of
+                          // the exponent, relative to m) may rise before m moves: kFloor while m is unset
 };
 
 }  // namespace
@@ -250,8 +251,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   auto init_patch = [&](PatchState& ps, const PatchWords& w) {
     const int ld_row = query_row(w, n, true);
     const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
-    ps.qb0 = as_bf16x8(*(const uint4*)qp); ps.qb1 = as_bf16x8(*(const uint4*)(qp + 8));
-    ps.thr = kFloor; ps.negmc = -kFloor * c;
+    // Q is kept as Q c (c = softmax scale x log2 e, rounded to bf16 once): the score tiles
+    // then are base-2 exponents as they leave the matrix pipe
+    const bf16x8 q0 = as_bf16x8(*(const uint4*)qp), q1 = as_bf16x8(*(const uint4*)(qp + 8));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ps.qb0[e] = (__bf16)((float)q0[e] * c); ps.qb1[e] = (__bf16)((float)q1[e] * c); }
+    ps.thr = kFloor; ps.negmc = 0.f;
     ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) ps.O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -264,8 +269,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
   asm volatile("" : "+v"(ones));     // kept in four registers (the compiler would rebuild it in every step)
-  const float slack = kSlack / c;
-
   // Step descriptors of a patch for one phase: the first step's is fetched during the phase
   // before (d0), those of the next kLater steps at the start of the phase (dl).
   uint2 dA0 = make_uint2(0u, 0u), dB0 = dA0, dAl[kLater], dBl[kLater];
@@ -332,7 +335,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     // (the masks were requested before the K pieces and share their counter: they are in,
     // and the compiler should know before the V^T reads go out, or it waits for those too)
     asm volatile("" : : "s"(mk[0]), "s"(mk[1]), "s"(mk[2]), "s"(mk[3]), "s"(mk[4]), "s"(mk[5]), "s"(mk[6]), "s"(mk[7]));
-    f32x4 S0 = {0.f, 0.f, 0.f, 0.f}, S1 = {0.f, 0.f, 0.f, 0.f};
+    // The accumulators of the score tiles start at -m c where the pair is kept and at -inf
+    // where it is not (one v_cndmask per score, by the lane masks): what leaves the matrix
+    // pipe is the exponent of the probability.
+    f32x4 S0, S1;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { S0[e] = mask_select(ps.negmc, mk[e]); S1[e] = mask_select(ps.negmc, mk[4 + e]); }
     S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k00), ps.qb0, S0, 0, 0, 0);
     S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k10), ps.qb0, S1, 0, 0, 0);
     S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k01), ps.qb1, S0, 0, 0, 0);
@@ -342,29 +350,28 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     uint2 va[4][2];
     lds_read_v<VOFF>(v0, v1, va_addr, va);
     float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) sv[e] = mask_select(sv[e], mk[e]);
-    // The reference m of a query only moves when one of its scores exceeds it by more than
-    // the slack (probabilities stay below 2^kSlack).  The common case needs the lane's own
-    // maximum only; the maximum over the query's four lanes is formed when some lane of the
-    // wave has crossed its threshold.
-    const float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                           fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    // The reference m of a query only moves when one of its exponents exceeds the slack
+    // (probabilities stay below 2^kSlack), and once at the query's first kept key.  The common
+    // case needs the lane's own maximum only; the maximum over the query's four lanes is
+    // formed when some lane of the wave has crossed its threshold.
+    const float m012 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), m345 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);   // (v_max3)
+    const float mx = fmaxf(fmaxf(fmaxf(sv[6], sv[7]), m012), m345);
     if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > ps.thr) != 0, 0)) {   // rare after the first steps
       const float mxr = max_across_rows(mx);
       const bool grow = mxr > ps.thr;
-      const float negmc_new = grow ? -mxr * c : ps.negmc;
-      const float alpha = __builtin_amdgcn_exp2f(negmc_new - ps.negmc);
-      ps.negmc = negmc_new;
-      ps.thr = grow ? mxr + slack : ps.thr;
+      const float shift = grow ? mxr : 0.f;               // m c moves by this much (down only when m was unset)
+      const float alpha = __builtin_amdgcn_exp2f(-fmaxf(shift, 0.f));
+      ps.negmc -= shift;
+      ps.thr = grow ? kSlack : ps.thr;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sv[e] -= shift;
       ps.Lacc *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt) ps.O[dt] *= alpha;
     }
-    const float negmc = ps.negmc;
     float p[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(sv[e], c, negmc));
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(sv[e]);
     bf16x8 pb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];

@@ -35,8 +35,10 @@ __global__ __launch_bounds__(256) void k_peak_mfma(int iters, float* out) {
   for (int t = 0; t < 8; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[t], 0, 0, 0);
+    for (int t = 0; t < 8; ++t)   // in place: the builtin form makes the compiler rotate the tiles through copies
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[t]) : "v"(a), "v"(b));
   }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // inline-assembly results are invisible to the hazard recogniser
   float s = 0.f;
 #pragma unroll
   for (int t = 0; t < 8; ++t) s += acc[t][0] + acc[t][1] + acc[t][2] + acc[t][3];
