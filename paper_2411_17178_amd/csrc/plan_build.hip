@@ -348,28 +348,45 @@ __device__ int wave_walk_patch(const Geom& g, const TableWin& win, const TableRa
     }
     return pack.finish();
   }
-  for (int j = 0; j <= e.k; ++j) {
-    // The twelve window intervals of this key scale (four patch rows, four patch columns, the
-    // group's first and last row and column) are fetched from the table by twelve lanes at
-    // once and handed round with v_readlane.
+  // The twelve window intervals that a key scale needs (four patch rows, four patch columns,
+  // the group's first and last row and column) are fetched from the table for ALL key scales
+  // before the walk: sixteen lanes per key scale, four key scales per round, so the walk pays
+  // the table's latency once and not once per key scale.  They are handed round with
+  // v_readlane.
+  constexpr int kRounds = kMaxScales / 4;
+  Interval pre[kRounds];
+  {
     const int sk = g.s[e.k];
-    int cq = lane < 4 ? p.y0 + lane : lane < 8 ? p.x0 + lane - 4 : lane == 8 ? e.qy0 : lane == 9 ? e.qy1 : lane == 10 ? e.qx0 : e.qx1;
+    const int role = lane & 15;
+    int cq = role < 4 ? p.y0 + role : role < 8 ? p.x0 + role - 4 : role == 8 ? e.qy0 : role == 9 ? e.qy1 : role == 10 ? e.qx0 : e.qx1;
     cq = cq < sk ? cq : sk - 1;
-    const Interval mine_iv = win(e.k, j, cq);
+#pragma unroll
+    for (int t = 0; t < kRounds; ++t) {
+      pre[t].lo = 1; pre[t].hi = 0;
+      const int j = 4 * t + (lane >> 4);
+      if (4 * t <= e.k && j <= e.k && role < 12) pre[t] = win(e.k, j, cq);
+    }
+  }
+  for (int j = 0; j <= e.k; ++j) {
+    Interval mine_iv = pre[0];
+#pragma unroll
+    for (int t = 1; t < kRounds; ++t)
+      if ((j >> 2) == t) mine_iv = pre[t];             // (uniform)
+    const int l0 = (j & 3) * 16;                         // first lane of this key scale's sixteen
     const Interval none = {1, 0};
     Interval rw[kPatch], cw[kPatch];
 #pragma unroll
     for (int d = 0; d < kPatch; ++d) {
-      const Interval r = {__shfl(mine_iv.lo, d), __shfl(mine_iv.hi, d)};
-      const Interval cc = {__shfl(mine_iv.lo, 4 + d), __shfl(mine_iv.hi, 4 + d)};
+      const Interval r = {__shfl(mine_iv.lo, l0 + d), __shfl(mine_iv.hi, l0 + d)};
+      const Interval cc = {__shfl(mine_iv.lo, l0 + 4 + d), __shfl(mine_iv.hi, l0 + 4 + d)};
       rw[d] = d < p.ny ? r : none;
       cw[d] = d < p.nx ? cc : none;
     }
     Box gb, pb;
-    gb.ylo = __shfl(mine_iv.lo, 8); gb.yhi = __shfl(mine_iv.hi, 9);
-    gb.xlo = __shfl(mine_iv.lo, 10); gb.xhi = __shfl(mine_iv.hi, 11);
-    pb.ylo = rw[0].lo; pb.yhi = __shfl(mine_iv.hi, p.ny - 1);
-    pb.xlo = cw[0].lo; pb.xhi = __shfl(mine_iv.hi, 4 + p.nx - 1);
+    gb.ylo = __shfl(mine_iv.lo, l0 + 8); gb.yhi = __shfl(mine_iv.hi, l0 + 9);
+    gb.xlo = __shfl(mine_iv.lo, l0 + 10); gb.xhi = __shfl(mine_iv.hi, l0 + 11);
+    pb.ylo = rw[0].lo; pb.yhi = __shfl(mine_iv.hi, l0 + p.ny - 1);
+    pb.xlo = cw[0].lo; pb.xhi = __shfl(mine_iv.hi, l0 + 4 + p.nx - 1);
     const int gw = gb.xhi - gb.xlo + 1;
     const int sj = g.s[j], offj = g.off[j];
     // lanes of a pass in key order: RP rows of the patch's box (W columns each) when the box
@@ -444,14 +461,13 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
     wd.pairs = pairs; wd.valid = valid; wd.first_ends = 0;
     p.waves[idx] = wd;
   }
-  if (w == 0 && lane == 0) {
+  if (w == 0) {
+    // the group's descriptor; in window mode lane j holds the group's box in key scale j, so
+    // that the table is read once, by all lanes at the same time
     GroupDesc gd;
-    gd.union_base = 0; gd.n_union = group_union_keys(g, t.win, t.rad, e);
-    gd.n_phases = (gd.n_union + g.C - 1) / g.C;
-    gd.k = k; gd.gy = gy; gd.gx = gx; gd.phase_base = 0;
-    // leading union entries whose token equals their position
-    int ident = 0;
+    int ident = 0;                                      // leading union entries whose token equals their position
     if (g.mode == kModeBand) {
+      gd.n_union = group_union_keys(g, t.win, t.rad, e);
       const int nk = g.s[k] * g.s[k];
       for (int pt = 0; pt < band_parts(k); ++pt) {
         const BandPart b = band_part(g, t.rad, k, pt);
@@ -461,10 +477,16 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
         if (ghi != b.cols - 1) break;
       }
     } else {
+      Box mine = {0, -1, 0, -1};
+      if (lane <= k) mine = window_box(t.win, k, lane, e.qy0, e.qy1, e.qx0, e.qx1);
+      int n = (mine.yhi - mine.ylo + 1) * (mine.xhi - mine.xlo + 1);
+#pragma unroll
+      for (int d = 32; d > 0; d >>= 1) n += __shfl_xor(n, d);
+      gd.n_union = n;
       // whole key scales from scale 0 on, then the first rows of the next box if it starts
       // at the scale's origin
       for (int j = 0; j <= k; ++j) {
-        const Box b = window_box(t.win, k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+        const Box b = {__shfl(mine.ylo, j), __shfl(mine.yhi, j), __shfl(mine.xlo, j), __shfl(mine.xhi, j)};
         const int gw = b.xhi - b.xlo + 1, rows = b.yhi - b.ylo + 1;
         if (b.ylo != 0 || b.xlo != 0 || g.off[j] != ident) break;
         if (gw != g.s[j]) { ident += gw; break; }
@@ -472,8 +494,11 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
         if (rows != g.s[j]) break;
       }
     }
+    gd.union_base = 0;
+    gd.n_phases = (gd.n_union + g.C - 1) / g.C;
+    gd.k = k; gd.gy = gy; gd.gx = gx; gd.phase_base = 0;
     gd.ident = ident;
-    p.groups[G] = gd;
+    if (lane == 0) p.groups[G] = gd;
   }
 }
 
@@ -546,8 +571,11 @@ __global__ void k_fill_union(Geom g, BlobPtrs p, Caps caps) {
       last_tok = b.tok0 + ghi;
     }
   } else {
+    __shared__ Box boxes[kMaxScales];                   // (the table is read once, by K threads at the same time)
+    if ((int)threadIdx.x <= e.k) boxes[threadIdx.x] = window_box(t.win, e.k, (int)threadIdx.x, e.qy0, e.qy1, e.qx0, e.qx1);
+    __syncthreads();
     for (int j = 0; j <= e.k; ++j) {
-      const Box b = window_box(t.win, e.k, j, e.qy0, e.qy1, e.qx0, e.qx1);
+      const Box b = boxes[j];
       const int gw = b.xhi - b.xlo + 1, n = (b.yhi - b.ylo + 1) * gw;
       for (int i = threadIdx.x; i < n; i += blockDim.x)
         out[ubase + i] = g.off[j] + (b.ylo + i / gw) * g.s[j] + b.xlo + i % gw;
