@@ -134,8 +134,15 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int grp_g = grp + (a.head_map ? a.head_map[h] * a.n_groups : 0);
   const GroupDesc gd = a.groups[grp_g];    // (requested together with the header words, used behind the check)
   if (!usable) return;
-  const bool shared = a.cfg_share && a.cfg_share[h * a.n_scales + gd.k];
-  if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
+  // output sharing flag of (head, query scale): a scalar load of the aligned word that holds
+  // the byte (a naturally aligned word lies in its byte's page), tested further down so that
+  // it travels together with the patch descriptors
+  uint32_t share_word = 0, share_shift = 0;
+  if (a.cfg_share) {
+    const uintptr_t sa = (uintptr_t)(a.cfg_share + h * a.n_scales + gd.k);
+    share_word = (uint32_t)*(const_i32_ptr)(sa & ~(uintptr_t)3);
+    share_shift = 8u * (uint32_t)(sa & 3);
+  }
 
   // Two workgroups share a CU, and the instruction arbiter prefers the older waves: left
   // alone, the workgroup that arrived first runs as if it had the CU to itself and the other
@@ -214,6 +221,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const unsigned feA = (unsigned)wA[7], feB = PW == 2 ? (unsigned)wB[7] : 0u;
   int endA = (int)(feA & 0xffffu), endB = (int)(feB & 0xffffu);
   int end1A = (int)(feA >> 16), end1B = (int)(feB >> 16);
+  const bool shared = ((share_word >> share_shift) & 0xffu) != 0;
+  if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
   asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.valid),
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.valid),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
@@ -251,11 +260,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   auto init_patch = [&](PatchState& ps, const PatchWords& w) {
     const int ld_row = query_row(w, n, true);
     const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
-    // Q is kept as Q c (c = softmax scale x log2 e, rounded to bf16 once): the score tiles
-    // then are base-2 exponents as they leave the matrix pipe
-    const bf16x8 q0 = as_bf16x8(*(const uint4*)qp), q1 = as_bf16x8(*(const uint4*)(qp + 8));
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { ps.qb0[e] = (__bf16)((float)q0[e] * c); ps.qb1[e] = (__bf16)((float)q1[e] * c); }
+    // (inline assembly: the compiler then does not know of a load into these registers, and
+    // the explicit wait below, which leaves the chunk transfers in flight, stays as written;
+    // the values are scaled there)
+    u32x4 r0, r1;
+    asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
+                 : "=&v"(r0), "=&v"(r1) : "v"(qp) : "memory");
+    ps.qb0 = __builtin_bit_cast(bf16x8, r0); ps.qb1 = __builtin_bit_cast(bf16x8, r1);
     ps.thr = kFloor; ps.negmc = 0.f;
     ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -311,6 +322,20 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   issue_chunk(0, tok0);
   issue_chunk(1, tok1);
   issue_chunk(2, tok2);
+  // Everything older than the three chunks is in: Q is turned into Q c (c = softmax scale x
+  // log2 e, rounded to bf16 once) while chunk 0 is on its way, so that the score tiles are
+  // base-2 exponents as they leave the matrix pipe.  (The registers are tied to this point:
+  // placed any earlier, the conversion would make the compiler wait for all loads, chunks
+  // included, between two chunk transfers.)
+  wait_vmcnt<3 * kDmaPerChunk>();
+  auto scale_q = [&](PatchState& ps) {
+    asm volatile("" : "+v"(ps.qb0), "+v"(ps.qb1));
+    const bf16x8 q0 = ps.qb0, q1 = ps.qb1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ps.qb0[e] = (__bf16)((float)q0[e] * c); ps.qb1[e] = (__bf16)((float)q1[e] * c); }
+  };
+  scale_q(A);
+  if constexpr (PW == 2) scale_q(B);
   wait_vmcnt<2 * kDmaPerChunk>();
   asm volatile("s_barrier" ::: "memory");
 
