@@ -227,12 +227,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.valid),
                "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
 
-  // ---- prologue, vector part: chunk 0 first.  The key list usually starts with whole key
-  // scales (token = position), which needs no token load; otherwise the tokens of the first
-  // three chunks are fetched (and waited for) before anything else is in flight.
-  int tok0 = load_tok(0), tok1 = load_tok(1), tok2 = load_tok(2);
-  tok0 = tok_of(0, tok0); tok1 = tok_of(1, tok1); tok2 = tok_of(2, tok2);
-  asm volatile("" : "+v"(tok0), "+v"(tok1), "+v"(tok2));   // (here: waits for the three, if they were loaded at all)
+  // ---- prologue, vector part.  The key list usually starts with whole key scales (token =
+  // position), which needs no token load; the tokens of the other chunks among the first
+  // three are requested here and waited for together with the small loads below.
+  // leading chunks (of the first three) that lie in the identity prefix: their transfers need no token
+  auto in_prefix = [&](int t) -> bool { return (min(t, NC - 1) + 1) * C <= ident; };
+  const int n_id = (int)in_prefix(0) + (int)in_prefix(1) + (int)in_prefix(2);   // (uniform; non-increasing in t)
 
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
   const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
@@ -319,9 +319,22 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   }
   // The chunks go out behind the small loads (a load issued behind a chunk is held up until
   // the chunk's data is in), chunks 1 and 2 (phase 1) last: phase 0 waits for everything but them.
-  issue_chunk(0, tok0);
-  issue_chunk(1, tok1);
-  issue_chunk(2, tok2);
+  if (n_id == 3) {
+    issue_chunk(0, tok_of(0, 0)); issue_chunk(1, tok_of(1, 0)); issue_chunk(2, tok_of(2, 0));
+  } else {
+    // Some of the three chunks need their tokens: these are requested behind the small loads
+    // and travel with them; the chunks of the prefix go out meanwhile; then one wait for
+    // everything issued so far.  (All in this branch, so that on the other one the compiler
+    // knows of no token load in flight.)
+    int tok0 = load_tok(0), tok1 = load_tok(1), tok2 = load_tok(2);
+    if (n_id >= 1) issue_chunk(0, tok_of(0, 0));
+    if (n_id >= 2) issue_chunk(1, tok_of(1, 0));
+    wait_vmcnt<0>();
+    asm volatile("" : "+v"(tok0), "+v"(tok1), "+v"(tok2));
+    if (n_id < 1) issue_chunk(0, tok_of(0, tok0));
+    if (n_id < 2) issue_chunk(1, tok_of(1, tok1));
+    issue_chunk(2, tok_of(2, tok2));
+  }
   // Everything older than the three chunks is in: Q is turned into Q c (c = softmax scale x
   // log2 e, rounded to bf16 once) while chunk 0 is on its way, so that the score tiles are
   // base-2 exponents as they leave the matrix pipe.  (The registers are tied to this point:
