@@ -53,8 +53,9 @@ __device__ inline float max_across_rows(float x) {
 // header is the same for every workgroup.)
 __device__ inline bool plan_usable(const Header* hdr) {
   const const_i32_ptr w = (const_i32_ptr)hdr;
-  return w[0] == (int32_t)(kMagic & 0xffffffffu) && w[1] == (int32_t)(kMagic >> 32) &&
-         w[offsetof(Header, error) / 4] != kErrBuilder;
+  int magic_lo = w[0], magic_hi = w[1], err = w[offsetof(Header, error) / 4];
+  asm volatile("" : "+s"(magic_lo), "+s"(magic_hi), "+s"(err));   // one round trip for the three words
+  return magic_lo == (int32_t)(kMagic & 0xffffffffu) && magic_hi == (int32_t)(kMagic >> 32) && err != kErrBuilder;
 }
 
 template <int N> __device__ inline void wait_vmcnt() {

@@ -16,10 +16,13 @@
 // chunks 2p-2 .. 2p, which are three of the five slots; the other two slots held chunks
 // 2p-4 and 2p-3, which nobody reads after the barrier that ended phase p-1, and receive
 // chunks 2p+1 and 2p+2 (phase p+1) while phase p computes.
-//   Prologue: all scalar plan words, then the tokens of chunks 0-2 (if the list does not
-//     start with whole key scales), Q, the first step descriptors, chunk 0, and last
-//     chunks 1 and 2; it waits until at most those last two chunks' loads (2 * PW per
-//     wave) are outstanding (vmcnt 2 * PW), then the first barrier: chunk 0 is in.
+//   Prologue: all scalar plan words, then Q, the first step descriptors and the other small
+//     loads, then chunks 0, 1 and 2.  (Where the list does not start with whole key scales,
+//     the tokens of the chunks that need them travel with the small loads; the chunks that
+//     need none go out meanwhile, one wait, then the rest.)  With at most the three chunks
+//     outstanding (a wave issues PW transfers per chunk: vmcnt 3 PW) Q is multiplied by the softmax
+//     scale; with at most chunks 1 and 2 outstanding (vmcnt 2 PW) comes the first barrier:
+//     chunk 0 is in.
 //   Phase p: a wave
 //     issues the descriptor loads of its steps of this phase beyond the first of each patch,
 //     runs the first step of each patch,
@@ -39,9 +42,11 @@
 // cannot tell which of them a plain LDS read depends on and would wait for all
 // (vmcnt(0)) before every read.
 //
-// Step arithmetic is that of the 8-patch kernel: S^T = K_tile . Q^T by
-// v_mfma_f32_16x16x32_bf16 (a lane owns one query column and four keys per tile), scalar
-// lane masks applied with v_cndmask, base-2 online softmax with a lazily updated
+// Step arithmetic is that of the 8-patch kernel: S^T = K_tile . (Q c)^T by
+// v_mfma_f32_16x16x32_bf16 (c = softmax scale x log2 e; a lane owns one query column and
+// four keys per tile) on accumulators that start at minus the softmax reference where the
+// scalar lane mask keeps the pair and at -inf elsewhere (one v_cndmask per score), so the
+// tiles leave the matrix pipe as exponents; base-2 online softmax with a lazily updated
 // reference, O^T += V^T . P^T with ds_read_b64_tr_b16 operands, row sums by a fifth MFMA.
 #include <type_traits>
 
@@ -129,20 +134,21 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int bh = (seq / a.n_groups) * 8 + xcd, grp = seq % a.n_groups;
   if (bh >= a.B * a.H) return;
   const int b = bh / a.H, h = bh % a.H;
-  const bool usable = plan_usable(a.hdr);
-  // heads with a radius table of their own use their head group's copy of the work-list
-  const int grp_g = grp + (a.head_map ? a.head_map[h] * a.n_groups : 0);
-  const GroupDesc gd = a.groups[grp_g];    // (requested together with the header words, used behind the check)
-  if (!usable) return;
-  // output sharing flag of (head, query scale): a scalar load of the aligned word that holds
-  // the byte (a naturally aligned word lies in its byte's page), tested further down so that
-  // it travels together with the patch descriptors
-  uint32_t share_word = 0, share_shift = 0;
-  if (a.cfg_share) {
-    const uintptr_t sa = (uintptr_t)(a.cfg_share + h * a.n_scales + gd.k);
-    share_word = (uint32_t)*(const_i32_ptr)(sa & ~(uintptr_t)3);
-    share_shift = 8u * (uint32_t)(sa & 3);
-  }
+  // Scalar round trip 1: the header words that say whether the plan may be used at all (a
+  // zeroed, stale or half-built blob makes the launch a no-op) and, for plans with a radius
+  // table per head, the head's group, whose copy of the work-list this workgroup walks.
+  // (Requested together and tied to one point, so that they cost one round trip, not four.)
+  const const_i32_ptr hw = (const_i32_ptr)a.hdr;
+  int magic_lo = hw[0], magic_hi = hw[1], herr = hw[offsetof(Header, error) / 4], hg = 0;
+  if (a.head_map) hg = ((const_i32_ptr)a.head_map)[h];
+  asm volatile("" : "+s"(magic_lo), "+s"(magic_hi), "+s"(herr), "+s"(hg));
+  if (magic_lo != (int32_t)(kMagic & 0xffffffffu) || magic_hi != (int32_t)(kMagic >> 32) || herr == kErrBuilder) return;
+  const int grp_g = grp + hg * a.n_groups;
+  // Scalar round trip 2 (together with the patch descriptors below): the group descriptor.
+  const const_i32_ptr gw = (const_i32_ptr)(a.groups + grp_g);
+  GroupDesc gd;
+  gd.union_base = gw[0]; gd.n_union = gw[1]; gd.n_phases = gw[2]; gd.k = gw[3];
+  gd.gy = gw[4]; gd.gx = gw[5]; gd.phase_base = gw[6]; gd.ident = gw[7];
 
   // Two workgroups share a CU, and the instruction arbiter prefers the older waves: left
   // alone, the workgroup that arrived first runs as if it had the CU to itself and the other
@@ -213,6 +219,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   struct PatchWords { int step_begin, q_base, sk_ny, valid; };
   const PatchWords pwA = {wA[0], wA[2], wA[3], wA[6]}, pwB = {wB[0], wB[2], wB[3], wB[6]};
   const int first_step = wF[0], n_group_steps = wL[0] + wL[1] - first_step;
+  const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);     // last step of each patch
   // cumulative step counts of phases 0 and 1 (an idle patch has zeros); the entry of
   // phase p + 2 is fetched during phase p
   // (one patch per wave: the second patch's counts are the constant 0 and its code goes away)
@@ -221,11 +228,19 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const unsigned feA = (unsigned)wA[7], feB = PW == 2 ? (unsigned)wB[7] : 0u;
   int endA = (int)(feA & 0xffffu), endB = (int)(feB & 0xffffu);
   int end1A = (int)(feA >> 16), end1B = (int)(feB >> 16);
-  const bool shared = ((share_word >> share_shift) & 0xffu) != 0;
-  if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
   asm volatile("" : : "s"(pwA.step_begin), "s"(pwA.q_base), "s"(pwA.sk_ny), "s"(pwA.valid),
                "s"(pwB.step_begin), "s"(pwB.q_base), "s"(pwB.sk_ny), "s"(pwB.valid),
-               "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B));   // all in
+               "s"(n_group_steps), "s"(endA), "s"(endB), "s"(end1A), "s"(end1B), "s"(lastA), "s"(lastB),
+               "s"(gd.union_base), "s"(gd.n_phases), "s"(gd.k), "s"(gd.phase_base), "s"(gd.ident));   // all in
+  // Scalar round trip 3, only with an output sharing table: the flag of (head, query scale),
+  // as the aligned word that holds the byte (a naturally aligned word lies in its byte's page).
+  bool shared = false;
+  if (a.cfg_share) {
+    const uintptr_t sa = (uintptr_t)(a.cfg_share + h * a.n_scales + gd.k);
+    const uint32_t share_word = (uint32_t)*(const_i32_ptr)(sa & ~(uintptr_t)3);
+    shared = ((share_word >> (8u * (uint32_t)(sa & 3))) & 0xffu) != 0;
+  }
+  if (shared && b >= a.B / 2) return;      // the conditional workgroup writes this row
 
   // ---- prologue, vector part.  The key list usually starts with whole key scales (token =
   // position), which needs no token load; the tokens of the other chunks among the first
@@ -235,7 +250,6 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const int n_id = (int)in_prefix(0) + (int)in_prefix(1) + (int)in_prefix(2);   // (uniform; non-increasing in t)
 
   const int64_t sbA = pwA.step_begin, sbB = pwB.step_begin;
-  const int lastA = max(wA[1] - 1, 0), lastB = max(wB[1] - 1, 0);
   const __amdgpu_buffer_rsrc_t descA = __builtin_amdgcn_make_buffer_rsrc((void*)(a.step_addr + sbA * 64), 0, (lastA + 1) * 512, kBufferFlags);
   const __amdgpu_buffer_rsrc_t descB = __builtin_amdgcn_make_buffer_rsrc((void*)(a.step_addr + sbB * 64), 0, (lastB + 1) * 512, kBufferFlags);
   const int lane8 = lane * 8;
