@@ -171,26 +171,24 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
       const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + qrow * a.qs[2] + 16 * g4;
       q0 = *(const uint4*)qp; q1 = *(const uint4*)(qp + 8);
     }
-    // Q is kept as Q c (c = softmax scale x log2 e, rounded to bf16 once): the score tiles
-    // then are base-2 exponents as they leave the matrix pipe
-    const bf16x8 r0 = as_bf16x8(q0), r1 = as_bf16x8(q1);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { qb0[e] = (__bf16)((float)r0[e] * c); qb1[e] = (__bf16)((float)r1[e] * c); }
+    qb0 = as_bf16x8(q0); qb1 = as_bf16x8(q1);
   }
 
   // Softmax state per lane (one query column): running reference m (not necessarily the
   // exact maximum, see below), O^T accumulators, and the row sum l, which is accumulated
   // by a fifth MFMA whose A operand is all ones (every row of Lacc holds the same sum of
   // the bf16-rounded probabilities of this query, over all four lane groups).
-  float negmc = 0.f, thr = kFloor;   // -m c, and how far an exponent may rise before m moves (kFloor: m unset)
+  float negm = 0.f, thr = kFloor;   // -m, and how far a score may rise above m before m moves (kFloor: m unset)
   f32x4 O[4], Lacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   bf16x8 ones;
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
-  // The reference m only moves when an exponent exceeds kSlack (and once at the query's first
-  // kept key), so probabilities stay below 2^kSlack and the accumulators are rescaled rarely.
+  // The reference m only moves when a score exceeds it by more than kSlack in the base-2
+  // exponent (and once at the query's first kept key), so probabilities stay below 2^kSlack
+  // and the accumulators are rescaled rarely.
+  const float slack = kSlack / c;
 
   // scalar loads (constant address space) for the wave-uniform tables
   const const_i32_ptr pe = (const_i32_ptr)(a.phase_end + gd.phase_base + wave * P);
@@ -217,10 +215,10 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
     const bf16x8 k01 = as_bf16x8(*(const uint4*)(Kring + (ka0 ^ 16u)));
     const bf16x8 k10 = as_bf16x8(*(const uint4*)(Kring + ka1));
     const bf16x8 k11 = as_bf16x8(*(const uint4*)(Kring + (ka1 ^ 16u)));
-    // accumulators start at -m c where the pair is kept and at -inf where it is not
+    // accumulators start at -m where the pair is kept and at -inf where it is not
     f32x4 S0, S1;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { S0[e] = mask_select(negmc, mk[e]); S1[e] = mask_select(negmc, mk[4 + e]); }
+    for (int e = 0; e < 4; ++e) { S0[e] = mask_select(negm, mk[e]); S1[e] = mask_select(negm, mk[4 + e]); }
     S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k00, qb0, S0, 0, 0, 0);
     S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k10, qb0, S1, 0, 0, 0);
     S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k01, qb1, S0, 0, 0, 0);
@@ -242,10 +240,10 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
     if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > thr) != 0, 0)) {      // rare after the first steps
       const float mxr = max_across_rows(mx);
       const bool grow = mxr > thr;
-      const float shift = grow ? mxr : 0.f;               // m c moves by this much (down only when m was unset)
-      const float alpha = __builtin_amdgcn_exp2f(-fmaxf(shift, 0.f));
-      negmc -= shift;
-      thr = grow ? kSlack : thr;
+      const float shift = grow ? mxr : 0.f;               // m moves by this much (down only when m was unset)
+      const float alpha = __builtin_amdgcn_exp2f(-fmaxf(shift, 0.f) * c);
+      negm -= shift;
+      thr = grow ? slack : thr;
 #pragma unroll
       for (int e = 0; e < 8; ++e) sv[e] -= shift;
       Lacc *= alpha;
@@ -254,7 +252,7 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
     }
     float p[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(sv[e]);
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(sv[e] * c);
 
     bf16x8 pb;
 #pragma unroll

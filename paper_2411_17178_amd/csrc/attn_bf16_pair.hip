@@ -20,9 +20,8 @@
 //     loads, then chunks 0, 1 and 2.  (Where the list does not start with whole key scales,
 //     the tokens of the chunks that need them travel with the small loads; the chunks that
 //     need none go out meanwhile, one wait, then the rest.)  With at most the three chunks
-//     outstanding (a wave issues PW transfers per chunk: vmcnt 3 PW) Q is multiplied by the softmax
-//     scale; with at most chunks 1 and 2 outstanding (vmcnt 2 PW) comes the first barrier:
-//     chunk 0 is in.
+//     outstanding (a wave issues PW transfers per chunk: vmcnt 3 PW) Q is in; with at most
+//     chunks 1 and 2 outstanding (vmcnt 2 PW) comes the first barrier: chunk 0 is in.
 //   Phase p: a wave
 //     issues the descriptor loads of its steps of this phase beyond the first of each patch,
 //     runs the first step of each patch,
@@ -42,12 +41,15 @@
 // cannot tell which of them a plain LDS read depends on and would wait for all
 // (vmcnt(0)) before every read.
 //
-// Step arithmetic is that of the 8-patch kernel: S^T = K_tile . (Q c)^T by
-// v_mfma_f32_16x16x32_bf16 (c = softmax scale x log2 e; a lane owns one query column and
-// four keys per tile) on accumulators that start at minus the softmax reference where the
-// scalar lane mask keeps the pair and at -inf elsewhere (one v_cndmask per score), so the
-// tiles leave the matrix pipe as exponents; base-2 online softmax with a lazily updated
+// Step arithmetic is that of the 8-patch kernel: S^T = K_tile . Q^T by
+// v_mfma_f32_16x16x32_bf16 (a lane owns one query column and four keys per tile) on
+// accumulators that start at minus the softmax reference where the scalar lane mask keeps the
+// pair and at -inf elsewhere (one v_cndmask per score), so the tiles leave the matrix pipe as
+// masked scores relative to the reference; base-2 online softmax with a lazily updated
 // reference, O^T += V^T . P^T with ds_read_b64_tr_b16 operands, row sums by a fifth MFMA.
+// (Folding the softmax scale into Q, which would save the multiplication per score, costs a
+// second bf16 rounding of Q: with peaked attention -- scores of some tens -- the output
+// error grows tenfold.  The scale is applied in fp32.)
 #include <type_traits>
 
 #include "attn_bf16_common.h"
@@ -108,8 +110,8 @@ __device__ inline void lds_wait(uint2 (&va)[4][2]) {
 struct PatchState {       // one query patch of a wave
   bf16x8 qb0, qb1;        // Q^T as the B operand: lane (n, g4) holds Q[query n][16 g4 .. +15]
   f32x4 O[4], Lacc;       // O^T accumulators and row sums
-  float thr, negmc;       // the softmax reference m as -m c; thr = how far a score (in units of
-                          // the exponent, relative to m) may rise before m moves: kFloor while m is unset
+  float thr, negm;        // minus the softmax reference m; thr = how far a score may rise above m
+                          // before m moves: kFloor while m is unset
 };
 
 }  // namespace
@@ -274,14 +276,13 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   auto init_patch = [&](PatchState& ps, const PatchWords& w) {
     const int ld_row = query_row(w, n, true);
     const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
-    // (inline assembly: the compiler then does not know of a load into these registers, and
-    // the explicit wait below, which leaves the chunk transfers in flight, stays as written;
-    // the values are scaled there)
+    // (inline assembly: the compiler then does not know of a load into these registers and
+    // places no wait of its own, which would cover the chunk transfers too, before their use)
     u32x4 r0, r1;
     asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
                  : "=&v"(r0), "=&v"(r1) : "v"(qp) : "memory");
     ps.qb0 = __builtin_bit_cast(bf16x8, r0); ps.qb1 = __builtin_bit_cast(bf16x8, r1);
-    ps.thr = kFloor; ps.negmc = 0.f;
+    ps.thr = kFloor; ps.negm = 0.f;
     ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) ps.O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -294,6 +295,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
   asm volatile("" : "+v"(ones));     // kept in four registers (the compiler would rebuild it in every step)
+  const float slack = kSlack / c;
   // Step descriptors of a patch for one phase: the first step's is fetched during the phase
   // before (d0), those of the next kLater steps at the start of the phase (dl).
   uint2 dA0 = make_uint2(0u, 0u), dB0 = dA0, dAl[kLater], dBl[kLater];
@@ -349,20 +351,11 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     if (n_id < 2) issue_chunk(1, tok_of(1, tok1));
     issue_chunk(2, tok_of(2, tok2));
   }
-  // Everything older than the three chunks is in: Q is turned into Q c (c = softmax scale x
-  // log2 e, rounded to bf16 once) while chunk 0 is on its way, so that the score tiles are
-  // base-2 exponents as they leave the matrix pipe.  (The registers are tied to this point:
-  // placed any earlier, the conversion would make the compiler wait for all loads, chunks
-  // included, between two chunk transfers.)
+  // (Q was loaded through inline assembly: everything older than the three chunks is in once
+  // at most their transfers are outstanding, and the registers are tied to that point)
   wait_vmcnt<3 * kDmaPerChunk>();
-  auto scale_q = [&](PatchState& ps) {
-    asm volatile("" : "+v"(ps.qb0), "+v"(ps.qb1));
-    const bf16x8 q0 = ps.qb0, q1 = ps.qb1;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { ps.qb0[e] = (__bf16)((float)q0[e] * c); ps.qb1[e] = (__bf16)((float)q1[e] * c); }
-  };
-  scale_q(A);
-  if constexpr (PW == 2) scale_q(B);
+  asm volatile("" : "+v"(A.qb0), "+v"(A.qb1));
+  if constexpr (PW == 2) asm volatile("" : "+v"(B.qb0), "+v"(B.qb1));
   wait_vmcnt<2 * kDmaPerChunk>();
   asm volatile("s_barrier" ::: "memory");
 
@@ -387,12 +380,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     // (the masks were requested before the K pieces and share their counter: they are in,
     // and the compiler should know before the V^T reads go out, or it waits for those too)
     asm volatile("" : : "s"(mk[0]), "s"(mk[1]), "s"(mk[2]), "s"(mk[3]), "s"(mk[4]), "s"(mk[5]), "s"(mk[6]), "s"(mk[7]));
-    // The accumulators of the score tiles start at -m c where the pair is kept and at -inf
-    // where it is not (one v_cndmask per score, by the lane masks): what leaves the matrix
-    // pipe is the exponent of the probability.
+    // The accumulators of the score tiles start at -m where the pair is kept and at -inf
+    // where it is not (one v_cndmask per score, by the lane masks, off the path that waits
+    // for the matrix pipe): the tiles come out as masked scores relative to the reference.
     f32x4 S0, S1;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { S0[e] = mask_select(ps.negmc, mk[e]); S1[e] = mask_select(ps.negmc, mk[4 + e]); }
+    for (int e = 0; e < 4; ++e) { S0[e] = mask_select(ps.negm, mk[e]); S1[e] = mask_select(ps.negm, mk[4 + e]); }
     S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k00), ps.qb0, S0, 0, 0, 0);
     S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k10), ps.qb0, S1, 0, 0, 0);
     S0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k01), ps.qb1, S0, 0, 0, 0);
@@ -402,19 +395,19 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     uint2 va[4][2];
     lds_read_v<VOFF>(v0, v1, va_addr, va);
     float sv[8] = {S0[0], S0[1], S0[2], S0[3], S1[0], S1[1], S1[2], S1[3]};
-    // The reference m of a query only moves when one of its exponents exceeds the slack
-    // (probabilities stay below 2^kSlack), and once at the query's first kept key.  The common
-    // case needs the lane's own maximum only; the maximum over the query's four lanes is
-    // formed when some lane of the wave has crossed its threshold.
+    // The reference m of a query only moves when one of its scores exceeds it by more than
+    // the slack (probabilities stay below 2^kSlack), and once at the query's first kept key.
+    // The common case needs the lane's own maximum only; the maximum over the query's four
+    // lanes is formed when some lane of the wave has crossed its threshold.
     const float m012 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), m345 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);   // (v_max3)
     const float mx = fmaxf(fmaxf(fmaxf(sv[6], sv[7]), m012), m345);
     if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > ps.thr) != 0, 0)) {   // rare after the first steps
       const float mxr = max_across_rows(mx);
       const bool grow = mxr > ps.thr;
-      const float shift = grow ? mxr : 0.f;               // m c moves by this much (down only when m was unset)
-      const float alpha = __builtin_amdgcn_exp2f(-fmaxf(shift, 0.f));
-      ps.negmc -= shift;
-      ps.thr = grow ? kSlack : ps.thr;
+      const float shift = grow ? mxr : 0.f;               // m moves by this much (down only when m was unset)
+      const float alpha = __builtin_amdgcn_exp2f(-fmaxf(shift, 0.f) * c);
+      ps.negm -= shift;
+      ps.thr = grow ? slack : ps.thr;
 #pragma unroll
       for (int e = 0; e < 8; ++e) sv[e] -= shift;
       ps.Lacc *= alpha;
@@ -423,7 +416,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     }
     float p[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(sv[e]);
+    for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(sv[e] * c);
     bf16x8 pb;
 #pragma unroll
     for (int e = 0; e < 8; ++e) pb[e] = (__bf16)p[e];
