@@ -54,8 +54,9 @@ def measured_traffic(workload, kernel, kernel_us):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload
     (FETCH_SIZE and WRITE_SIZE runs, each scaled by a known-size copy kernel).  None when no
     summary exists for this kernel instance, or when the kernel time recorded with the
-    counters differs from this run's by more than 5 % (the summary then describes another
-    version of the kernel)."""
+    counters differs from this run's by more than 8 % (the summary then describes another
+    version of the kernel; short runs under the profiler are a few per cent slower than a
+    long run without it)."""
     path = os.path.join(ROOT, "profiles", f"{kernel.split(chr(60))[0]}_{workload}_pmc.txt")
     if not os.path.exists(path):
         return None
@@ -66,7 +67,7 @@ def measured_traffic(workload, kernel, kernel_us):
             kv[a.strip()] = b.strip()
     if kv.get("kernel") != kernel or kv.get("workload") != workload or "kernel_us" not in kv:
         return None
-    if abs(float(kv["kernel_us"]) - kernel_us) > 0.05 * kernel_us:
+    if abs(float(kv["kernel_us"]) - kernel_us) > 0.08 * kernel_us:
         return None
     return int(kv["traffic_bytes_per_launch"])
 
