@@ -245,7 +245,12 @@ litevar_status litevar_mask_export_csr(const litevar_plan* plan, int32_t head, i
                                        int32_t* d_cols, size_t cols_cap, void* stream);
 
 typedef enum { LITEVAR_BF16 = 0, LITEVAR_F32 = 1 } litevar_dtype;
-enum { LITEVAR_FLAG_CFG_SHARE = 1u }; /* batch rows [0, B/2) conditional, b + B/2 its partner */
+enum {
+  LITEVAR_FLAG_CFG_SHARE = 1u,       /* batch rows [0, B/2) conditional, b + B/2 its partner */
+  LITEVAR_FLAG_QKV8_IN_KERNEL = 2u   /* litevar_windowed_attn_qkv8_fwd only: convert the 8-bit operands in
+                                        the attention kernel whatever the plan's shape (the plan must have
+                                        16 patches per group); no workspace is used */
+};
 
 /*
  * O = softmax(sm_scale * Q K^T restricted to the plan's kept pairs) V   (Section 2),
@@ -323,13 +328,19 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
  *                          litevar_windowed_attn_fwd on 8-bit operands: d_q int8
  *                          [B,H,q_len,64] with d_q_sz float [B,H,q_len,2], d_k / d_v int8
  *                          [B,H,kv_len,64] with their (s, z); all packed.  d_o DEVICE bf16
- *                          [B,H,q_len,64].  The operands are dequantised once into
- *                          d_workspace (DEVICE, 256-byte aligned,
- *                          litevar_windowed_attn_qkv8_workspace_bytes() bytes, contents
- *                          undefined before and after) and the bf16 kernels run on that copy:
- *                          results equal attention on the dequantised tensors up to their
- *                          rounding to bf16 and the bf16 path's own rounding.  Other arguments
- *                          as litevar_windowed_attn_fwd.  Asynchronous on `stream`.
+ *                          [B,H,q_len,64].  Plans with 16 patches per group whose groups
+ *                          stream at most a quarter more key rows than the tensors hold (KV-cache steps) hand codes and
+ *                          parameters to the attention kernel, which converts them on their way
+ *                          into LDS; litevar_windowed_attn_qkv8_workspace_bytes() is then 0 and
+ *                          d_workspace is ignored.  For other plans the operands are
+ *                          dequantised once into d_workspace (DEVICE, 256-byte aligned, that
+ *                          many bytes, contents undefined before and after) and the bf16 kernels
+ *                          run on that copy.  Either way the results equal attention on the
+ *                          dequantised tensors up to their rounding to bf16 and the bf16 path's
+ *                          own rounding.  LITEVAR_FLAG_QKV8_IN_KERNEL in `flags` asks for the
+ *                          first form whatever the plan's shape (LITEVAR_E_UNSUPPORTED unless
+ *                          the plan has 16 patches per group).  Other arguments as
+ *                          litevar_windowed_attn_fwd.  Asynchronous on `stream`.
  */
 litevar_status litevar_qkv8_quantize(const void* d_x, litevar_dtype dt, int64_t rows, int64_t row_stride,
                                      int32_t D, int8_t* d_codes, float* d_scale_zero, void* stream);

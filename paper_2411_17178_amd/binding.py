@@ -16,6 +16,7 @@ MAX_SCALES = 32
 MAX_HEADS = 256
 MASK_WINDOW_2D, MASK_BAND_1D = 0, 1
 FLAG_CFG_SHARE = 1
+FLAG_QKV8_IN_KERNEL = 2
 DT_BF16, DT_F32 = 0, 1
 
 
@@ -347,10 +348,18 @@ def litevar_qkv8_dequantize(codes, scale_zero, stream=None):
     return out
 
 
+def litevar_windowed_attn_qkv8_workspace_bytes(plan, B, H):
+    n = C.c_size_t(0)
+    _check(load_library().litevar_windowed_attn_qkv8_workspace_bytes(C.byref(plan.handle), C.c_int32(B),
+                                                                      C.c_int32(H), C.byref(n)))
+    return n.value
+
+
 def litevar_windowed_attn_qkv8_fwd(plan, q8, q_sz, k8, k_sz, v8, v_sz, sm_scale, out=None,
-                                   cfg_share=None, workspace=None, stream=None):
+                                   cfg_share=None, workspace=None, stream=None, in_kernel=False):
     """Windowed attention on 8-bit Q, K, V (codes int8 [B,H,L,64] + (scale, zero) float32
-    [B,H,L,2], as litevar_qkv8_quantize returns them); output bf16 [B,H,q_len,64]."""
+    [B,H,L,2], as litevar_qkv8_quantize returns them); output bf16 [B,H,q_len,64].
+    in_kernel: pass LITEVAR_FLAG_QKV8_IN_KERNEL."""
     lib = load_library()
     B, H, Lq, D = q8.shape
     for t, sz in ((q8, q_sz), (k8, k_sz), (v8, v_sz)):
@@ -370,6 +379,8 @@ def litevar_windowed_attn_qkv8_fwd(plan, q8, q_sz, k8, k_sz, v8, v_sz, sm_scale,
         assert cfg_share.is_cuda and cfg_share.dtype == torch.uint8 and cfg_share.is_contiguous()
         assert cfg_share.shape == (H, plan.n_scales)
         flags, share_ptr = FLAG_CFG_SHARE, C.c_void_p(cfg_share.data_ptr())
+    if in_kernel:
+        flags |= FLAG_QKV8_IN_KERNEL
     _check(lib.litevar_windowed_attn_qkv8_fwd(
         C.byref(plan.handle), C.c_void_p(q8.data_ptr()), C.c_void_p(q_sz.data_ptr()),
         C.c_void_p(k8.data_ptr()), C.c_void_p(k_sz.data_ptr()), C.c_void_p(v8.data_ptr()),

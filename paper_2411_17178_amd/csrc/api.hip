@@ -223,6 +223,50 @@ litevar_status litevar_mask_export_csr(const litevar_plan* plan, int32_t head, i
   return export_csr(plan, head, d_rowptr, d_cols, cols_cap, (hipStream_t)stream);
 }
 
+}  // extern "C"
+
+namespace lv {
+
+litevar_status make_attn_args(const litevar_plan* plan, int32_t B, int32_t H, int32_t D, float sm_scale,
+                              const uint8_t* d_cfg_share, uint32_t flags, AttnArgs& a) {
+  litevar_status rc = check_plan(plan);
+  if (rc) return rc;
+  if (B < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "B and H must be positive (got %d, %d)", B, H);
+  if ((int64_t)B * H > (1 << 24)) return fail(LITEVAR_E_UNSUPPORTED, "B*H above 2^24");
+  if (D != 64) return fail(LITEVAR_E_UNSUPPORTED, "head dimension %d is not supported (only 64)", D);
+  if (!(sm_scale > 0.f) || !std::isfinite(sm_scale) || sm_scale > 1.0e4f)
+    return fail(LITEVAR_E_INVALID_ARG, "sm_scale must be finite, positive and at most 1e4");
+  if (flags & ~(uint32_t)LITEVAR_FLAG_CFG_SHARE) return fail(LITEVAR_E_INVALID_ARG, "unknown flag bits 0x%x", flags);
+  if (flags & LITEVAR_FLAG_CFG_SHARE) {
+    if (B & 1) return fail(LITEVAR_E_INVALID_ARG, "CFG sharing needs an even batch (got %d)", B);
+    if (!d_cfg_share) return fail(LITEVAR_E_INVALID_ARG, "CFG sharing flag set but d_cfg_share is NULL");
+  }
+  if (plan->n_heads > 0 && H != plan->n_heads)
+    return fail(LITEVAR_E_INVALID_ARG, "the plan holds radius tables for %d heads, the call has H = %d", plan->n_heads, H);
+  memset(&a, 0, sizeof a);
+  a.B = B; a.H = H; a.sm_scale = sm_scale;
+  a.cfg_share = (flags & LITEVAR_FLAG_CFG_SHARE) ? d_cfg_share : nullptr;
+  a.n_scales = plan->n_scales;
+  const char* blob = (const char*)plan->d_blob;
+  a.groups = (const GroupDesc*)(blob + plan->off[kSecGroups]);
+  a.waves = (const WaveDesc*)(blob + plan->off[kSecWaves]);
+  a.phase_end = (const int32_t*)(blob + plan->off[kSecPhaseEnd]);
+  a.union_tok = (const int32_t*)(blob + plan->off[kSecUnion]);
+  a.step_addr = (const uint2*)(blob + plan->off[kSecStepAddr]);
+  a.step_mask = (const uint64_t*)(blob + plan->off[kSecStepMask]);
+  a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
+  a.n_groups = plan->n_groups;
+  a.head_map = plan->n_heads > 0 ? (const int32_t*)(blob + plan->off[kSecHeadMap]) : nullptr;
+  a.q_len = plan->q_len;
+  a.hdr = (Header*)(plan->d_blob);
+  a.spin_limit = plan->spin_limit > 0 ? plan->spin_limit : kDefaultSpinLimit;
+  return LITEVAR_OK;
+}
+
+}  // namespace lv
+
+extern "C" {
+
 static bool strides_ok(const int64_t* s, int B, int H, int64_t len, int D, int64_t out[3]) {
   if (!s) { out[2] = D; out[1] = len * D; out[0] = (int64_t)H * len * D; return true; }
   for (int i = 0; i < 3; ++i) out[i] = s[i];
@@ -238,26 +282,13 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
                                          const int64_t* kv_strides, const int64_t* o_strides,
                                          float sm_scale, const uint8_t* d_cfg_share, uint32_t flags,
                                          void* stream) {
-  litevar_status rc = check_plan(plan);
-  if (rc) return rc;
+  AttnArgs a;
+  if (litevar_status s = make_attn_args(plan, B, H, D, sm_scale, d_cfg_share, flags, a)) return s;
   if (!d_q || !d_k || !d_v || !d_o) return fail(LITEVAR_E_INVALID_ARG, "q, k, v or o is NULL");
-  if (B < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "B and H must be positive (got %d, %d)", B, H);
-  if ((int64_t)B * H > (1 << 24)) return fail(LITEVAR_E_UNSUPPORTED, "B*H above 2^24");
-  if (D != 64) return fail(LITEVAR_E_UNSUPPORTED, "head dimension %d is not supported (only 64)", D);
   if (dt != LITEVAR_BF16 && dt != LITEVAR_F32) return fail(LITEVAR_E_UNSUPPORTED, "unknown dtype %d", (int)dt);
-  if (!(sm_scale > 0.f) || !std::isfinite(sm_scale) || sm_scale > 1.0e4f)
-    return fail(LITEVAR_E_INVALID_ARG, "sm_scale must be finite, positive and at most 1e4");
-  if (flags & ~(uint32_t)LITEVAR_FLAG_CFG_SHARE) return fail(LITEVAR_E_INVALID_ARG, "unknown flag bits 0x%x", flags);
-  if (flags & LITEVAR_FLAG_CFG_SHARE) {
-    if (B & 1) return fail(LITEVAR_E_INVALID_ARG, "CFG sharing needs an even batch (got %d)", B);
-    if (!d_cfg_share) return fail(LITEVAR_E_INVALID_ARG, "CFG sharing flag set but d_cfg_share is NULL");
-  }
   if (d_o == d_q || d_o == d_k || d_o == d_v) return fail(LITEVAR_E_INVALID_ARG, "o aliases an input");
   const uintptr_t align = (uintptr_t)d_q | (uintptr_t)d_k | (uintptr_t)d_v | (uintptr_t)d_o;
   if (align & 15) return fail(LITEVAR_E_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
-
-  AttnArgs a;
-  memset(&a, 0, sizeof a);
   if (!strides_ok(q_strides, B, H, plan->q_len, D, a.qs) ||
       !strides_ok(kv_strides, B, H, plan->kv_len, D, a.ks) ||
       !strides_ok(o_strides, B, H, plan->q_len, D, a.os))
@@ -270,24 +301,6 @@ litevar_status litevar_windowed_attn_fwd(const litevar_plan* plan, const void* d
   if (a.ks[2] * esize >= ((int64_t)1 << 24))
     return fail(LITEVAR_E_UNSUPPORTED, "k/v token stride of 16 MiB or more");
   a.q = d_q; a.k = d_k; a.v = d_v; a.o = d_o;
-  a.B = B; a.H = H; a.sm_scale = sm_scale;
-  a.cfg_share = (flags & LITEVAR_FLAG_CFG_SHARE) ? d_cfg_share : nullptr;
-  a.n_scales = plan->n_scales;
-  const char* blob = (const char*)plan->d_blob;
-  a.groups = (const GroupDesc*)(blob + plan->off[kSecGroups]);
-  a.waves = (const WaveDesc*)(blob + plan->off[kSecWaves]);
-  a.phase_end = (const int32_t*)(blob + plan->off[kSecPhaseEnd]);
-  a.union_tok = (const int32_t*)(blob + plan->off[kSecUnion]);
-  a.step_addr = (const uint2*)(blob + plan->off[kSecStepAddr]);
-  a.step_mask = (const uint64_t*)(blob + plan->off[kSecStepMask]);
-  a.step_tok = (const int32_t*)(blob + plan->off[kSecStepTok]);
-  a.n_groups = plan->n_groups;
-  if (plan->n_heads > 0 && H != plan->n_heads)
-    return fail(LITEVAR_E_INVALID_ARG, "the plan holds radius tables for %d heads, the call has H = %d", plan->n_heads, H);
-  a.head_map = plan->n_heads > 0 ? (const int32_t*)(blob + plan->off[kSecHeadMap]) : nullptr;
-  a.q_len = plan->q_len;
-  a.hdr = (Header*)(plan->d_blob);
-  a.spin_limit = plan->spin_limit > 0 ? plan->spin_limit : kDefaultSpinLimit;
   if (dt == LITEVAR_F32) return launch_attn_f32(plan, a, (hipStream_t)stream);
   return launch_attn_bf16(plan, a, (hipStream_t)stream);
 }

@@ -120,7 +120,16 @@ struct PatchState {       // one query patch of a wave
 // launches that fill the GPU) or 1 (16 waves per workgroup, one workgroup per CU: a launch with
 // no more workgroups than CUs then still has four waves on every SIMD).  Same plan, same
 // phases; with 16 waves the loading duty of a chunk is one K or one V transfer per wave.
-template <int PW>
+//
+// Q8 (Section 4, 8-bit Q, K, V): the operands are int8 codes with one (scale, zero point) per
+// token row.  A wave's share of a chunk then comes through registers instead of LDS-DMA: one
+// 16-byte load of codes and one of the row's parameters per lane (lanes 0-31 K rows, lanes
+// 32-63 V rows with eight waves; K waves and V waves with sixteen), requested where the bf16
+// form issues its transfers, converted to bf16(s code + z) and written to the ring -- same
+// slots, same swizzle -- at the end of the phase, before the barrier.  Steps, masks and
+// epilogue are the same code; the ring holds exactly what a dequantised bf16 copy would put
+// there, so the results equal those of the bf16 kernel on such a copy bit for bit.
+template <int PW, bool Q8>
 __global__ __launch_bounds__((kGroupPatches / PW) * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void k_attn_bf16_pair(AttnArgs a, float c) {
   [[maybe_unused]] constexpr int NWV = kGroupPatches / PW;   // waves per workgroup
@@ -170,12 +179,14 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   // ---- loading duty: rows [8 w, 8 w + 8) of every chunk, w = wave mod 8: K and V rows with
   // eight waves, K rows (waves 0-7) or V rows (waves 8-15) with sixteen ----
-  const unsigned char* Kp = (const unsigned char*)((const __bf16*)a.k + b * a.ks[0] + h * a.ks[1]);
-  const unsigned char* Vp = (const unsigned char*)((const __bf16*)a.v + b * a.ks[0] + h * a.ks[1]);
-  const unsigned row_bytes = (unsigned)a.ks[2] * 2u;   // a (batch, head) slab spans < 2 GiB (checked by the API)
+  constexpr int kElem = Q8 ? 1 : 2;                    // bytes per operand element
+  const unsigned char* Kp = (const unsigned char*)a.k + (b * a.ks[0] + h * a.ks[1]) * kElem;
+  const unsigned char* Vp = (const unsigned char*)a.v + (b * a.ks[0] + h * a.ks[1]) * kElem;
+  const unsigned row_bytes = (unsigned)a.ks[2] * kElem;   // a (batch, head) slab spans < 2 GiB (checked by the API)
   const int32_t* utok = a.union_tok + gd.union_base;
   const int ident = __builtin_amdgcn_readfirstlane(gd.ident);   // union entries [0, ident) are token i at position i
-  const int row = 8 * (wave & 7) + (lane >> 3);
+  // bf16: eight lanes per 128-byte row; Q8: four lanes per 64-byte row of codes
+  const int row = Q8 ? 8 * (wave & 7) + ((lane >> 2) & 7) : 8 * (wave & 7) + (lane >> 3);
   // A lane's row of chunk t goes to slot (t % 5) * 64 + row.  Chunks start at multiples of 64
   // slots, so the slot's swizzle -- and with it the 16-byte piece of the source row that
   // this lane fetches -- does not depend on t.
@@ -190,7 +201,37 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
       __builtin_amdgcn_global_load_lds((global_void*)(Vp + src), (lds_void*)(Vring + slot0 * kRingRowBytes), 16, 0, 0);
   };
   constexpr int kDmaPerChunk = PW;                       // transfers that a wave issues per chunk
-  // (tokens and descriptors through buffer loads: a scalar resource and a scalar offset plus a
+  // Q8: this lane's share of a chunk on its way through registers
+  struct ChunkRegs { u32x4 codes; float2 sz; };
+  const bool q8_v = PW == 2 ? lane >= 32 : wave >= 8;     // the lane works on V rows (else K rows)
+  const bool q8_active = PW == 2 || lane < 32;
+  [[maybe_unused]] auto load_chunk = [&](int tok) -> ChunkRegs {
+    ChunkRegs r;
+    r.codes = u32x4{0u, 0u, 0u, 0u}; r.sz = make_float2(0.f, 0.f);
+    if (q8_active) {
+      const unsigned char* base = q8_v ? Vp : Kp;
+      const float2* sz = (q8_v ? a.v_sz : a.k_sz) + (int64_t)(b * a.H + h) * (a.ks[1] / a.ks[2]);
+      r.codes = *(const u32x4*)(base + __umul24((unsigned)tok, row_bytes) + 16u * ((unsigned)lane & 3u));
+      r.sz = sz[tok];
+    }
+    return r;
+  };
+  [[maybe_unused]] auto commit_chunk = [&](int t, const ChunkRegs& r) {   // chunk t -> ring slots (t % 5) * 64 ...
+    if (!q8_active) return;
+    const unsigned slot = (unsigned)((t % kRingChunks) * C + row);
+    const unsigned sw = ring_swizzle((unsigned)row), p2 = 2u * ((unsigned)lane & 3u);
+    unsigned char* dst = (q8_v ? Vring : Kring) + slot * kRingRowBytes;
+    bf16x8 lo, hi;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int8_t c0 = (int8_t)((r.codes[e >> 2] >> (8 * (e & 3))) & 0xffu);
+      const int8_t c1 = (int8_t)((r.codes[2 + (e >> 2)] >> (8 * (e & 3))) & 0xffu);
+      lo[e] = (__bf16)fmaf(r.sz.x, (float)c0, r.sz.y);
+      hi[e] = (__bf16)fmaf(r.sz.x, (float)c1, r.sz.y);
+    }
+    *(bf16x8*)(dst + ((p2 ^ sw) << 4)) = lo;
+    *(bf16x8*)(dst + (((p2 + 1u) ^ sw) << 4)) = hi;
+  };  // (tokens and descriptors through buffer loads: a scalar resource and a scalar offset plus a
   // lane offset register, where a flat address costs 64-bit vector arithmetic per load)
   const __amdgpu_buffer_rsrc_t tok_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)utok, 0, NC * C * 4, kBufferFlags);
   // this lane's row of chunk t (clamped to the last chunk): load_tok() fetches the list entry
@@ -275,13 +316,24 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   // is never stored, and MFMA columns do not mix
   auto init_patch = [&](PatchState& ps, const PatchWords& w) {
     const int ld_row = query_row(w, n, true);
-    const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
-    // (inline assembly: the compiler then does not know of a load into these registers and
-    // places no wait of its own, which would cover the chunk transfers too, before their use)
-    u32x4 r0, r1;
-    asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
-                 : "=&v"(r0), "=&v"(r1) : "v"(qp) : "memory");
-    ps.qb0 = __builtin_bit_cast(bf16x8, r0); ps.qb1 = __builtin_bit_cast(bf16x8, r1);
+    if constexpr (Q8) {
+      const int8_t* qp = (const int8_t*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
+      const u32x4 qc = *(const u32x4*)qp;
+      const float2 qz = a.q_sz[(int64_t)(b * a.H + h) * a.q_len + ld_row];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        ps.qb0[e] = (__bf16)fmaf(qz.x, (float)(int8_t)((qc[e >> 2] >> (8 * (e & 3))) & 0xffu), qz.y);
+        ps.qb1[e] = (__bf16)fmaf(qz.x, (float)(int8_t)((qc[2 + (e >> 2)] >> (8 * (e & 3))) & 0xffu), qz.y);
+      }
+    } else {
+      const __bf16* qp = (const __bf16*)a.q + b * a.qs[0] + h * a.qs[1] + ld_row * a.qs[2] + 16 * g4;
+      // (inline assembly: the compiler then does not know of a load into these registers and
+      // places no wait of its own, which would cover the chunk transfers too, before their use)
+      u32x4 r0, r1;
+      asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
+                   : "=&v"(r0), "=&v"(r1) : "v"(qp) : "memory");
+      ps.qb0 = __builtin_bit_cast(bf16x8, r0); ps.qb1 = __builtin_bit_cast(bf16x8, r1);
+    }
     ps.thr = kFloor; ps.negm = 0.f;
     ps.Lacc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -335,7 +387,14 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   }
   // The chunks go out behind the small loads (a load issued behind a chunk is held up until
   // the chunk's data is in), chunks 1 and 2 (phase 1) last: phase 0 waits for everything but them.
-  if (n_id == 3) {
+  if constexpr (Q8) {
+    // through registers: the three chunks are requested together, converted and written, and
+    // the first barrier finds all of them in the ring
+    int tok0 = 0, tok1 = 0, tok2 = 0;
+    if (n_id < 3) { tok0 = load_tok(0); tok1 = load_tok(1); tok2 = load_tok(2); }
+    const ChunkRegs c0 = load_chunk(tok_of(0, tok0)), c1 = load_chunk(tok_of(1, tok1)), c2 = load_chunk(tok_of(2, tok2));
+    commit_chunk(0, c0); commit_chunk(1, c1); commit_chunk(2, c2);
+  } else if (n_id == 3) {
     issue_chunk(0, tok_of(0, 0)); issue_chunk(1, tok_of(1, 0)); issue_chunk(2, tok_of(2, 0));
   } else {
     // Some of the three chunks need their tokens: these are requested behind the small loads
@@ -353,11 +412,15 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   }
   // (Q was loaded through inline assembly: everything older than the three chunks is in once
   // at most their transfers are outstanding, and the registers are tied to that point)
-  wait_vmcnt<3 * kDmaPerChunk>();
-  asm volatile("" : "+v"(A.qb0), "+v"(A.qb1));
-  if constexpr (PW == 2) asm volatile("" : "+v"(B.qb0), "+v"(B.qb1));
-  wait_vmcnt<2 * kDmaPerChunk>();
-  asm volatile("s_barrier" ::: "memory");
+  if constexpr (Q8) {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // (the ring writes above are visible)
+  } else {
+    wait_vmcnt<3 * kDmaPerChunk>();
+    asm volatile("" : "+v"(A.qb0), "+v"(A.qb1));
+    if constexpr (PW == 2) asm volatile("" : "+v"(B.qb0), "+v"(B.qb1));
+    wait_vmcnt<2 * kDmaPerChunk>();
+    asm volatile("s_barrier" ::: "memory");
+  }
 
   // One step: 32 keys against the 16 queries of patch ps.
   auto run_step = [&](PatchState& ps, const uint2 cur, const uint64_t* masks, int s) {
@@ -435,6 +498,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   auto run_phase = [&](int ph, auto is_first, auto has_next) {
     constexpr bool FIRST = decltype(is_first)::value, NEXT = decltype(has_next)::value;
     if (!FIRST && ph == kBoostPhases) __builtin_amdgcn_s_setprio(0);
+    [[maybe_unused]] ChunkRegs cr0, cr1;                 // Q8: the chunks of phase ph + 1 on their way
     // (scalar loads, two phases ahead of their use)
     const int end2A = peA[last_chunk(ph + 2)], end2B = PW == 2 ? peB[last_chunk(ph + 2)] : 0;
     if constexpr (!FIRST) {            // (phase 0: fetched in the prologue)
@@ -458,7 +522,8 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
         const int t0 = tok_of(2 * ph + 1, tokn0), t1 = tok_of(2 * ph + 2, tokn1);
         tokn0 = load_tok(2 * ph + 3); tokn1 = load_tok(2 * ph + 4);
         // the chunks of phase ph + 1, into the slots of chunks 2 ph - 4 and 2 ph - 3
-        issue_chunk(2 * ph + 1, t0); issue_chunk(2 * ph + 2, t1);
+        if constexpr (Q8) { cr0 = load_chunk(t0); cr1 = load_chunk(t1); }
+        else { issue_chunk(2 * ph + 1, t0); issue_chunk(2 * ph + 2, t1); }
       }
     }
 #pragma unroll
@@ -476,6 +541,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     // this wave is outstanding.  All LDS reads of the phase have returned (each step waits
     // for its own), so after the barrier the slots of chunks 2 ph - 3 and 2 ph - 2 are free.
     wait_vmcnt<0>();
+    if constexpr (Q8 && NEXT && !FIRST) {
+      // (their slots held chunks 2 ph - 4 and 2 ph - 3, which nobody has read since the
+      // barrier that ended phase ph - 1; the writes are complete before this phase's barrier)
+      commit_chunk(2 * ph + 1, cr0); commit_chunk(2 * ph + 2, cr1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
     if constexpr (NEXT) asm volatile("s_barrier" ::: "memory");
   };
   {
@@ -531,10 +602,12 @@ litevar_status launch_attn_bf16_pair(const litevar_plan* pl, const AttnArgs& a, 
     pw = working <= cus ? 1 : 2;
   }
   const float c = a.sm_scale * 1.4426950408889634f;
-  if (pw == 1)
-    hipLaunchKernelGGL(k_attn_bf16_pair<1>, dim3((unsigned)blocks), dim3(kGroupPatches * 64), 0, st, a, c);
-  else
-    hipLaunchKernelGGL(k_attn_bf16_pair<2>, dim3((unsigned)blocks), dim3(kGroupPatches / 2 * 64), 0, st, a, c);
+  const bool q8 = a.k_sz != nullptr;
+  const dim3 grid((unsigned)blocks), wg1(kGroupPatches * 64), wg2(kGroupPatches / 2 * 64);
+  if (pw == 1 && q8) hipLaunchKernelGGL((k_attn_bf16_pair<1, true>), grid, wg1, 0, st, a, c);
+  else if (pw == 1) hipLaunchKernelGGL((k_attn_bf16_pair<1, false>), grid, wg1, 0, st, a, c);
+  else if (q8) hipLaunchKernelGGL((k_attn_bf16_pair<2, true>), grid, wg2, 0, st, a, c);
+  else hipLaunchKernelGGL((k_attn_bf16_pair<2, false>), grid, wg2, 0, st, a, c);
   return hip_check(hipGetLastError(), "bf16 attention launch");
 }
 

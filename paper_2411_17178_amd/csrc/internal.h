@@ -60,7 +60,16 @@ struct AttnArgs {
   int q_len;                     // query rows per (batch, head)
   Header* hdr;                   // the blob's header: checked by every kernel before the plan is used
   int spin_limit;                // polls after which a kernel's wait on an LDS flag gives up
+  // 8-bit operands (Section 4): q, k, v then hold int8 codes (strides in codes) and these the
+  // (scale, zero point) of every token row, packed [B][H][len]; nullptr for bf16 / fp32 operands
+  const float2* q_sz; const float2* k_sz; const float2* v_sz;
 };
+
+// Checks what every attention entry point checks (plan, batch and head counts, softmax scale,
+// flags) and fills the fields of `a` that come from the plan and from these arguments; the
+// operand pointers and strides are the caller's.
+litevar_status make_attn_args(const litevar_plan* plan, int32_t B, int32_t H, int32_t D, float sm_scale,
+                              const uint8_t* d_cfg_share, uint32_t flags, AttnArgs& a);
 
 litevar_status launch_attn_f32(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);
 litevar_status launch_attn_bf16(const litevar_plan* pl, const AttnArgs& a, hipStream_t st);

@@ -9,9 +9,9 @@
 // exactly this order of operations (IEEE division, no contraction), so that the codes can be
 // compared bit for bit with a CPU statement of the same formula.
 //
-// The attention entry point dequantises K, V and Q into a caller-owned bf16 workspace (one
-// pass, each value converted once however many workgroups will stage it) and runs the bf16
-// windowed-attention kernels on it.
+// The attention entry point hands codes and parameters to the 16-patch attention kernel, which
+// converts them on their way into its LDS ring; for plans with smaller groups it dequantises
+// K, V and Q into a caller-owned bf16 workspace and runs the bf16 kernels on that copy.
 #include "attn_bf16_common.h"
 
 namespace lv {
@@ -131,11 +131,23 @@ litevar_status litevar_qkv8_dequantize(const int8_t* d_codes, const float* d_sca
   return hip_check(hipGetLastError(), "dequantiser launch");
 }
 
+// Plans whose groups hold 16 patches can be served by the attention kernel's own 8-bit form,
+// which converts every key row once per group that streams it.  That pays while the groups of
+// a (batch, head) stream few rows more than once (KV-cache steps: one group; the 680-token
+// sequence); once they stream a quarter more rows than the three tensors hold (q_len + 2 kv_len
+// per (batch, head)), a single dequantising pass over the tensors is cheaper (measured: both
+// cost 35-40 ps per row; 2240 tokens: 9088 rows streamed against 6720, 276 against 262 us).
+static bool fused(const litevar_plan* plan) {
+  if (plan->waves_per_group != 16) return false;
+  const int64_t streamed = plan->n_union_keys / (plan->n_head_groups > 0 ? plan->n_head_groups : 1);
+  return 4 * streamed <= 5 * ((int64_t)plan->q_len + 2 * (int64_t)plan->kv_len);
+}
+
 litevar_status litevar_windowed_attn_qkv8_workspace_bytes(const litevar_plan* plan, int32_t B, int32_t H,
                                                           size_t* out_bytes) {
   if (!plan || !out_bytes) return fail(LITEVAR_E_INVALID_ARG, "plan or out_bytes is NULL");
   if (B < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "B and H must be positive");
-  *out_bytes = (size_t)B * H * ((size_t)plan->q_len + 2 * (size_t)plan->kv_len) * 64 * 2;
+  *out_bytes = fused(plan) ? 0 : (size_t)B * H * ((size_t)plan->q_len + 2 * (size_t)plan->kv_len) * 64 * 2;
   return LITEVAR_OK;
 }
 
@@ -145,9 +157,32 @@ litevar_status litevar_windowed_attn_qkv8_fwd(const litevar_plan* plan, const in
                                               float sm_scale, const uint8_t* d_cfg_share, uint32_t flags,
                                               void* d_workspace, size_t workspace_bytes, void* stream) {
   if (!plan) return fail(LITEVAR_E_INVALID_ARG, "plan is NULL");
-  if (!d_q || !d_q_sz || !d_k || !d_k_sz || !d_v || !d_v_sz || !d_o || !d_workspace)
+  if (!d_q || !d_q_sz || !d_k || !d_k_sz || !d_v || !d_v_sz || !d_o)
     return fail(LITEVAR_E_INVALID_ARG, "a pointer is NULL");
   if (B < 1 || H < 1) return fail(LITEVAR_E_INVALID_ARG, "B and H must be positive (got %d, %d)", B, H);
+  const bool forced = (flags & LITEVAR_FLAG_QKV8_IN_KERNEL) != 0;
+  flags &= ~(uint32_t)LITEVAR_FLAG_QKV8_IN_KERNEL;
+  if (forced && plan->waves_per_group != 16)
+    return fail(LITEVAR_E_UNSUPPORTED, "in-kernel conversion needs a plan with 16 patches per group (this one has %d)",
+                plan->waves_per_group);
+  if (forced || fused(plan)) {
+    // codes and parameters go straight to the attention kernel: no dequantised copy
+    AttnArgs a;
+    if (litevar_status s = make_attn_args(plan, B, H, D, sm_scale, d_cfg_share, flags, a)) return s;
+    const uintptr_t align = (uintptr_t)d_q | (uintptr_t)d_k | (uintptr_t)d_v | (uintptr_t)d_o;
+    if (align & 15) return fail(LITEVAR_E_INVALID_ARG, "q, k, v, o must be 16-byte aligned");
+    if (((uintptr_t)d_q_sz | (uintptr_t)d_k_sz | (uintptr_t)d_v_sz) & 7)
+      return fail(LITEVAR_E_INVALID_ARG, "the (scale, zero point) arrays must be 8-byte aligned");
+    if ((int64_t)plan->kv_len * 64 >= ((int64_t)1 << 31))
+      return fail(LITEVAR_E_UNSUPPORTED, "one (batch, head) slab of k/v spans 2 GiB or more");
+    a.q = d_q; a.k = d_k; a.v = d_v; a.o = d_o;
+    a.qs[2] = 64; a.qs[1] = (int64_t)plan->q_len * 64; a.qs[0] = a.qs[1] * H;
+    a.ks[2] = 64; a.ks[1] = (int64_t)plan->kv_len * 64; a.ks[0] = a.ks[1] * H;
+    a.os[2] = 64; a.os[1] = (int64_t)plan->q_len * 64; a.os[0] = a.os[1] * H;
+    a.q_sz = (const float2*)d_q_sz; a.k_sz = (const float2*)d_k_sz; a.v_sz = (const float2*)d_v_sz;
+    return launch_attn_bf16_pair(plan, a, (hipStream_t)stream);
+  }
+  if (!d_workspace) return fail(LITEVAR_E_INVALID_ARG, "d_workspace is NULL");
   size_t need = 0;
   if (litevar_status s = litevar_windowed_attn_qkv8_workspace_bytes(plan, B, H, &need)) return s;
   if (workspace_bytes < need)

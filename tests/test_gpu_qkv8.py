@@ -122,3 +122,63 @@ def test_qkv8_constant_value_rows_pass_through(lv):
     o = lv.litevar_windowed_attn_qkv8_fwd(plan, *ops, 0.125).float().cpu()
     assert bool((o[:, :, 0] == 0.5).all())
     assert float((o - o[..., :1]).abs().max()) <= 2 ** -6
+
+
+@pytest.mark.parametrize("ppw", [1, 2])
+@pytest.mark.parametrize("case", ["full", "kv_step", "cfg", "kv_step_cfg"])
+def test_qkv8_in_kernel_conversion_equals_bf16_kernel_on_dequantised_copy(lv, ppw, case):
+    """Plans with 16 patches per group can take the 8-bit operands straight into the attention
+    kernel, which converts them on their way into LDS.  What it puts there is what
+    litevar_qkv8_dequantize writes, so the output must equal, bit for bit, that of the bf16
+    kernel on such a copy (same plan, both wave layouts), sharing included.  The library
+    takes that route by itself while the groups stream few rows twice (no workspace then);
+    the flag asks for it whatever the shape."""
+    scales = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+    q_scales = (9, 10) if case.startswith("kv_step") else None
+    B, H = 4, 3
+    q, k, v = workloads.make_qkv(scales, B, H, 64, "bf16", 11, 1.0, q_scales)
+    share = workloads.make_cfg_share(H, len(scales), 5).cuda() if case.endswith("cfg") else None
+    plan = lv.litevar_mask_build(scales, 3, None, 0, q_scales, waves_per_group=(16, 0, 0, -1, ppw))
+    assert plan.waves_per_group == 16
+    # (the documented rule: in the kernel while the groups stream at most 1.25 (q_len + 2 kv_len) rows)
+    by_itself = 4 * plan.n_union_keys <= 5 * (plan.q_len + 2 * plan.kv_len)
+    assert by_itself                             # holds for this short sequence, full or KV step
+    assert (lv.litevar_windowed_attn_qkv8_workspace_bytes(plan, B, H) == 0) == by_itself
+    ops = []
+    for t in (q, k, v):
+        ops += list(lv.litevar_qkv8_quantize(t.cuda()))
+    print(f"  in-kernel qkv8 vs bf16 on copy: case={case} patches per wave={ppw}", flush=True)
+    forced = lv.litevar_windowed_attn_qkv8_fwd(plan, *ops, 0.125, cfg_share=share, in_kernel=True)
+    default = lv.litevar_windowed_attn_qkv8_fwd(plan, *ops, 0.125, cfg_share=share)
+    copies = [lv.litevar_qkv8_dequantize(ops[i], ops[i + 1]) for i in (0, 2, 4)]
+    plain = lv.litevar_windowed_attn_fwd(plan, *copies, 0.125, cfg_share=share)
+    torch.cuda.synchronize()
+    assert torch.equal(forced, plain)
+    assert torch.equal(default, plain)
+
+
+def test_qkv8_in_kernel_flag_needs_16_patch_plan(lv):
+    scales = (1, 2, 3, 4)
+    q, k, v = workloads.make_qkv(scales, 2, 2, 64, "bf16", 3)
+    plan = lv.litevar_mask_build(scales, 1, waves_per_group=4)
+    ops = []
+    for t in (q, k, v):
+        ops += list(lv.litevar_qkv8_quantize(t.cuda()))
+    with pytest.raises(lv.LitevarError):
+        lv.litevar_windowed_attn_qkv8_fwd(plan, *ops, 0.125, in_kernel=True)
+
+
+def test_qkv8_long_sequences_take_the_workspace_route(lv):
+    w = workloads.get("var_d36_512")
+    plan = lv.litevar_mask_build(w.scales, w.radius, waves_per_group=16)
+    assert 4 * plan.n_union_keys > 5 * (plan.q_len + 2 * plan.kv_len)
+    assert lv.litevar_windowed_attn_qkv8_workspace_bytes(plan, 1, 6) == 6 * 3 * plan.kv_len * 64 * 2
+    # both routes agree bit for bit here too
+    q, k, v = workloads.make_qkv(w.scales, 1, 6, 64, "bf16", w.seed)
+    ops = []
+    for t in (q, k, v):
+        ops += list(lv.litevar_qkv8_quantize(t.cuda()))
+    a = lv.litevar_windowed_attn_qkv8_fwd(plan, *ops, 0.125)
+    b = lv.litevar_windowed_attn_qkv8_fwd(plan, *ops, 0.125, in_kernel=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
