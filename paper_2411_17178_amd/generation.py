@@ -9,7 +9,7 @@ output in every head and at every scale (paper Section 3: the unconditional work
 at once, the conditional ones store both rows).
 
 Argument marshalling only: the plans are built by litevar_mask_build and every step runs
-litevar_windowed_attn_fwd.  The calls allocate nothing and never synchronise, so a caller may
+litevar_windowed_attn_fwd (litevar_windowed_attn_qkv8_fwd for 8-bit caches).  The calls allocate nothing and never synchronise, so a caller may
 capture them in a HIP graph (torch.cuda.graph) and replay a whole layer with one launch.
 """
 import torch
@@ -47,6 +47,22 @@ class GenerationLayer:
         share = self._share_table(q_k) if share_all else None
         return binding.litevar_windowed_attn_fwd(self.plans[k], q_k, k_cache, v_cache, sm_scale,
                                                  out=out_k, cfg_share=share, stream=stream)
+
+    def qkv8_workspace_bytes(self, B, H):
+        """Bytes of the workspace that step_qkv8 needs at most (steps whose plan converts the
+        8-bit operands in the attention kernel need none)."""
+        return max(binding.litevar_windowed_attn_qkv8_workspace_bytes(p, B, H) for p in self.plans)
+
+    def step_qkv8(self, k, q8_k, q_sz_k, k8_cache, k_sz_cache, v8_cache, v_sz_cache, sm_scale, out_k=None,
+                  share_all=False, workspace=None, stream=None):
+        """The same step on 8-bit operands (paper Section 4): codes int8 `[B, H, *, 64]` with one
+        (scale, zero point) per token row, float32 `[B, H, *, 2]`, as litevar_qkv8_quantize
+        returns them; the caches hold the rows of scales 0..k.  Packed tensors.  `workspace`:
+        a uint8 CUDA tensor of qkv8_workspace_bytes() bytes (allocated per call when omitted)."""
+        share = self._share_table(q8_k) if share_all else None
+        return binding.litevar_windowed_attn_qkv8_fwd(self.plans[k], q8_k, q_sz_k, k8_cache, k_sz_cache,
+                                                      v8_cache, v_sz_cache, sm_scale, out=out_k,
+                                                      cfg_share=share, workspace=workspace, stream=stream)
 
     def prepare(self, q_steps, k_cache, v_cache, sm_scale, out_steps, share_all=False, stream=None):
         """Marshal all steps once; returns zero-argument callables, one per step, that

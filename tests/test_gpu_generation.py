@@ -105,3 +105,37 @@ def test_generation_layer_in_a_graph(lv):
         assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
         scratch = (out.float() * 2).sum().item()  # more eager work, a library reduction included
         assert np.isfinite(scratch)
+
+
+@pytest.mark.parametrize("share_all", [False, True])
+def test_generation_steps_on_an_8_bit_cache(lv, share_all):
+    """Section 4 on the generation path: K and V live in the cache as 8-bit codes with one
+    (scale, zero point) per token; rows of later scales carry NaN parameters, so a step that
+    read one would poison its output.  Quantisation is per token, so the steps concatenate to
+    the oracle's full-sequence result on quantised operands."""
+    from paper_2411_17178_amd.generation import GenerationLayer
+    radius, n_sink, B, H = 2, 0, 2, 3
+    q, k, v = workloads.make_qkv(VAR_SCALES, B, H, 64, "bf16", 78, 1.0, None)
+    gen = GenerationLayer(VAR_SCALES, radius, n_sink_scales=n_sink)
+    (k8, kz), (v8, vz) = lv.litevar_qkv8_quantize(k.cuda()), lv.litevar_qkv8_quantize(v.cuda())
+    k_cache, v_cache = torch.zeros_like(k8), torch.zeros_like(v8)
+    kz_cache, vz_cache = torch.full_like(kz, float("nan")), torch.full_like(vz, float("nan"))
+    work = torch.empty(gen.qkv8_workspace_bytes(B, H), dtype=torch.uint8, device="cuda")
+    out = torch.empty(q.shape, dtype=torch.bfloat16, device="cuda")
+    for s in range(gen.n_steps):
+        lo, hi = gen.rows(s)
+        for cache, src in ((k_cache, k8), (v_cache, v8), (kz_cache, kz), (vz_cache, vz)):
+            cache[:, :, lo:hi] = src[:, :, lo:hi]      # in-place append of scale s
+        q8, qz = lv.litevar_qkv8_quantize(q[:, :, lo:hi].contiguous().cuda())
+        print(f"  8-bit generation step {s}: queries [{lo}, {hi}) share_all={share_all}", flush=True)
+        out[:, :, lo:hi] = gen.step_qkv8(s, q8, qz, k_cache, kz_cache, v_cache, vz_cache, 0.125,
+                                         share_all=share_all, workspace=work)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all()), "a step read a key of a later scale"
+    arrs = [workloads.to_oracle_array(t) for t in (q, k, v)]
+    ref = oracle.attn_qkv8(VAR_SCALES, [radius] * len(VAR_SCALES), *arrs, 0.125, n_sink, None)
+    if share_all:
+        oracle.cfg_share(VAR_SCALES, ref, np.ones((H, len(VAR_SCALES)), dtype=np.uint8), None)
+    err = float(np.abs(out.float().cpu().numpy().astype(np.float64) - ref).max())
+    print(f"  8-bit cache generation: max-abs err {err:.3e}")
+    assert err <= 3e-2, err
