@@ -76,7 +76,7 @@ def kernel_name(plan, w, working, cus):
     if w.dtype == "bf16" and plan.waves_per_group == 16:
         # the library's rule: one patch per wave when the working workgroups fit the CUs
         pw = plan.patches_per_wave or (1 if working <= cus else 2)
-        return f"k_attn_bf16_pair<{pw}>"
+        return f"k_attn_bf16_pair<{pw}, false>"
     if w.dtype == "bf16":
         return (f"k_attn_bf16<{plan.waves_per_group}, {plan.chunk_keys}, 1, {plan.prefetch_chunks}, "
                 f"{plan.ring_chunks - plan.prefetch_chunks - 2}>")
