@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     litevar_qkv8_quantize, litevar_scale_offsets, litevar_windowed_attn_qkv8_fwd,
     litevar_windowed_attn_qkv8_workspace_bytes,
     litevar_window_calibrate, litevar_window_calibrate_static, litevar_window_table_export,
-    litevar_windowed_attn_fwd, load_library,
+    litevar_windowed_attn_fwd, load_library, use_library,
 )

@@ -3,6 +3,7 @@
 Function names match include/litevar.h.  Tensors are torch CUDA(HIP) tensors; the
 binding passes their data pointers and the current stream handle to the library.
 """
+import contextlib
 import ctypes as C
 import os
 
@@ -84,6 +85,21 @@ def load_library():
         getattr(lib, name).restype = C.c_int32
     _lib = lib
     return lib
+
+
+@contextlib.contextmanager
+def use_library(path):
+    """Inside the block the binding's calls go to another build of the library at `path` (the
+    bounds-checking one: paper_2411_17178_amd.build.LIB_DEBUG_BOUNDS).  Plans are plain data
+    plus a device blob and may cross between builds."""
+    global _lib, _LIB_PATH
+    saved = (_lib, _LIB_PATH)
+    _lib, _LIB_PATH = None, path
+    try:
+        load_library()
+        yield
+    finally:
+        _lib, _LIB_PATH = saved
 
 
 def _check(rc):

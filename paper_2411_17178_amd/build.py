@@ -30,19 +30,28 @@ def _run(cmd, verbose):
         print(out)
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles every source (one hipcc per file, in parallel) and links the shared library."""
+# The bounds-checking build of the same sources (-DLITEVAR_DEBUG_BOUNDS): every token, query row
+# and LDS offset that a kernel takes from the plan is compared with its limit before use.
+LIB_DEBUG_BOUNDS = os.path.join(HERE, "liblitevar_debug_bounds.so")
+
+
+def build(verbose: bool = False, debug_bounds: bool = False) -> str:
+    """Compiles every source (one hipcc per file, in parallel) and links the shared library;
+    debug_bounds: the bounds-checking variant, into a library of its own."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    obj_dir = OBJ_DIR + ("_debug_bounds" if debug_bounds else "")
+    lib = LIB_DEBUG_BOUNDS if debug_bounds else LIB
+    flags = FLAGS + (["-DLITEVAR_DEBUG_BOUNDS"] if debug_bounds else [])
+    os.makedirs(obj_dir, exist_ok=True)
+    objs = [os.path.join(obj_dir, s.replace(".hip", ".o")) for s in SOURCES]
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        jobs = [ex.submit(_run, [hipcc] + FLAGS + ["-c", "-o", o, os.path.join(CSRC, s)], verbose)
+        jobs = [ex.submit(_run, [hipcc] + flags + ["-c", "-o", o, os.path.join(CSRC, s)], verbose)
                 for s, o in zip(SOURCES, objs)]
         for j in jobs:
             j.result()
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, verbose)
-    return LIB
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs, verbose)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, debug_bounds="--debug-bounds" in sys.argv[1:]))

@@ -171,6 +171,8 @@ litevar_status litevar_plan_check(const litevar_plan* plan, void* stream) {
   if (h.error == kErrBuilder) return fail(LITEVAR_E_PLAN_CORRUPT, "device builder disagrees with the host sizing");
   if (h.error == kErrWaitGaveUp)
     return fail(LITEVAR_E_PLAN_CORRUPT, "an attention kernel's bounded wait gave up (its output is invalid)");
+  if (h.error == kErrBounds)
+    return fail(LITEVAR_E_PLAN_CORRUPT, "a kernel of the bounds-checking build found an index out of range");
   if (h.error) return fail(LITEVAR_E_PLAN_CORRUPT, "device blob carries the unknown error mark %d", h.error);
   if (h.blob_bytes != plan->blob_bytes || h.n_groups != plan->n_groups * plan->n_head_groups ||
       h.n_steps != plan->n_steps || h.n_union != plan->n_union_keys ||
@@ -258,6 +260,7 @@ litevar_status make_attn_args(const litevar_plan* plan, int32_t B, int32_t H, in
   a.n_groups = plan->n_groups;
   a.head_map = plan->n_heads > 0 ? (const int32_t*)(blob + plan->off[kSecHeadMap]) : nullptr;
   a.q_len = plan->q_len;
+  a.kv_len = plan->kv_len;
   a.hdr = (Header*)(plan->d_blob);
   a.spin_limit = plan->spin_limit > 0 ? plan->spin_limit : kDefaultSpinLimit;
   return LITEVAR_OK;

@@ -102,7 +102,7 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
 #pragma unroll
       for (int i = 0; i < C / 8; ++i) {
         const int slot = ring0 + 8 * i + row8;
-        const unsigned src = (unsigned)tok[i] * row_bytes + ((pos ^ ring_swizzle(slot)) << 4);
+        const unsigned src = (unsigned)checked_index(a.hdr, tok[i], a.kv_len) * row_bytes + ((pos ^ ring_swizzle(slot)) << 4);
         __builtin_amdgcn_global_load_lds((global_void*)(Kp + src),
                                          (lds_void*)(Kring + (ring0 + 8 * i) * kRingRowBytes), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((global_void*)(Vp + src),
@@ -163,7 +163,7 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
 
   // Q^T as the B operand: lane (n, g4) holds Q[query n][16*g4 .. 16*g4+15]
   const int dy = n >> 2, dx = n & 3;
-  const int qrow = ((wd.valid >> n) & 1u) ? wd.q_base + dy * wd.sk + dx : -1;
+  const int qrow = ((wd.valid >> n) & 1u) ? checked_index(a.hdr, wd.q_base + dy * wd.sk + dx, a.q_len) : -1;
   bf16x8 qb0, qb1;
   {
     uint4 z = {0, 0, 0, 0}, q0 = z, q1 = z;
@@ -210,7 +210,8 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
     const const_u64_ptr mk = (const_u64_ptr)(masks + (int64_t)s * 8);
 
     // S^T tiles: keys x queries
-    const unsigned ka0 = cur.x & 0xffffu, ka1 = cur.x >> 16;
+    constexpr int kRingBytes = R * kRingRowBytes;
+    const unsigned ka0 = checked_index(a.hdr, cur.x & 0xffffu, kRingBytes), ka1 = checked_index(a.hdr, cur.x >> 16, kRingBytes);
     const bf16x8 k00 = as_bf16x8(*(const uint4*)(Kring + ka0));
     const bf16x8 k01 = as_bf16x8(*(const uint4*)(Kring + (ka0 ^ 16u)));
     const bf16x8 k10 = as_bf16x8(*(const uint4*)(Kring + ka1));
@@ -225,7 +226,7 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu((
     S1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k11, qb1, S1, 0, 0, 0);
 
     // V^T operand: transposing LDS reads, 4 keys x 16 dims per 16-lane block
-    const unsigned v0 = cur.y & 0xffffu, v1 = cur.y >> 16;
+    const unsigned v0 = checked_index(a.hdr, cur.y & 0xffffu, kRingBytes), v1 = checked_index(a.hdr, cur.y >> 16, kRingBytes);
     s16x4 va[4][2];
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) {

@@ -58,6 +58,18 @@ __device__ inline bool plan_usable(const Header* hdr) {
   return magic_lo == (int32_t)(kMagic & 0xffffffffu) && magic_hi == (int32_t)(kMagic >> 32) && err != kErrBuilder;
 }
 
+// The bounds-checking build (-DLITEVAR_DEBUG_BOUNDS, a second library for tests and for chasing
+// a suspected plan/kernel mismatch): every token that addresses a K/V row, every query row
+// that addresses Q or O and every LDS offset taken from a step descriptor is compared with
+// its limit before use; a value out of range is replaced by 0 and the plan's header is
+// marked (litevar_plan_check then says so).  The normal build compiles the checks away.
+__device__ inline int checked_index([[maybe_unused]] Header* hdr, int value, [[maybe_unused]] int limit) {
+#ifdef LITEVAR_DEBUG_BOUNDS
+  if ((unsigned)value >= (unsigned)limit) { hdr->error = kErrBounds; return 0; }
+#endif
+  return value;
+}
+
 template <int N> __device__ inline void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   // gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt/lgkmcnt left at max

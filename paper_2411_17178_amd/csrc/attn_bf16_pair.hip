@@ -193,6 +193,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   const unsigned piece_off = (((unsigned)lane & 7u) ^ ring_swizzle((unsigned)row)) << 4;
   static_assert((kDmaKeys & 63) == 0, "the swizzle folds slot bits 0..5 only");
   auto issue_chunk = [&](int t, int tok) {             // chunk t -> ring slots (t % 5) * 64 ...
+    tok = checked_index(a.hdr, tok, a.kv_len);
     const int slot0 = (t % kRingChunks) * C + 8 * (wave & 7);
     const unsigned src = __umul24((unsigned)tok, row_bytes) + piece_off;   // (both below 2^24, checked by the API)
     if (PW == 2 || wave < 8)
@@ -209,6 +210,7 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
     ChunkRegs r;
     r.codes = u32x4{0u, 0u, 0u, 0u}; r.sz = make_float2(0.f, 0.f);
     if (q8_active) {
+      tok = checked_index(a.hdr, tok, a.kv_len);
       const unsigned char* base = q8_v ? Vp : Kp;
       const float2* sz = (q8_v ? a.v_sz : a.k_sz) + (int64_t)(b * a.H + h) * (a.ks[1] / a.ks[2]);
       r.codes = *(const u32x4*)(base + __umul24((unsigned)tok, row_bytes) + 16u * ((unsigned)lane & 3u));
@@ -431,9 +433,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) mk[e] = mkp[e];
     u32x4 k00, k01, k10, k11;
-    lds_read_k_issue(lds_addr(Kring + (cur.x & 0xffffu)), lds_addr(Kring + (cur.x >> 16)), k00, k01, k10, k11);
+    constexpr int kRingBytes = R * kRingRowBytes;       // (descriptor offsets are relative to either ring)
+    lds_read_k_issue(lds_addr(Kring + checked_index(a.hdr, cur.x & 0xffffu, kRingBytes)),
+                     lds_addr(Kring + checked_index(a.hdr, cur.x >> 16, kRingBytes)), k00, k01, k10, k11);
     // addresses of the V^T pieces: computed while the K pieces are on their way
-    unsigned v0 = lds_addr(Kring + (cur.y & 0xffffu)), v1 = lds_addr(Kring + (cur.y >> 16));
+    unsigned v0 = lds_addr(Kring + checked_index(a.hdr, cur.y & 0xffffu, kRingBytes)),
+             v1 = lds_addr(Kring + checked_index(a.hdr, cur.y >> 16, kRingBytes));
     unsigned va_addr[3][2];
 #pragma unroll
     for (int dt = 1; dt < 4; ++dt) { va_addr[dt - 1][0] = v0 ^ (32u * dt); va_addr[dt - 1][1] = v1 ^ (32u * dt); }
@@ -563,8 +568,9 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   auto store_patch = [&](const PatchState& ps, const PatchWords& w) {
     int n_again = n;                           // recomputed from scratch: the row is not worth a
     asm volatile("" : "+v"(n_again));          // register (or a spill slot) through the loop
-    const int qrow = query_row(w, n_again, false);
+    int qrow = query_row(w, n_again, false);
     if (qrow < 0) return;
+    qrow = checked_index(a.hdr, qrow, a.q_len);
     const float inv = 1.f / ps.Lacc[0];
     __bf16* op = (__bf16*)a.o + b * a.os[0] + h * a.os[1] + qrow * a.os[2] + 4 * g4;
 #pragma unroll

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a, int n_waves) {
 
   const int lane = threadIdx.x, n = lane % 16, g4 = lane / 16;
   const int dy = n / 4, dx = n % 4;
-  const int qrow = ((wd.valid >> n) & 1u) ? wd.q_base + dy * wd.sk + dx : -1;
+  const int qrow = ((wd.valid >> n) & 1u) ? checked_index(a.hdr, wd.q_base + dy * wd.sk + dx, a.q_len) : -1;
 
   const float* Q = (const float*)a.q + b * a.qs[0] + h * a.qs[1];
   const float* Kp = (const float*)a.k + b * a.ks[0] + h * a.ks[1];
@@ -35,8 +35,9 @@ __global__ __launch_bounds__(64) void k_attn_f32(AttnArgs a, int n_waves) {
   for (int s = 0; s < wd.n_steps; ++s) {
     const int64_t S = (int64_t)wd.step_begin + s;
     for (int i = 0; i < kStepKeys; ++i) {
-      const int tok = a.step_tok[S * kStepKeys + i];
+      int tok = a.step_tok[S * kStepKeys + i];
       if (tok < 0) continue;                      // padding key (uniform over the wave)
+      tok = checked_index(a.hdr, tok, a.kv_len);
       const float* kr = Kp + tok * a.ks[2] + 16 * g4;
       float dot = 0.f;
       for (int d = 0; d < 16; ++d) dot = fmaf(qv[d], kr[d], dot);

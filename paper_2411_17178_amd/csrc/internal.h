@@ -58,6 +58,7 @@ struct AttnArgs {
   int n_groups;                  // groups of one head group
   const int32_t* head_map;       // head -> head group, or nullptr when all heads share one
   int q_len;                     // query rows per (batch, head)
+  int kv_len;                    // key rows per (batch, head)
   Header* hdr;                   // the blob's header: checked by every kernel before the plan is used
   int spin_limit;                // polls after which a kernel's wait on an LDS flag gives up
   // 8-bit operands (Section 4): q, k, v then hold int8 codes (strides in codes) and these the

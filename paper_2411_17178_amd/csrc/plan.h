@@ -92,13 +92,15 @@ struct Header {      // first 256 bytes of the blob
   int64_t retained_pairs;
   int32_t error;       // kErrBuilder: set by the builder when a capacity would be exceeded (the
                        // work-list sections are then not written and no kernel uses the plan);
-                       // kErrWaitGaveUp: an attention kernel's bounded wait on an LDS flag ran out
+                       // kErrWaitGaveUp: an attention kernel's bounded wait on an LDS flag ran out;
+                       // kErrBounds: a kernel of the bounds-checking build found a token, a query
+                       // row or an LDS offset out of range (it used index 0 instead)
   int32_t pad0;
   uint64_t pad[24];
 };
 static_assert(sizeof(Header) == 256, "header size");
 
-enum HeaderError { kErrNone = 0, kErrBuilder = 1, kErrWaitGaveUp = 2 };
+enum HeaderError { kErrNone = 0, kErrBuilder = 1, kErrWaitGaveUp = 2, kErrBounds = 3 };
 constexpr int kDefaultSpinLimit = 1 << 22;   // polls of about 64 cycles each
 
 enum Section { kSecHeader = 0, kSecWin, kSecRad, kSecHeadMap, kSecGroups, kSecWaves, kSecPhaseEnd,
