@@ -274,6 +274,12 @@ __global__ void k_head_map(HeadMapArg m, int n_heads, int32_t* out) {
   if (i < kMaxHeads) out[i] = i < n_heads ? m.group[i] : 0;
 }
 
+// value of `v` in lane `lane`, for a lane index that is the same in every lane of the wave:
+// v_readlane_b32, where __shfl would go through the LDS crossbar
+__device__ inline int lane_value(int v, int lane) {
+  return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(lane));
+}
+
 // Placement of the kept keys of one pass (64 candidate keys, one per lane, in key order) in
 // the patch's steps: they get consecutive places; a pass is cut where a step fills up (32
 // keys) or where the next key's 2^logS-key block lies more than A blocks after the block of
@@ -292,7 +298,7 @@ struct WavePacker {
     uint64_t km = __ballot(kept);                     // kept keys of this pass not yet placed
     while (km) {
       const int fl = __builtin_ctzll(km);
-      const int fblk = __shfl(blk, fl);
+      const int fblk = lane_value(blk, fl);
       if (cnt > 0 && fblk - first_block > g.A) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
       if (cnt == 0) first_block = fblk;
       const bool mine = (km >> lane) & 1;
@@ -302,7 +308,7 @@ struct WavePacker {
       const bool take = ((fit >> lane) & 1) && rank < kStepKeys - cnt;
       const uint64_t tm = __ballot(take);
       sink.keys(step, cnt + rank, upos, tok, qmask, take);
-      last_upos = __shfl(upos, 63 - __builtin_clzll(tm));
+      last_upos = lane_value(upos, 63 - __builtin_clzll(tm));
       cnt += __builtin_popcountll(tm);
       km &= ~tm;
       if (cnt == kStepKeys) { sink.close(step, cnt, last_upos); ++step; cnt = 0; }
@@ -333,8 +339,8 @@ __device__ int wave_walk_patch(const Geom& g, const TableWin& win, const TableRa
       if (lane < p.nx) mine = band_interval(b, nk, p.y0 + lane);
       Interval iv[kPatchQueries];
 #pragma unroll
-      for (int n = 0; n < kPatchQueries; ++n) { iv[n].lo = __shfl(mine.lo, n); iv[n].hi = __shfl(mine.hi, n); }
-      const int clo = iv[0].lo, chi = __shfl(mine.hi, p.nx - 1);
+      for (int n = 0; n < kPatchQueries; ++n) { iv[n].lo = lane_value(mine.lo, n); iv[n].hi = lane_value(mine.hi, n); }
+      const int clo = iv[0].lo, chi = lane_value(mine.hi, p.nx - 1);
       for (int c0 = clo; c0 <= chi; c0 += 64) {
         const int c = c0 + lane;
         unsigned qmask = 0;
@@ -377,16 +383,16 @@ __device__ int wave_walk_patch(const Geom& g, const TableWin& win, const TableRa
     Interval rw[kPatch], cw[kPatch];
 #pragma unroll
     for (int d = 0; d < kPatch; ++d) {
-      const Interval r = {__shfl(mine_iv.lo, l0 + d), __shfl(mine_iv.hi, l0 + d)};
-      const Interval cc = {__shfl(mine_iv.lo, l0 + 4 + d), __shfl(mine_iv.hi, l0 + 4 + d)};
+      const Interval r = {lane_value(mine_iv.lo, l0 + d), lane_value(mine_iv.hi, l0 + d)};
+      const Interval cc = {lane_value(mine_iv.lo, l0 + 4 + d), lane_value(mine_iv.hi, l0 + 4 + d)};
       rw[d] = d < p.ny ? r : none;
       cw[d] = d < p.nx ? cc : none;
     }
     Box gb, pb;
-    gb.ylo = __shfl(mine_iv.lo, l0 + 8); gb.yhi = __shfl(mine_iv.hi, l0 + 9);
-    gb.xlo = __shfl(mine_iv.lo, l0 + 10); gb.xhi = __shfl(mine_iv.hi, l0 + 11);
-    pb.ylo = rw[0].lo; pb.yhi = __shfl(mine_iv.hi, l0 + p.ny - 1);
-    pb.xlo = cw[0].lo; pb.xhi = __shfl(mine_iv.hi, l0 + 4 + p.nx - 1);
+    gb.ylo = lane_value(mine_iv.lo, l0 + 8); gb.yhi = lane_value(mine_iv.hi, l0 + 9);
+    gb.xlo = lane_value(mine_iv.lo, l0 + 10); gb.xhi = lane_value(mine_iv.hi, l0 + 11);
+    pb.ylo = rw[0].lo; pb.yhi = lane_value(mine_iv.hi, l0 + p.ny - 1);
+    pb.xlo = cw[0].lo; pb.xhi = lane_value(mine_iv.hi, l0 + 4 + p.nx - 1);
     const int gw = gb.xhi - gb.xlo + 1;
     const int sj = g.s[j], offj = g.off[j];
     // lanes of a pass in key order: RP rows of the patch's box (W columns each) when the box
@@ -486,7 +492,7 @@ __global__ __launch_bounds__(64) void k_count(Geom g, BlobPtrs p) {
       // whole key scales from scale 0 on, then the first rows of the next box if it starts
       // at the scale's origin
       for (int j = 0; j <= k; ++j) {
-        const Box b = {__shfl(mine.ylo, j), __shfl(mine.yhi, j), __shfl(mine.xlo, j), __shfl(mine.xhi, j)};
+        const Box b = {lane_value(mine.ylo, j), lane_value(mine.yhi, j), lane_value(mine.xlo, j), lane_value(mine.xhi, j)};
         const int gw = b.xhi - b.xlo + 1, rows = b.yhi - b.ylo + 1;
         if (b.ylo != 0 || b.xlo != 0 || g.off[j] != ident) break;
         if (gw != g.s[j]) { ident += gw; break; }
