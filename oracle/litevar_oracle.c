@@ -458,6 +458,68 @@ int lvo_calibrate(int32_t K, const int32_t* scales, const double* p, int32_t N, 
   return LVO_OK;
 }
 
+/* The same procedure with Section 2, step (2) read literally (LVO_BAND): the map of query
+ * scale k is cut into parts -- the first three key scales together, then one part per key
+ * scale -- and the window of a part is the band of radius r around the part's diagonal; for
+ * each part the band grows from radius zero until it holds the fraction r0 of the part's
+ * values (n - 1 at the latest, n = the part's columns).  radius[h][k][j] receives the radius of
+ * the part that key scale j belongs to (the same value for every key scale of the merged
+ * part; -1 for j > k), i.e. a table that the band predicate reads back.  mass[h][k][j][r],
+ * optional, r < mcols: the in-band sum at radius r (the part's sum from r = n - 1 on). */
+int lvo_calibrate_band(int32_t K, const int32_t* scales, const double* p, int32_t N, int32_t H,
+                       double r0, int32_t* radius, double* mass, int32_t mcols) {
+  if (K < 1 || !scales || !p || !radius || N < 1 || H < 1) return LVO_BAD_ARG;
+  const int64_t L = lvo_seq_len(K, scales);
+  int32_t* rad = (int32_t*)malloc((size_t)K * K * sizeof(int32_t));
+  if (!rad) return LVO_NO_MEM;
+  for (int32_t h = 0; h < H; ++h)
+    for (int32_t k = 0; k < K; ++k) {
+      for (int32_t j = 0; j < K; ++j) {
+        radius[((int64_t)h * K + k) * K + j] = -1;
+        if (mass) for (int32_t r = 0; r < mcols; ++r) mass[(((int64_t)h * K + k) * K + j) * mcols + r] = 0.0;
+      }
+      const int64_t oq = lvo_scale_offset(K, scales, k);
+      const int32_t sk = scales[k];
+      int32_t first = 0;
+      while (first <= k) {
+        const int32_t last = first < 3 ? (k < 2 ? k : 2) : first;   /* key scales of this part */
+        int64_t n = 0;
+        for (int32_t j = first; j <= last; ++j) n += (int64_t)scales[j] * scales[j];
+        if (mass && n > mcols) { free(rad); return LVO_BAD_ARG; }
+        int32_t found = -1;
+        for (int64_t r = 0; r < n; ++r) {              /* the band grows from zero */
+          for (int32_t i = 0; i < K * K; ++i) rad[i] = (int32_t)r;
+          double in = 0.0, all = 0.0;
+          for (int32_t s = 0; s < N; ++s)
+            for (int32_t qy = 0; qy < sk; ++qy)
+              for (int32_t qx = 0; qx < sk; ++qx)
+                for (int32_t j = first; j <= last; ++j)
+                  for (int32_t ky = 0; ky < scales[j]; ++ky)
+                    for (int32_t kx = 0; kx < scales[j]; ++kx) {
+                      const int64_t q = oq + (int64_t)qy * sk + qx;
+                      const int64_t t = lvo_scale_offset(K, scales, j) + (int64_t)ky * scales[j] + kx;
+                      const double v = p[(((int64_t)s * H + h) * L + q) * L + t];
+                      all += v;
+                      if (allowed_coords(K, scales, rad, 0, LVO_BAND, k, qy, qx, j, ky, kx)) in += v;
+                    }
+          if (mass)
+            for (int32_t j = first; j <= last; ++j) {
+              double* m = mass + (((int64_t)h * K + k) * K + j) * mcols;
+              m[r] = in;
+              if (r == n - 1) for (int64_t rr = n; rr < mcols; ++rr) m[rr] = in;
+            }
+          if (found < 0 && (all == 0.0 || in / all >= r0)) found = (int32_t)r;
+          if (found >= 0 && !mass) break;
+        }
+        for (int32_t j = first; j <= last; ++j)
+          radius[((int64_t)h * K + k) * K + j] = found < 0 ? (int32_t)(n - 1) : found;
+        first = last + 1;
+      }
+    }
+  free(rad);
+  return LVO_OK;
+}
+
 /* ---- QKV8: attention on 8-bit Q, K, V (Section 4, "Quantization Scheme": min-max
  * quantisation with dynamic parameters computed online from the data's maximum and
  * minimum) ----

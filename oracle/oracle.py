@@ -230,6 +230,33 @@ def calibrate(scales, p, r0, with_mass=False):
     return (radius, mass) if with_mass else radius
 
 
+def band_part_columns(scales):
+    """Largest number of columns of a part of the band reading (first three key scales merged)."""
+    s = [int(x) * int(x) for x in scales]
+    return max([sum(s[:3])] + s[3:])
+
+
+def calibrate_band(scales, p, r0, with_mass=False):
+    """Band radii (Section 2 step (2) read literally: parts with the first three key scales
+    merged, a band around each part's diagonal) from a post-softmax map p[N][H][L][L]: the
+    smallest radius per (head, query scale, part) whose band holds the fraction r0 of the
+    part's values, written to every key scale of the part.  Returns radius[H][K][K] (and
+    mass[H][K][K][band_part_columns(scales)] when asked)."""
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    N, H, L, L2 = p.shape
+    K = len(scales)
+    assert L == L2 == seq_len(scales)
+    mcols = band_part_columns(scales)
+    radius = np.zeros((H, K, K), dtype=np.int32)
+    mass = np.zeros((H, K, K, mcols), dtype=np.float64) if with_mass else None
+    sc = _i32(scales)
+    rc = _L().lvo_calibrate_band(C.c_int32(K), _p(sc), _p(p), C.c_int32(N), C.c_int32(H),
+                                 C.c_double(float(r0)), _p(radius), _p(mass) if with_mass else None,
+                                 C.c_int32(mcols))
+    assert rc == 0, rc
+    return (radius, mass) if with_mass else radius
+
+
 def quantize_rows(x, bits=8):
     """Section 4 min-max quantiser, one (scale, zero) per row of the last axis.
     Returns (codes int32 like x, scale float64 [rows], zero float64 [rows])."""

@@ -13,6 +13,7 @@ import pytest
 
 import oracle
 import oracle.oracle as front
+import test_oracle_calibrate_band_pins as band_cal_pins
 import test_oracle_calibrate_pins as cal_pins
 import test_oracle_pins as pins
 import test_oracle_qkv8_pins as q8_pins
@@ -95,6 +96,14 @@ MISTAKES = [
     ("calibration window one key too wide",
      [("for (int32_t i = 0; i < K * K; ++i) rad[i] = r;", "for (int32_t i = 0; i < K * K; ++i) rad[i] = r + 1;")],
      lambda: cal_pins.test_mass_at_a_known_distance_from_the_centre(1)),
+    ("band calibration sums a part over its last key scale only",
+     [("                for (int32_t j = first; j <= last; ++j)\n                  for (int32_t ky = 0; ky < scales[j]; ++ky)",
+       "                for (int32_t j = last; j <= last; ++j)\n                  for (int32_t ky = 0; ky < scales[j]; ++ky)")],
+     band_cal_pins.test_hand_placed_mass_in_the_merged_part),
+    ("band calibration stops one radius late",
+     [("          if (found < 0 && (all == 0.0 || in / all >= r0)) found = (int32_t)r;",
+       "          if (found < 0 && (all == 0.0 || in / all >= r0)) found = (int32_t)r + 1;")],
+     band_cal_pins.test_hand_placed_mass_in_the_last_part),
 ]
 
 
