@@ -311,6 +311,29 @@ litevar_status litevar_window_calibrate(const int32_t* scales, int32_t n_scales,
                                         int32_t* d_radius, double* d_mass, void* stream);
 
 /*
+ * The same calibration for the band mask mode (Section 2, step (2) read literally:
+ * LITEVAR_MASK_BAND_1D): the map of query scale k is cut into parts -- the first three key
+ * scales together, then one part per key scale -- and in every part the band around the
+ * part's diagonal grows from radius zero until it holds the fraction r0 of the part's values
+ * (n - 1 at the latest, n = the part's columns).
+ *   d_radius     DEVICE int32 [H][K][K]: the radius of the part that key scale j belongs to,
+ *                the same value for the key scales of the merged part, -1 for j > k: the layout
+ *                of litevar_mask_desc.radius_per_head for a band plan.
+ *   d_mass       DEVICE double [H][K][K][C] or NULL, C = the largest number of columns of a part
+ *                (max of s_1^2 + s_2^2 + s_3^2 and the later s_j^2): in-band sums by radius, the
+ *                part's sum from radius n - 1 on.
+ *   d_workspace  DEVICE, 8-byte aligned, litevar_window_calibrate_band_workspace_bytes() bytes.
+ * Scale sides up to 64, parts of at most 4096 columns.  Other arguments and conventions as
+ * litevar_window_calibrate.
+ */
+litevar_status litevar_window_calibrate_band_workspace_bytes(const int32_t* scales, int32_t n_scales,
+                                                             int32_t H, size_t* out_bytes);
+litevar_status litevar_window_calibrate_band(const int32_t* scales, int32_t n_scales,
+                                             const float* d_attn, int32_t N, int32_t H, float r0,
+                                             void* d_workspace, size_t workspace_bytes,
+                                             int32_t* d_radius, double* d_mass, void* stream);
+
+/*
  * QKV8 (Section 4, "Quantization Scheme": min-max quantisation of Q, K and V to 8-bit
  * integers with dynamic parameters computed online from the data's maximum and minimum).
  * One (scale s, zero point z) per token row of D = 64 values:

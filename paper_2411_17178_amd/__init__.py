@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     litevar_peak_mfma_bf16, litevar_peak_read, litevar_plan_check, litevar_qkv8_dequantize,
     litevar_qkv8_quantize, litevar_scale_offsets, litevar_windowed_attn_qkv8_fwd,
     litevar_windowed_attn_qkv8_workspace_bytes,
-    litevar_window_calibrate, litevar_window_calibrate_static, litevar_window_table_export,
+    litevar_window_calibrate, litevar_window_calibrate_band, litevar_window_calibrate_static, litevar_window_table_export,
     litevar_windowed_attn_fwd, load_library, use_library,
 )

@@ -2,7 +2,7 @@
 post-softmax attention maps of N reference samples -> one radius per (head, query scale, key
 scale).  Run as
 
-    python -m paper_2411_17178_amd.bench_calibrate [--samples 8] [--heads 30] [--r0 0.95]
+    python -m paper_2411_17178_amd.bench_calibrate [--samples 8] [--heads 30] [--r0 0.95] [--band]
 
 Prints one JSON line.  The maps are seeded synthetic rows (a noisy bump around each query's
 position, block-causal across scales, rows summing to one), resident in HBM; the algorithmic
@@ -23,6 +23,8 @@ def main():
     ap.add_argument("--r0", type=float, default=0.95)
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--band", action="store_true",
+                    help="the band mask mode's parts (Section 2, step (2) read literally)")
     args = ap.parse_args()
 
     import torch
@@ -46,13 +48,14 @@ def main():
     for n in range(args.samples):
         w = base[0] * torch.exp(0.3 * torch.randn(base[0].shape, generator=g, device=dev))
         maps[n] = w / w.sum(dim=-1, keepdim=True)
+    calibrate = lv.litevar_window_calibrate_band if args.band else lv.litevar_window_calibrate
     for _ in range(args.warmup):
-        radius = lv.litevar_window_calibrate(scales, maps, args.r0)
+        radius = calibrate(scales, maps, args.r0)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.iters):
-        radius = lv.litevar_window_calibrate(scales, maps, args.r0)
+        radius = calibrate(scales, maps, args.r0)
     e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / args.iters
@@ -63,7 +66,8 @@ def main():
     nbytes = 4 * causal * args.samples * args.heads
     r = radius.cpu()
     print(json.dumps({
-        "metric": "window calibration, microseconds per call", "value": round(us, 2), "unit": "us",
+        "metric": ("band" if args.band else "window") + " calibration, microseconds per call",
+        "value": round(us, 2), "unit": "us",
         "higher_is_better": False, "dtype": "f64 sums over f32 maps",
         "data": "synthetic (seeded noisy bumps, block-causal rows summing to one)",
         "config": {"workload": "VAR 10-scale attention maps", "scales": list(scales),

@@ -79,7 +79,8 @@ def load_library():
                  "litevar_window_table_export", "litevar_mask_export_dense",
                  "litevar_mask_export_csr", "litevar_windowed_attn_fwd",
                  "litevar_window_calibrate_workspace_bytes", "litevar_window_calibrate",
-                 "litevar_window_calibrate_static", "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16", "litevar_qkv8_quantize",
+                 "litevar_window_calibrate_static", "litevar_window_calibrate_band_workspace_bytes",
+                 "litevar_window_calibrate_band", "litevar_peak_copy", "litevar_peak_read", "litevar_peak_mfma_bf16", "litevar_qkv8_quantize",
                  "litevar_qkv8_dequantize", "litevar_windowed_attn_qkv8_workspace_bytes",
                  "litevar_windowed_attn_qkv8_fwd"):
         getattr(lib, name).restype = C.c_int32
@@ -315,6 +316,29 @@ def litevar_window_calibrate(scales, attn_map, r0, with_mass=False, stream=None)
         C.c_float(r0), C.c_void_p(work.data_ptr()), C.c_size_t(work.numel() * 8),
         C.c_void_p(radius.data_ptr()), C.c_void_p(mass.data_ptr()) if with_mass else None,
         _stream_handle(stream)))
+    return (radius, mass) if with_mass else radius
+
+
+def litevar_window_calibrate_band(scales, attn_map, r0, with_mass=False, stream=None):
+    """Band radii (the band mask mode's parts) from post-softmax maps [N][H][L][L] (float32 CUDA
+    tensor): int32 [H][K][K] (and the in-band sums, float64 [H][K][K][C], when asked)."""
+    lib = load_library()
+    assert attn_map.is_cuda and attn_map.dtype == torch.float32 and attn_map.is_contiguous()
+    N, H, L, L2 = attn_map.shape
+    K = len(scales)
+    sq = [int(s) * int(s) for s in scales]
+    assert L == L2 == sum(sq)
+    sc = (C.c_int32 * K)(*[int(s) for s in scales])
+    n = C.c_size_t(0)
+    _check(lib.litevar_window_calibrate_band_workspace_bytes(sc, C.c_int32(K), C.c_int32(H), C.byref(n)))
+    work = torch.empty(n.value, dtype=torch.uint8, device=attn_map.device)
+    radius = torch.empty((H, K, K), dtype=torch.int32, device=attn_map.device)
+    cols = max([sum(sq[:3])] + sq[3:])
+    mass = torch.empty((H, K, K, cols), dtype=torch.float64, device=attn_map.device) if with_mass else None
+    _check(lib.litevar_window_calibrate_band(
+        sc, C.c_int32(K), C.c_void_p(attn_map.data_ptr()), C.c_int32(N), C.c_int32(H), C.c_float(r0),
+        C.c_void_p(work.data_ptr()), C.c_size_t(n.value), C.c_void_p(radius.data_ptr()),
+        C.c_void_p(mass.data_ptr()) if with_mass else None, _stream_handle(stream)))
     return (radius, mass) if with_mass else radius
 
 

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblitevar.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "plan_build.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_pair.hip",
-           "calibrate.hip", "peaks.hip", "qkv8.hip"]
+           "calibrate.hip", "calibrate_band.hip", "peaks.hip", "qkv8.hip"]
 # -fno-honor-nans: the kernels never produce NaN from finite inputs (masked scores are -inf
 # and the softmax reference starts at a finite floor), and it spares the canonicalising
 # v_max that IEEE maxNum semantics would need in front of every fmaxf.

@@ -92,3 +92,71 @@ def test_calibrate_repeats_bit_for_bit_and_feeds_the_plan(lv):
     mask, _ = lv.litevar_mask_export_dense(plan)
     want = oracle.mask_dense(VAR_SCALES, per_key_scale, 3)
     assert np.array_equal(mask.cpu().numpy().astype(bool), want.astype(bool))
+
+
+# ---- the band mask mode's parts (Section 2, step (2) read literally) ----------------------
+
+def _compare_band(lv, scales, p32, r0):
+    print(f"  band calibrate: scales={scales} map{tuple(p32.shape)} r0={r0}", flush=True)
+    rad, mass = lv.litevar_window_calibrate_band(scales, p32.cuda(), r0, with_mass=True)
+    torch.cuda.synchronize()
+    rad, mass = rad.cpu().numpy(), mass.cpu().numpy()
+    r0_used = float(np.float32(r0))
+    want, wmass = oracle.calibrate_band(scales, p32.numpy().astype(np.float64), r0_used, with_mass=True)
+    assert mass.shape == wmass.shape
+    assert np.allclose(mass, wmass, rtol=1e-9, atol=1e-13), float(np.abs(mass / np.maximum(wmass, 1e-300) - 1).max())
+    K = len(scales)
+    differ = 0
+    for h in range(p32.shape[1]):
+        for k in range(K):
+            for j in range(K):
+                g, w = rad[h, k, j], want[h, k, j]
+                if g == w:
+                    continue
+                # a tie: the oracle's own ratio already sits on the threshold at the smaller of
+                # the two radii (at threshold 1 the far values lie below the rounding of the
+                # part's sum, and the plateau may be several radii wide)
+                differ += 1
+                total = wmass[h, k, j, -1]
+                assert j <= k and total > 0
+                assert abs(wmass[h, k, j, min(g, w)] / total - r0_used) < 1e-9, (h, k, j, g, w)
+    return rad, differ
+
+
+@pytest.mark.parametrize("r0", [0.6, 0.95, 1.0])
+def test_band_calibrate_var_scales(lv, r0):
+    p = workloads.make_attn_map(VAR_SCALES, 2, 3, 32)
+    rad, differ = _compare_band(lv, VAR_SCALES, p, r0)
+    assert differ == 0 or r0 == 1.0
+    assert (rad[:, np.triu_indices(10, 1)[0], np.triu_indices(10, 1)[1]] == -1).all()
+    assert (rad[:, 9, 0] == rad[:, 9, 1]).all() and (rad[:, 9, 1] == rad[:, 9, 2]).all()   # one merged part
+
+
+@pytest.mark.parametrize("scales", [(1,), (3,), (7, 2, 9, 4), (2, 17), (5, 9, 12), (24,), (1, 1, 1, 1, 6)])
+def test_band_calibrate_edge_scale_lists(lv, scales):
+    p = workloads.make_attn_map(scales, 1, 2, 8, sigma=(0.08, 0.3))
+    _compare_band(lv, scales, p, 0.9)
+
+
+def test_band_calibrate_feeds_a_band_plan(lv):
+    """The table goes straight into a band plan with one table per head, whose mask keeps at
+    least the fraction R_0 of every part's values."""
+    scales = (1, 2, 3, 4, 5, 6)
+    p = workloads.make_attn_map(scales, 2, 2, 9)
+    rad = lv.litevar_window_calibrate_band(scales, p.cuda(), 0.9)
+    torch.cuda.synchronize()
+    tabs = rad.cpu().numpy()
+    plan = lv.litevar_mask_build(scales, 0, np.maximum(tabs, 0).tolist(), mask_mode=1)
+    lv.litevar_plan_check(plan)
+    off = oracle.scale_offsets(scales)
+    for h in range(2):
+        mask, _ = lv.litevar_mask_export_dense(plan, head=h)
+        m = mask.cpu().numpy().astype(bool)
+        assert (m == oracle.mask_dense(scales, np.maximum(tabs[h], 0), 0, mode=1).astype(bool)).all()
+        summed = p[:, h].sum(dim=0).numpy().astype(np.float64)
+        for k in range(len(scales)):
+            parts = [(0, min(2, k))] + [(j, j) for j in range(3, k + 1)]
+            for first, last in parts:
+                blk = summed[off[k]:off[k + 1], off[first]:off[last + 1]]
+                kept = blk[m[off[k]:off[k + 1], off[first]:off[last + 1]]].sum()
+                assert kept / blk.sum() >= float(np.float32(0.9)) - 1e-9
