@@ -44,36 +44,45 @@ struct BandPartInfo {
   int n, nk, tok0;          // columns, query rows, first column's token
   int row_blocks, rows_per_block;
   int64_t base;             // first double of the part's partial sums inside a head's region
+  int block0;               // first workgroup of the part in the mass kernel's launch
 };
-__host__ __device__ inline BandPartInfo band_part_info(const BandArgs& a, int idx) {
+__host__ __device__ inline int blocks_of(int n, int row_blocks) {
+  return ((2 * n - 1 + kBandThreads - 1) / kBandThreads) * row_blocks;
+}
+// (by_block: `idx` is a workgroup of the mass kernel and the part that owns it is wanted)
+__host__ __device__ inline BandPartInfo band_part_info(const BandArgs& a, int idx, bool by_block = false) {
   BandPartInfo r = {};
   int64_t base = 0;
-  int at = 0;
+  int at = 0, block0 = 0;
   for (int k = 0; k < a.K; ++k) {
     const int nk = a.s[k] * a.s[k], rb = row_blocks_of(nk);
     for (int pt = 0; pt < parts_of(k); ++pt, ++at) {
       const int first = pt == 0 ? 0 : pt + kMergedScales - 1;
       const int last = pt == 0 ? (k < kMergedScales - 1 ? k : kMergedScales - 1) : first;
       const int n = a.off[last + 1] - a.off[first];
-      if (at == idx) {
+      const int nb = blocks_of(n, rb);
+      if (by_block ? idx < block0 + nb : at == idx) {
         r.k = k; r.first = first; r.last = last; r.n = n; r.nk = nk; r.tok0 = a.off[first];
-        r.row_blocks = rb; r.rows_per_block = (nk + rb - 1) / rb; r.base = base;
+        r.row_blocks = rb; r.rows_per_block = (nk + rb - 1) / rb; r.base = base; r.block0 = block0;
         return r;
       }
       base += (int64_t)rb * (2 * n - 1);
+      block0 += nb;
     }
   }
   r.k = -1;
   return r;
 }
 
-// grid (blocks of the largest part, parts, heads): block x of a part is (row block, tile of 256 offsets)
+// grid (workgroups of all parts, heads): the launch holds exactly the workgroups that have
+// work (starting an empty one costs about as much as a short one); a part's workgroups are
+// (row block, tile of 256 offsets)
 __global__ __launch_bounds__(kBandThreads) void k_band_mass(BandArgs a) {
-  const BandPartInfo pi = band_part_info(a, blockIdx.y);
-  const int h = blockIdx.z;
+  const BandPartInfo pi = band_part_info(a, blockIdx.x, true);
+  const int h = blockIdx.y;
   const int n_off = 2 * pi.n - 1, tiles = (n_off + kBandThreads - 1) / kBandThreads;
-  if ((int)blockIdx.x >= tiles * pi.row_blocks) return;         // (uniform)
-  const int tile = blockIdx.x % tiles, rb = blockIdx.x / tiles;
+  const int local = (int)blockIdx.x - pi.block0;
+  const int tile = local % tiles, rb = local / tiles;
   const int u = tile * kBandThreads + threadIdx.x;               // offset index: o = u - (n - 1)
   if (u >= n_off) return;
   const int o = u - (pi.n - 1);
@@ -81,7 +90,8 @@ __global__ __launch_bounds__(kBandThreads) void k_band_mass(BandArgs a) {
   const int64_t q0 = a.off[pi.k];
   double acc = 0.0;
   for (int i = i0; i < i1; ++i) {
-    const int c = (int)(((2 * (int64_t)i + 1) * pi.n) / (2 * (int64_t)pi.nk)) + o;   // the diagonal at row i, plus o
+    // the diagonal at row i, plus o (sides are at most 64: (2 i + 1) n stays below 2^26)
+    const int c = (int)(((2u * (unsigned)i + 1u) * (unsigned)pi.n) / (2u * (unsigned)pi.nk)) + o;
     if (c < 0 || c >= pi.n) continue;
     const float* row = a.p + ((int64_t)h * a.L + q0 + i) * a.L + pi.tok0 + c;
     for (int s = 0; s < a.N; ++s) acc += (double)row[(int64_t)s * a.H * a.L * a.L];
@@ -134,7 +144,7 @@ __global__ __launch_bounds__(kBandThreads) void k_band_pick(BandArgs a) {
   }
 }
 
-litevar_status band_geom(const int32_t* scales, int32_t n_scales, int32_t H, BandArgs& a, int& max_blocks) {
+litevar_status band_geom(const int32_t* scales, int32_t n_scales, int32_t H, BandArgs& a, int& n_blocks) {
   if (!scales) return fail(LITEVAR_E_INVALID_ARG, "scales is NULL");
   if (n_scales < 1 || n_scales > kMaxScales)
     return fail(LITEVAR_E_INVALID_ARG, "n_scales must be in 1..%d (got %d)", kMaxScales, n_scales);
@@ -153,14 +163,13 @@ litevar_status band_geom(const int32_t* scales, int32_t n_scales, int32_t H, Ban
   a.n_parts = 0;
   for (int k = 0; k < n_scales; ++k) a.n_parts += parts_of(k);
   if (a.n_parts > 65535) return fail(LITEVAR_E_UNSUPPORTED, "grid too large");
-  a.mcols = 0; max_blocks = 1;
+  a.mcols = 0; n_blocks = 0;
   int64_t stride = 0;
   for (int idx = 0; idx < a.n_parts; ++idx) {
     const BandPartInfo pi = band_part_info(a, idx);
     if (pi.n > kMaxPartCols) return fail(LITEVAR_E_UNSUPPORTED, "a part of %d columns (at most %d)", pi.n, kMaxPartCols);
     a.mcols = pi.n > a.mcols ? pi.n : a.mcols;
-    const int blocks = ((2 * pi.n - 1 + kBandThreads - 1) / kBandThreads) * pi.row_blocks;
-    max_blocks = blocks > max_blocks ? blocks : max_blocks;
+    n_blocks = pi.block0 + blocks_of(pi.n, pi.row_blocks);     // (running total: all parts' workgroups)
     stride = pi.base + (int64_t)pi.row_blocks * (2 * pi.n - 1);
   }
   a.head_stride = stride;
@@ -179,8 +188,8 @@ litevar_status litevar_window_calibrate_band_workspace_bytes(const int32_t* scal
                                                              size_t* out_bytes) {
   if (!out_bytes) return fail(LITEVAR_E_INVALID_ARG, "out_bytes is NULL");
   BandArgs a;
-  int max_blocks = 0;
-  if (litevar_status s = band_geom(scales, n_scales, H, a, max_blocks)) return s;
+  int n_blocks = 0;
+  if (litevar_status s = band_geom(scales, n_scales, H, a, n_blocks)) return s;
   *out_bytes = (size_t)a.head_stride * (size_t)H * sizeof(double);
   return LITEVAR_OK;
 }
@@ -189,8 +198,8 @@ litevar_status litevar_window_calibrate_band(const int32_t* scales, int32_t n_sc
                                              int32_t H, float r0, void* d_workspace, size_t workspace_bytes,
                                              int32_t* d_radius, double* d_mass, void* stream) {
   BandArgs a;
-  int max_blocks = 0;
-  if (litevar_status s = band_geom(scales, n_scales, H, a, max_blocks)) return s;
+  int n_blocks = 0;
+  if (litevar_status s = band_geom(scales, n_scales, H, a, n_blocks)) return s;
   if (N < 1) return fail(LITEVAR_E_INVALID_ARG, "N must be positive");
   if (!(r0 > 0.f) || r0 > 1.f) return fail(LITEVAR_E_INVALID_ARG, "r0 must be in (0, 1] (got %g)", r0);
   if (!d_attn || !d_radius || !d_workspace) return fail(LITEVAR_E_INVALID_ARG, "d_attn, d_radius or d_workspace is NULL");
@@ -200,7 +209,7 @@ litevar_status litevar_window_calibrate_band(const int32_t* scales, int32_t n_sc
   if (workspace_bytes < need) return fail(LITEVAR_E_INVALID_ARG, "workspace of %zu bytes, %zu needed", workspace_bytes, need);
   a.N = N; a.p = d_attn; a.partial = (double*)d_workspace; a.radius = d_radius; a.mass = d_mass; a.r0 = (double)r0;
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(k_band_mass, dim3(max_blocks, a.n_parts, H), dim3(kBandThreads), 0, st, a);
+  hipLaunchKernelGGL(k_band_mass, dim3(n_blocks, H), dim3(kBandThreads), 0, st, a);
   if (litevar_status s = hip_check(hipGetLastError(), "band calibration mass launch")) return s;
   hipLaunchKernelGGL(k_band_pick, dim3(a.n_parts, H), dim3(kBandThreads), 0, st, a);
   return hip_check(hipGetLastError(), "band calibration pick launch");
