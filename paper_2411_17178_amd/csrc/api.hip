@@ -263,6 +263,8 @@ litevar_status make_attn_args(const litevar_plan* plan, int32_t B, int32_t H, in
   a.kv_len = plan->kv_len;
   a.hdr = (Header*)(plan->d_blob);
   a.spin_limit = plan->spin_limit > 0 ? plan->spin_limit : kDefaultSpinLimit;
+  a.n_groups_magic = (uint32_t)(((uint64_t)1 << 32) / (uint64_t)(plan->n_groups > 1 ? plan->n_groups : 1) - (plan->n_groups <= 1));
+  a.H_magic = (uint32_t)(((uint64_t)1 << 32) / (uint64_t)(H > 1 ? H : 1) - (H <= 1));
   return LITEVAR_OK;
 }
 

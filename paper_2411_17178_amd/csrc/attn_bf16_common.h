@@ -70,6 +70,15 @@ __device__ inline int checked_index([[maybe_unused]] Header* hdr, int value, [[m
   return value;
 }
 
+// x = q n + r for a divisor n whose magic = floor(2^32 / n) came with the kernel arguments
+// (n = 1: magic = 2^32 - 1): the estimate floor(x magic / 2^32) is the quotient or one below it
+// for every x < 2^32, so one correction step makes it exact.
+__device__ inline void divmod_by(uint32_t x, uint32_t n, uint32_t magic, int& q, int& r) {
+  uint32_t qq = __umulhi(x, magic), rr = x - qq * n;
+  if (rr >= n) { ++qq; rr -= n; }
+  q = (int)qq; r = (int)rr;
+}
+
 template <int N> __device__ inline void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   // gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt/lgkmcnt left at max

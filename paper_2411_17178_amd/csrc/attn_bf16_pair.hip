@@ -142,9 +142,11 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
 
   // workgroup i runs on XCD i % 8: all groups of one (batch, head) share one L2
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
-  const int bh = (seq / a.n_groups) * 8 + xcd, grp = seq % a.n_groups;
+  int me, grp, b, h;                      // me: which of the (batch, head) pairs of this XCD
+  divmod_by((uint32_t)seq, (uint32_t)a.n_groups, a.n_groups_magic, me, grp);
+  const int bh = me * 8 + xcd;
   if (bh >= a.B * a.H) return;
-  const int b = bh / a.H, h = bh % a.H;
+  divmod_by((uint32_t)bh, (uint32_t)a.H, a.H_magic, b, h);
   // Scalar round trip 1: the header words that say whether the plan may be used at all (a
   // zeroed, stale or half-built blob makes the launch a no-op) and, for plans with a radius
   // table per head, the head's group, whose copy of the work-list this workgroup walks.
@@ -378,12 +380,12 @@ void k_attn_bf16_pair(AttnArgs a, float c) {
   {
     const char* da = (const char*)(a.step_addr + (int64_t)first_step * 64);
     const char* ma = (const char*)(a.step_mask + (int64_t)first_step * 8);
-    const int n_share = (a.B * a.H + 7) / 8, me = seq / a.n_groups;    // workgroups of this group on this XCD
+    // one load per thread: workgroup `me` of this group on this XCD touches the lines
+    // [me T, me T + T), T = threads per workgroup (the workgroups beyond the plan's end all
+    // touch its last line; with more lines than workgroups x T the rest is touched in part
+    // only, which costs nothing but speed)
     const int lines_d = n_group_steps * 4, lines = lines_d + (n_group_steps + 1) / 2;
-    const int per = (lines + n_share - 1) / n_share;
-    // one load per thread; a slice longer than the workgroup is touched in part only, which
-    // costs nothing but speed
-    const int l = min(me * per + min(tid, per - 1), lines - 1);
+    const int l = min(me * (int)blockDim.x + tid, lines - 1);
     const char* src = l < lines_d ? da + (int64_t)l * 128 : ma + (int64_t)(l - lines_d) * 128;
     warm = *(const int*)src;
   }

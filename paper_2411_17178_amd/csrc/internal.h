@@ -64,6 +64,9 @@ struct AttnArgs {
   // 8-bit operands (Section 4): q, k, v then hold int8 codes (strides in codes) and these the
   // (scale, zero point) of every token row, packed [B][H][len]; nullptr for bf16 / fp32 operands
   const float2* q_sz; const float2* k_sz; const float2* v_sz;
+  // floor(2^32 / n) for n = n_groups and n = H: a workgroup's index is taken apart with two
+  // multiplications instead of two divisions by run-time values (see divmod_by in the kernels' header)
+  uint32_t n_groups_magic, H_magic;
 };
 
 // Checks what every attention entry point checks (plan, batch and head counts, softmax scale,
