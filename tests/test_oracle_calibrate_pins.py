@@ -1,6 +1,6 @@
 """Pins of the oracle's window calibration (paper Section 2: R_w = values inside the window
-over values of the part; the window grows from zero until R_w reaches R_0; R_0 = 1 falls back
-to full attention) against things other than itself: hand-placed mass at known distances,
+over values of the part; the radius is raised from 0 until that ratio is at least R_0; with
+R_0 = 1 the whole part is kept) against things other than itself: hand-placed mass at known distances,
 the closed form for a uniform same-scale part, an independent brute force, and invariants."""
 import numpy as np
 import pytest
